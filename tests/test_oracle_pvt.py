@@ -1,0 +1,321 @@
+"""Pins for the oracle's per-variable transformation (Sec. 2.3), its exact sums, the packed-size
+accounting against the paper's printed memory tables, and the optimizer forms."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import omc_oracle as orc
+from oracle.omc_oracle import Format, Opt
+from paper_2205_03494_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_memory_tables.txt")
+
+
+# ------------------------------------------------------------------ exact sums
+def test_exact_sum_matches_fsum():
+    rng = np.random.default_rng(1)
+    for trial in range(20):
+        n = int(rng.integers(1, 5000))
+        a = (rng.standard_normal(n) * np.exp2(rng.integers(-60, 60, size=n))).astype(np.float32)
+        b = (rng.standard_normal(n) * np.exp2(rng.integers(-60, 60, size=n))).astype(np.float32)
+        terms = a.astype(np.float64) * b.astype(np.float64)          # exact products
+        assert orc.exact_sum(terms) == math.fsum(terms)
+        assert orc.exact_sum(a.astype(np.float64)) == math.fsum(a.astype(np.float64))
+    # cancellation that defeats naive summation
+    x = np.array([1e30, 1.0, -1e30, 2.0 ** -100, -1.0], dtype=np.float32).astype(np.float64)
+    assert orc.exact_sum(x) == math.fsum(x) == float(np.float32(2.0 ** -100))
+    # ties in the final rounding: 2^53 + 1 is a tie -> even
+    assert orc.exact_sum(np.array([2.0 ** 53, 1.0])) == 2.0 ** 53
+    assert orc.exact_sum(np.array([2.0 ** 53, 1.0, 2.0 ** -30])) == 2.0 ** 53 + 2
+    assert orc.exact_sum(np.array([2.0 ** 53 + 2, 1.0])) == 2.0 ** 53 + 4
+    assert orc.exact_sum(np.array([-(2.0 ** 53), -1.0, -(2.0 ** -30)])) == -(2.0 ** 53 + 2)
+    # smallest terms the fit can see: products of fp32 subnormals
+    t = np.float64(np.float32(1e-45)) ** 2
+    assert orc.exact_sum(np.array([t, t, t])) == 3 * t
+
+
+# ------------------------------------------------------------------ P5: normal equations
+@pytest.mark.parametrize("fmt", [Format(4, 3), Format(3, 7), Format(5, 10), Format(2, 3)])
+def test_fit_satisfies_normal_equations_and_matches_polyfit(fmt):
+    V = synth.normal_f32(20000, 0.03, 17) + np.float32(0.004)
+    Vt = orc.decode(orc.encode(V, fmt), fmt)
+    s, b = orc.pvt_fit(V, Vt)
+    v, t = V.astype(np.float64), Vt.astype(np.float64)
+    r = v - (float(s) * t + float(b))
+    scale = np.sum(np.abs(v))
+    # stationarity of ||s Vt + b 1 - V||_2 in b and in s (fp32 storage of s, b limits this to ~1e-7)
+    assert abs(np.sum(r)) <= 2e-7 * scale
+    assert abs(np.sum(r * t)) <= 2e-7 * np.sum(np.abs(v * t))
+    # not worse than the identity transform, which is feasible
+    assert np.linalg.norm(r) <= np.linalg.norm(v - t) * (1 + 1e-9)
+    # textbook simple linear regression of V on Vt
+    s_ref, b_ref = np.polyfit(t, v, 1)
+    assert abs(float(s) - s_ref) <= 1e-6 * abs(s_ref)
+    assert abs(float(b) - b_ref) <= 1e-6 * abs(b_ref) + 1e-9
+    sol = np.linalg.lstsq(np.stack([t, np.ones_like(t)], 1), v, rcond=None)[0]
+    assert abs(float(s) - sol[0]) <= 1e-6 * abs(sol[0])
+    assert abs(float(b) - sol[1]) <= 1e-6 * abs(sol[1]) + 1e-9
+
+
+def test_fit_is_exactly_rounded_formula():
+    # the four sums exactly rounded, then the closed form in double, one rounding to fp32
+    V = synth.normal_f32(5000, 0.05, 3)
+    Vt = orc.decode(orc.encode(V, Format(3, 7)), Format(3, 7))
+    v, t = V.astype(np.float64), Vt.astype(np.float64)
+    SV, ST, SVT, STT = math.fsum(v), math.fsum(t), math.fsum(v * t), math.fsum(t * t)
+    n = float(V.size)
+    s = (n * SVT - SV * ST) / (n * STT - ST * ST)
+    b = (SV - s * ST) / n
+    got = orc.pvt_fit(V, Vt)
+    assert got[0] == np.float32(s) and got[1] == np.float32(b)
+
+
+def test_printed_formula_is_not_the_minimiser():
+    # The denominator printed in Sec. 2.3 uses SUM V^2 where the least-squares solution has
+    # SUM Vt^2, and the printed b multiplies SUM V by n; neither satisfies the normal equations.
+    V = synth.normal_f32(4000, 0.05, 9) + np.float32(0.01)
+    Vt = orc.decode(orc.encode(V, Format(2, 3)), Format(2, 3))
+    v, t = V.astype(np.float64), Vt.astype(np.float64)
+    n = float(V.size)
+    s_pr = (n * np.sum(v * t) - v.sum() * t.sum()) / (n * np.sum(v * v) - t.sum() ** 2)
+    b_pr = (n * v.sum() - s_pr * t.sum()) / n
+    s, b = orc.pvt_fit(V, Vt)
+    err = np.linalg.norm(v - (float(s) * t + float(b)))
+    err_pr = np.linalg.norm(v - (s_pr * t + b_pr))
+    err_pr_b_fixed = np.linalg.norm(v - (s_pr * t + (v.sum() - s_pr * t.sum()) / n))
+    assert err < err_pr_b_fixed < err_pr
+
+
+# ------------------------------------------------------------------ P6: special cases
+def test_fit_special_cases():
+    fmt = Format(4, 3)
+    # already representable -> Vt == V -> s = 1, b = 0 exactly
+    V = orc.decode(np.arange(1, 120, dtype=np.uint32), fmt)
+    packed, sb = orc.compress(V, fmt)
+    assert sb[0] == 1.0 and sb[1] == 0.0
+    assert np.array_equal(orc.decompress(packed, V.size, fmt, sb), V)
+    # constant variable -> degenerate case -> s = 1 (Sec. 2.3), b = V0 - Vt0
+    V = np.full(1000, 0.3, dtype=np.float32)
+    packed, sb = orc.compress(V, fmt)
+    t0 = orc.decode(orc.encode(V[:1], fmt), fmt)[0]
+    assert sb[0] == 1.0
+    assert sb[1] == np.float32(np.float64(np.float32(0.3)) - np.float64(t0))
+    # all Vt equal while V varies (everything rounds to zero): still degenerate
+    V = synth.normal_f32(1000, 1e-6, 4)
+    packed, sb = orc.compress(V, fmt)
+    assert sb[0] == 1.0 and sb[1] == np.float32(math.fsum(V.astype(np.float64)) / 1000)
+    # +0 and -0 together count as equal
+    s, b = orc.pvt_fit(np.array([1e-7, -1e-7], np.float32), np.array([0.0, -0.0], np.float32))
+    assert s == 1.0 and b == 0.0
+    # n = 1
+    s, b = orc.pvt_fit(np.array([0.3], np.float32), np.array([0.25], np.float32))
+    assert s == 1.0 and b == np.float32(np.float64(np.float32(0.3)) - 0.25)
+    # a constructed affine pair: V = 0.5 Vt + 0.5
+    Vt = np.arange(-8, 9, dtype=np.float32)
+    s, b = orc.pvt_fit(0.5 * Vt + 0.5, Vt)
+    assert s == 0.5 and b == 0.5
+    # without the transformation
+    packed, sb = orc.compress(synth.normal_f32(100, 0.1, 1), fmt, use_pvt=False)
+    assert sb[0] == 1.0 and sb[1] == 0.0
+    # non-finite input poisons (s, b)                                    [reading; unpinned]
+    V = synth.normal_f32(100, 0.1, 1)
+    V[7] = np.inf
+    _, sb = orc.compress(V, fmt)
+    assert np.isnan(sb[0]) and np.isnan(sb[1])
+
+
+def test_decompress_applies_two_roundings():
+    fmt = Format(3, 7)
+    V = synth.normal_f32(3000, 0.2, 8)
+    packed, sb = orc.compress(V, fmt)
+    t = orc.decode(orc.unpack(packed, V.size, fmt.bits), fmt)
+    want = (sb[0] * t) + sb[1]                         # numpy float32: one rounding per op
+    assert want.dtype == np.float32
+    assert np.array_equal(orc.decompress(packed, V.size, fmt, sb), want)
+    assert np.array_equal(orc.decompress(packed, V.size, fmt, None), t)
+
+
+# ------------------------------------------------------------------ P7: memory model vs Tables 1, 2
+def _golden_rows():
+    rows = []
+    with open(GOLDEN) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            rows.append(line.split())
+    return rows
+
+
+def test_packed_size_model_reproduces_paper_memory_ratios():
+    specs = synth.conformer_varset(512, 17, 2048, 32)
+    n_total = sum(s.n for s in specs)
+    n_mat = sum(s.n for s in specs if s.is_matrix)
+    assert n_mat / n_total > 0.995                     # Sec. 2.4: matrices dominate (paper: 99.8 %)
+    for tab, name, bits, fp32_mb, omc_mb, pct in _golden_rows():
+        bits = int(bits)
+        if tab == "avgbits":
+            assert abs((0.9 * bits + 0.1 * 32) - float(pct)) < 1e-9
+            continue
+        ratios = []
+        for seed in range(8):
+            mask = synth.ppq_mask(specs, 0.9, seed)
+            lay = synth.make_layout(specs, mask, lambda n: orc.packed_bytes(n, bits))
+            ratios.append((lay.arena_bytes + 8 * int(mask.sum())) / (4.0 * n_total))
+        ratio = float(np.mean(ratios))
+        closed = (n_mat / n_total) * (0.9 * bits / 32 + 0.1) + (1 - n_mat / n_total)
+        assert abs(ratio - closed) < 0.01
+        assert abs(ratio - float(omc_mb) / float(fp32_mb)) < 0.015
+        if name != "S1E2M3":                           # its printed 29 % disagrees with its own MB
+            assert abs(100 * ratio - float(pct)) < 1.5
+
+
+# ------------------------------------------------------------------ optimizer forms
+def _np_update(kind, w, g, m, v, o: Opt):
+    f = np.float32
+    if kind == 0:
+        return w - f(o.lr) * g, m, v
+    if kind == 1:
+        m = f(o.momentum) * m + g
+        return w - f(o.lr) * m, m, v
+    m = f(o.beta1) * m + f(1.0 - o.beta1) * g
+    v = f(o.beta2) * v + (f(1.0 - o.beta2) * g) * g
+    mhat = m / f(1.0 - o.beta1 ** o.t)
+    vhat = v / f(1.0 - o.beta2 ** o.t)
+    return w - (f(o.lr) * mhat) / (np.sqrt(vhat) + f(o.eps)), m, v
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2])
+def test_update_forms_bit_exact_against_numpy_float32(kind):
+    n = 5000
+    w = synth.normal_f32(n, 0.05, 1)
+    m = np.zeros(n, np.float32)
+    v = np.zeros(n, np.float32)
+    wo, mo, vo = w.copy(), m.copy(), v.copy()
+    for t in range(1, 6):
+        g = synth.normal_f32(n, 1e-3, 100 + t)
+        o = Opt(kind=kind, lr=0.01 if kind < 2 else 1e-3, t=t)
+        w, m, v = _np_update(kind, w, g, m, v, o)
+        orc.step_fp32(wo, g, mo if kind >= 1 else None, vo if kind == 2 else None, o)
+        assert np.array_equal(w, wo)
+        assert np.array_equal(m, mo) and np.array_equal(v, vo)
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2])
+def test_update_forms_agree_with_torch_optim(kind):
+    n = 4000
+    w0 = synth.normal_f32(n, 0.05, 2)
+    p = torch.nn.Parameter(torch.from_numpy(w0.copy()))
+    if kind == 0:
+        opt = torch.optim.SGD([p], lr=0.01)
+    elif kind == 1:
+        opt = torch.optim.SGD([p], lr=0.01, momentum=0.9)
+    else:
+        opt = torch.optim.Adam([p], lr=1e-3, betas=(0.9, 0.999), eps=1e-8)
+    w = w0.copy()
+    m = np.zeros(n, np.float32)
+    v = np.zeros(n, np.float32)
+    for t in range(1, 8):
+        g = synth.normal_f32(n, 1e-3, 200 + t)
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+        orc.step_fp32(w, g, m if kind >= 1 else None, v if kind == 2 else None,
+                      Opt(kind=kind, lr=0.01 if kind < 2 else 1e-3, t=t))
+    ref = p.detach().numpy()
+    assert np.allclose(w, ref, rtol=2e-5, atol=1e-7)    # torch groups the operations differently
+
+
+# ------------------------------------------------------------------ the cycle (Sec. 2.1)
+@pytest.mark.parametrize("kind", [0, 1, 2])
+def test_step_is_decompress_update_compress(kind):
+    fmt = Format(4, 3)
+    n = 2048 + 77
+    V = synth.normal_f32(n, 0.02, 0)
+    packed, sb = orc.compress(V, fmt)
+    m = np.zeros(n, np.float32)
+    v = np.zeros(n, np.float32)
+    p2, sb2, m2, v2 = packed.copy(), sb.copy(), m.copy(), v.copy()
+    for t in range(1, 4):
+        g = synth.normal_f32(n, 0.05, 1000 + t)
+        o = Opt(kind=kind, lr=0.01, t=t)
+        orc.step_quantized(p2, n, fmt, sb2, g, m2 if kind >= 1 else None,
+                           v2 if kind == 2 else None, o)
+        W = orc.decompress(packed, n, fmt, sb)
+        orc.step_fp32(W, g, m if kind >= 1 else None, v if kind == 2 else None, o)
+        packed, sb = orc.compress(W, fmt)
+        assert np.array_equal(packed, p2) and np.array_equal(sb, sb2)
+        assert np.array_equal(m, m2) and np.array_equal(v, v2)
+
+
+def test_varset_step_equals_per_variable_steps_and_threads_do_not_matter():
+    fmt = Format(3, 7)
+    specs = synth.conformer_varset(32, 2, 64, 4, frontend=False)
+    mask = synth.ppq_mask(specs, 0.5, 3)
+    lay = synth.make_layout(specs, mask, lambda n: orc.packed_bytes(n, fmt.bits))
+    vals = synth.init_values(lay, 5)
+    arena = np.zeros(lay.arena_bytes, np.uint8)
+    sbt = np.zeros((len(specs), 2), np.float32)
+    sbt[:, 0] = 1
+    for i, s in enumerate(specs):
+        a, d = int(lay.aux_offset[i]), int(lay.data_offset[i])
+        x = vals[a:a + s.n]
+        if mask[i]:
+            p, sb = orc.compress(x, fmt)
+            arena[d:d + p.size] = p
+            sbt[i] = sb
+        else:
+            arena[d:d + 4 * s.n] = x.view(np.uint8)
+    table = orc.make_var_table(dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]),
+                                    n=s.n, fmt=fmt, quantized=bool(mask[i])) for i, s in enumerate(specs))
+    runs = []
+    for threads in (1, 4):
+        ar, sb_ = arena.copy(), sbt.copy()
+        m = np.zeros(lay.aux_elems, np.float32)
+        v = np.zeros(lay.aux_elems, np.float32)
+        for t in range(1, 3):
+            g = synth.gradients(lay, 0.02, 50 + t)
+            orc.step_varset(ar, table, sb_, g, m, v, Opt(kind=2, lr=1e-3, t=t), threads=threads)
+        runs.append((ar, sb_, m, v))
+    for a, b in zip(runs[0], runs[1]):
+        assert np.array_equal(a, b)
+    # against per-variable calls
+    ar, sb_ = arena.copy(), sbt.copy()
+    m = np.zeros(lay.aux_elems, np.float32)
+    v = np.zeros(lay.aux_elems, np.float32)
+    for t in range(1, 3):
+        g = synth.gradients(lay, 0.02, 50 + t)
+        o = Opt(kind=2, lr=1e-3, t=t)
+        for i, s in enumerate(specs):
+            a, d = int(lay.aux_offset[i]), int(lay.data_offset[i])
+            if mask[i]:
+                nb = orc.packed_bytes(s.n, fmt.bits)
+                p = ar[d:d + nb].copy()
+                sb = sb_[i].copy()
+                orc.step_quantized(p, s.n, fmt, sb, g[a:a + s.n], m[a:a + s.n], v[a:a + s.n], o)
+                ar[d:d + nb] = p
+                sb_[i] = sb
+            else:
+                W = ar[d:d + 4 * s.n].view(np.float32).copy()
+                orc.step_fp32(W, g[a:a + s.n], m[a:a + s.n], v[a:a + s.n], o)
+                ar[d:d + 4 * s.n] = W.view(np.uint8)
+    assert np.array_equal(ar, runs[0][0]) and np.array_equal(sb_, runs[0][1])
+
+
+def test_gemm_oracle_against_numpy_matmul():
+    fmt = Format(4, 3)
+    M, N, K = 24, 40, 56
+    A = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 1))
+    W = synth.normal_f32(K * N, 1 / np.sqrt(K), 2)
+    packed, sb = orc.compress(W, fmt)
+    C = orc.dequant_gemm(A, packed, fmt, sb, M, N, K)
+    Af = (A.astype(np.uint32) << 16).view(np.float32).astype(np.float64).reshape(M, K)
+    Wb = orc.decompress(packed, K * N, fmt, sb).astype(np.float64).reshape(K, N)
+    assert np.allclose(C, Af @ Wb, rtol=1e-12, atol=1e-12)
+    Cs = orc.dequant_gemm(A, packed, fmt, sb, M, N, K, rows=(5, 9))
+    assert np.array_equal(Cs, C[5:9])
+    # bf16 rounding of the activations against torch
+    x = synth.normal_f32(10000, 3.0, 4)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(synth.to_bf16_bits(x), want)
