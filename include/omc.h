@@ -1,0 +1,213 @@
+/*
+ * omc.h -- C ABI of libomc: the per-iteration hot path of Online Model Compression (OMC,
+ * arxiv 2205.03494) on one AMD MI355X (gfx950).
+ *
+ * The method keeps model variables in a reduced-bitwidth floating-point format, decompresses
+ * them when an operation needs them, and recompresses them after every training iteration
+ * (paper Sec. 2.1).  This library is that cycle:
+ *
+ *   omc_compress                 fp32 variable -> packed codes + per-variable (s, b)   (Sec. 2.2, 2.3)
+ *   omc_decompress               packed codes + (s, b) -> fp32                           (Sec. 2.1, 2.3)
+ *   omc_step_update_recompress   one training iteration over a whole variable set:
+ *                                decompress -> parameter update -> recompress, fused     (Sec. 2.1, backward path)
+ *   omc_dequant_gemm             C = A * decompress(W), weights expanded on chip          (Sec. 2.1, forward path)
+ *
+ * Conventions that hold for every entry point
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     process memory.  The library allocates nothing, frees nothing and keeps no pointer after
+ *     a call returns.  There is no global state; calls on different streams may overlap as long
+ *     as their buffers do not.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *     on it and the call returns without synchronising.
+ *   - Arguments are validated on the host before anything is enqueued: a status other than
+ *     OMC_OK means that no kernel was launched and no buffer was touched.
+ *   - Device buffers of packed codes, fp32 values, gradients and optimizer state must be
+ *     16-byte aligned (OMC_ERR_ALIGN otherwise).
+ *
+ * Format (Sec. 2.2; notation SxEyMz of Sec. 3.1, x = 1).  A code has B = 1 + E + M bits,
+ * most significant first [sign | e : E bits | m : M bits].
+ *     e == 0 :  value = (-1)^sign * 2^(1-bias)   * (m / 2^M)          zero and subnormals
+ *     e >= 1 :  value = (-1)^sign * 2^(e-bias)   * (1 + m / 2^M)      every other exponent, the top one included
+ * There are no Inf/NaN codes.  bias defaults to 2^(E-1)-1.  Conversion from fp32 rounds to the
+ * nearest value, ties to the even integer significand, and saturates at the largest magnitude.
+ * Codes whose value would exceed the largest finite fp32 (possible only when 2^E-1-bias > 127,
+ * i.e. E = 8) are never produced and must not be fed to the decoder.  Non-finite inputs encode
+ * to the saturated code of their sign and make the variable's (s, b) NaN.
+ *
+ * Packing.  A variable of n elements is a dense little-endian bit stream: element k occupies
+ * stream bits [k*B, (k+1)*B), least significant code bit first; stream bit i is bit (i mod 32) of
+ * the little-endian 32-bit word i/32.  The buffer is omc_packed_bytes(f, n) long: the stream padded
+ * with zero bits to a multiple of 16 bytes.  This is also the transport form of a variable.
+ *
+ * Per-variable transformation (Sec. 2.3).  The decompressed value of element k is
+ *     Vbar_k = fl32( fl32(s * Vtilde_k) + b )
+ * with Vtilde_k the value of its code and (s, b) two fp32 numbers per variable.  At compression
+ * (s, b) minimise || s*Vtilde + b*1 - V ||_2 over the n elements:
+ *     s = (n SUM V Vt - SUM V SUM Vt) / (n SUM Vt^2 - (SUM Vt)^2),   b = (SUM V - s SUM Vt) / n,
+ * evaluated in fp64 and stored as fp32; s = 1 when all Vtilde_k are equal (the degenerate case).
+ * The sums are accumulated in fp64 in a fixed order, so results are bit-identical from run to run.
+ */
+#ifndef OMC_H
+#define OMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OMC_OK = 0,
+    OMC_ERR_NULL = 1,      /* a required pointer is NULL */
+    OMC_ERR_FORMAT = 2,    /* exp_bits / man_bits / bias outside the supported range */
+    OMC_ERR_SIZE = 3,      /* n == 0, a dimension is 0 or not a supported multiple, offsets overlap or run past a buffer */
+    OMC_ERR_ALIGN = 4,     /* a device pointer or an offset is not aligned as required */
+    OMC_ERR_WORKSPACE = 5, /* workspace missing or smaller than the queried size */
+    OMC_ERR_OPT = 6,       /* unknown optimizer kind, or a state buffer it needs is NULL */
+    OMC_ERR_DEVICE = 7,    /* the HIP runtime refused a launch */
+    OMC_ERR_PLAN = 8       /* the plan blob is corrupt or does not belong to this call */
+} omc_status;
+
+/* SxEyMz with x = 1 (Sec. 2.2).  1 <= exp_bits <= 8, 0 <= man_bits <= 23,
+ * exp_bias in [0, 127] or OMC_BIAS_DEFAULT. */
+#define OMC_BIAS_DEFAULT (-1)
+typedef struct {
+    uint8_t exp_bits;
+    uint8_t man_bits;
+    int16_t exp_bias;
+} omc_format;
+
+/* One variable of a set (Sec. 2.4, 2.5: weight matrices may be quantized, everything else and
+ * the matrices not selected by partial parameter quantization stay fp32). */
+#define OMC_VAR_QUANTIZED 1u /* packed codes at data_offset; otherwise n fp32 values */
+#define OMC_VAR_NO_PVT 2u    /* keep (s, b) = (1, 0): quantization without the transformation */
+typedef struct {
+    uint64_t data_offset; /* bytes into the arena; multiple of 16 */
+    uint64_t aux_offset;  /* fp32 elements into grads / state0 / state1; multiple of 4 */
+    uint64_t n;           /* elements, >= 1 */
+    omc_format fmt;       /* ignored unless OMC_VAR_QUANTIZED */
+    uint32_t flags;       /* OMC_VAR_* */
+} omc_var;
+
+/* The parameter update applied to the decompressed values (Sec. 2.1: "applies the gradients to
+ * update them"; the paper does not name the client optimizer).  Every fp32 operation is rounded
+ * on its own, in the order written:
+ *   OMC_SGD       V' = V - fl(lr*g)
+ *   OMC_MOMENTUM  m' = fl(fl(momentum*m) + g);                       V' = V - fl(lr*m')         state0 = m
+ *   OMC_ADAM      m' = fl(fl(beta1*m) + fl(one_minus_beta1*g))
+ *                 v' = fl(fl(beta2*v) + fl(fl(one_minus_beta2*g)*g))
+ *                 V' = V - fl( fl(lr*fl(m'/bias_corr1)) / fl(fl(sqrt(fl(v'/bias_corr2))) + eps) )
+ *                                                                         state0 = m, state1 = v
+ * one_minus_beta* = fp32(1 - beta*) and bias_corr* = fp32(1 - beta*^t) are computed by the caller
+ * in fp64 and rounded once. */
+typedef enum { OMC_SGD = 0, OMC_MOMENTUM = 1, OMC_ADAM = 2 } omc_opt_kind;
+typedef struct {
+    int32_t kind; /* omc_opt_kind */
+    float lr;
+    float momentum;
+    float beta1, beta2, eps;
+    float one_minus_beta1, one_minus_beta2;
+    float bias_corr1, bias_corr2;
+} omc_opt;
+
+/* ---- host-only helpers (no device work) ------------------------------------------------- */
+
+const char *omc_status_string(omc_status s);
+
+/* OMC_OK or OMC_ERR_FORMAT. */
+omc_status omc_format_validate(omc_format f);
+
+/* Bits per code, 1 + E + M; 0 for an invalid format. */
+uint32_t omc_format_bits(omc_format f);
+
+/* Largest representable magnitude (exact in fp32); 0 for an invalid format. */
+float omc_format_max(omc_format f);
+
+/* Bytes of the packed buffer of n elements: ceil(n*B/8) rounded up to a multiple of 16;
+ * 0 for an invalid format or n == 0. */
+size_t omc_packed_bytes(omc_format f, uint64_t n);
+
+/* Workspace (device bytes) that omc_compress needs for n elements. */
+size_t omc_compress_workspace_bytes(uint64_t n);
+
+/* ---- single variable --------------------------------------------------------------------- */
+
+/* Compress n fp32 values (Sec. 2.2 quantization, Sec. 2.3 fit).
+ *   v        device, n floats, read only
+ *   codes    device, omc_packed_bytes(f, n) bytes, written completely (padding bits zero)
+ *   sb       device, 2 floats: receives s, b ((1, 0) when use_pvt == 0)
+ *   ws       device workspace of at least omc_compress_workspace_bytes(n) bytes, 16-byte aligned;
+ *            contents undefined afterwards
+ * v and codes must not overlap. */
+omc_status omc_compress(const float *v, uint64_t n, omc_format f, int use_pvt, void *codes,
+                        float *sb, void *ws, size_t ws_bytes, void *stream);
+
+/* Decompress n elements: out_k = fl32(fl32(s*Vtilde_k) + b)  (Sec. 2.1, 2.3).
+ *   codes    device, omc_packed_bytes(f, n) bytes, read only
+ *   sb       device, 2 floats (s, b), or NULL for s = 1, b = 0 (then out_k = Vtilde_k exactly)
+ *   out      device, n floats */
+omc_status omc_decompress(const void *codes, uint64_t n, omc_format f, const float *sb, float *out,
+                          void *stream);
+
+/* ---- variable set: the per-iteration cycle ---------------------------------------------- */
+
+/* A plan is a position-independent blob that describes a variable set to the kernels: the
+ * validated variable table, derived format constants and the list of work items.  It is built on
+ * the host once per variable set (and again whenever the set of quantized variables changes,
+ * Sec. 2.5); the caller copies the same bytes to device memory and passes both copies to every
+ * step.
+ *
+ * omc_plan_bytes: size of the blob, 0 if the table is invalid (see omc_plan_build for the reason).
+ * omc_plan_build: validates the table (formats, n >= 1, alignment of offsets, no two variables
+ *   overlapping in the arena or in the aux range) and fills plan_host[0 .. plan_bytes).
+ * omc_plan_workspace_bytes / omc_plan_arena_bytes / omc_plan_aux_elems: device workspace a step
+ *   needs, and the extent of arena / aux that the plan addresses (0 for a corrupt blob). */
+size_t omc_plan_bytes(const omc_var *vars_host, uint32_t nvars);
+omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_host, size_t plan_bytes);
+size_t omc_plan_workspace_bytes(const void *plan_host);
+size_t omc_plan_arena_bytes(const void *plan_host);
+uint64_t omc_plan_aux_elems(const void *plan_host);
+
+/* One training iteration over the whole set (Sec. 2.1 backward path, with Sec. 2.4 / 2.5 deciding
+ * which variables are packed).  For every quantized variable: unpack, decode, apply (s, b), apply
+ * the update with the variable's gradient and optimizer state, round to the format, refit (s, b)
+ * against the updated full-precision values, pack.  The decompressed copy lives in registers only.
+ * For every fp32 variable: the update alone.  Everything is in place.
+ *   arena        device, arena_bytes bytes: packed codes and fp32 values at the plan's data offsets
+ *   plan_host    host copy of the plan blob;  plan_dev: device copy of the same bytes
+ *   sb_table     device, 2*nvars floats: (s, b) per variable, read and rewritten for quantized
+ *                variables, untouched for the others
+ *   grads        device, aux_elems floats, read only
+ *   state0/1     device, aux_elems floats each; state0 needed for OMC_MOMENTUM and OMC_ADAM,
+ *                state1 for OMC_ADAM; otherwise ignored (may be NULL)
+ *   ws           device workspace, at least omc_plan_workspace_bytes(plan_host), 16-byte aligned
+ * arena_bytes and aux_elems must be at least what the plan addresses (OMC_ERR_SIZE otherwise). */
+omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const void *plan_host,
+                                      const void *plan_dev, float *sb_table, const float *grads,
+                                      float *state0, float *state1, uint64_t aux_elems,
+                                      const omc_opt *opt, void *ws, size_t ws_bytes, void *stream);
+
+/* ---- forward path ------------------------------------------------------------------------ */
+
+/* Workspace (device bytes) for omc_dequant_gemm with M activation rows. */
+size_t omc_dequant_gemm_workspace_bytes(uint32_t M);
+
+/* C[M x N] = A[M x K] * Wbar[K x N], Wbar = decompress(codes, sb)  (Sec. 2.1 forward path: the
+ * layer's parameters are decompressed on the fly and consumed at once; here they are expanded
+ * inside the kernel and never reach memory as fp32).
+ *   A        device, M*K bfloat16 bit patterns, row-major
+ *   codes    device, packed K*N-element variable, element index k*N + j
+ *   sb       device, 2 floats, or NULL for (1, 0)
+ *   C        device, M*N floats, row-major; fp32 accumulation
+ *   ws       device workspace of omc_dequant_gemm_workspace_bytes(M) bytes
+ * Uses  A*(s*Vt + b*1) = s*(A*Vt) + b*rowsum(A)*1^T.  Requires man_bits <= 7 (every Vtilde is then
+ * exactly a bfloat16), M % 256 == 0, N % 256 == 0, K % 64 == 0 (OMC_ERR_FORMAT / OMC_ERR_SIZE). */
+omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, const float *sb,
+                            float *C, uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes,
+                            void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMC_H */

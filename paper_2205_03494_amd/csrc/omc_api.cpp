@@ -1,0 +1,335 @@
+// Host side of libomc: format constants, plan construction, argument validation, and the
+// extern "C" entry points.  No device code here; launches live in the .hip files.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "omc_internal.h"
+
+namespace omc {
+
+static int resolved_bias(omc_format f) {
+    return f.exp_bias == OMC_BIAS_DEFAULT ? (1 << (f.exp_bits - 1)) - 1 : f.exp_bias;
+}
+
+static bool format_ok(omc_format f) {
+    if (f.exp_bits < 1 || f.exp_bits > 8) return false;
+    if (f.man_bits > 23) return false;
+    if (f.exp_bias != OMC_BIAS_DEFAULT && (f.exp_bias < 0 || f.exp_bias > 127)) return false;
+    return true;
+}
+
+// largest exponent field whose binade lies inside finite fp32
+static int top_field(omc_format f) {
+    const int bias = resolved_bias(f);
+    int top = (1 << f.exp_bits) - 1;
+    if (top - bias > 127) top = 127 + bias;
+    return top;
+}
+
+bool make_fmt_params(omc_format f, FmtParams *out) {
+    if (!format_ok(f)) return false;
+    const int E = f.exp_bits, M = f.man_bits, bias = resolved_bias(f);
+    FmtParams p{};
+    p.bits = 1 + E + M;
+    p.exp_bits = E;
+    p.man_bits = M;
+    p.bias = bias;
+    p.sh = 23 - M;
+    p.asr = 8 - E;
+    p.keep_mask = 0x80000000u | (((1u << (E + M)) - 1u) << p.sh);
+    p.min_norm_bits = static_cast<uint32_t>(127 + 1 - bias) << 23;
+    p.magic_off = static_cast<uint32_t>(23 - M) << 23;
+    const int top_exp = top_field(f) - bias;
+    p.wide = (M == 23 || top_exp + 23 - M > 127) ? 1u : 0u;
+    p.exp_adj = 127 + M;
+    p.dec_scale = std::ldexp(1.0f, 127 - bias);
+    p.enc_scale = std::ldexp(1.0f, bias - 127);
+    p.maxval = static_cast<float>(std::ldexp(2.0 - std::ldexp(1.0, -M), top_exp));
+    *out = p;
+    return true;
+}
+
+static size_t packed_bytes_u(uint32_t bits, uint64_t n) {
+    const uint64_t total_bits = n * bits;
+    const uint64_t bytes = (total_bits + 7) / 8;
+    return static_cast<size_t>((bytes + 15) / 16 * 16);
+}
+
+constexpr uint64_t kMaxElems = 1ull << 36;
+
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+const PlanHeader *plan_check(const void *plan_host) {
+    if (!plan_host) return nullptr;
+    const PlanHeader *ph = static_cast<const PlanHeader *>(plan_host);
+    if (ph->magic != kPlanMagic || ph->version != kPlanVersion) return nullptr;
+    if (ph->var_off != sizeof(PlanHeader)) return nullptr;
+    if (ph->item_off != ph->var_off + static_cast<uint64_t>(ph->nvars) * sizeof(PlanVar)) return nullptr;
+    if (ph->group_off != ph->item_off + static_cast<uint64_t>(ph->nitems) * sizeof(PlanItem)) return nullptr;
+    if (ph->total_bytes != align_up(ph->group_off + static_cast<uint64_t>(ph->ngroups) * sizeof(PlanGroup), 16))
+        return nullptr;
+    if (ph->ws_bytes != std::max<uint64_t>(16, static_cast<uint64_t>(ph->nitems) * sizeof(Partial))) return nullptr;
+    return ph;
+}
+
+struct PlanLayout {
+    uint64_t var_off, item_off, group_off, total;
+    uint32_t nitems, ngroups, nquant;
+    std::vector<uint32_t> group_bits;  // ascending code widths present, then 0 if fp32 variables exist
+};
+
+// Validates the table; returns OMC_OK and the layout, or the first error.
+static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *pl) {
+    if (!vars) return OMC_ERR_NULL;
+    if (nvars == 0) return OMC_ERR_SIZE;
+    bool present[33] = {false};
+    bool any_fp32 = false;
+    uint64_t nitems = 0;
+    uint32_t nquant = 0;
+    struct Span { uint64_t lo, hi; };
+    std::vector<Span> data(nvars), aux(nvars);
+    for (uint32_t i = 0; i < nvars; ++i) {
+        const omc_var &v = vars[i];
+        if (v.n == 0 || v.n > kMaxElems) return OMC_ERR_SIZE;
+        if (v.data_offset % 16 != 0 || v.aux_offset % 4 != 0) return OMC_ERR_ALIGN;
+        if (v.flags & ~(OMC_VAR_QUANTIZED | OMC_VAR_NO_PVT)) return OMC_ERR_SIZE;
+        uint64_t bytes;
+        if (v.flags & OMC_VAR_QUANTIZED) {
+            if (!format_ok(v.fmt)) return OMC_ERR_FORMAT;
+            const uint32_t bits = 1u + v.fmt.exp_bits + v.fmt.man_bits;
+            present[bits] = true;
+            bytes = packed_bytes_u(bits, v.n);
+            ++nquant;
+        } else {
+            any_fp32 = true;
+            bytes = 4 * v.n;
+        }
+        data[i] = {v.data_offset, v.data_offset + bytes};
+        aux[i] = {v.aux_offset, v.aux_offset + v.n};
+        nitems += (v.n + kChunkElems - 1) / kChunkElems;
+    }
+    if (nitems > 0x7fffffffull) return OMC_ERR_SIZE;
+    auto overlaps = [](std::vector<Span> s) {
+        std::sort(s.begin(), s.end(), [](const Span &a, const Span &b) { return a.lo < b.lo; });
+        for (size_t i = 1; i < s.size(); ++i)
+            if (s[i].lo < s[i - 1].hi) return true;
+        return false;
+    };
+    if (overlaps(data) || overlaps(aux)) return OMC_ERR_SIZE;
+    pl->group_bits.clear();
+    for (uint32_t b = 2; b <= 32; ++b)
+        if (present[b]) pl->group_bits.push_back(b);
+    if (any_fp32) pl->group_bits.push_back(0);
+    pl->nitems = static_cast<uint32_t>(nitems);
+    pl->ngroups = static_cast<uint32_t>(pl->group_bits.size());
+    pl->nquant = nquant;
+    pl->var_off = sizeof(PlanHeader);
+    pl->item_off = pl->var_off + static_cast<uint64_t>(nvars) * sizeof(PlanVar);
+    pl->group_off = pl->item_off + nitems * sizeof(PlanItem);
+    pl->total = align_up(pl->group_off + static_cast<uint64_t>(pl->ngroups) * sizeof(PlanGroup), 16);
+    return OMC_OK;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace omc
+
+using namespace omc;
+
+extern "C" {
+
+const char *omc_status_string(omc_status s) {
+    switch (s) {
+        case OMC_OK: return "ok";
+        case OMC_ERR_NULL: return "null pointer";
+        case OMC_ERR_FORMAT: return "unsupported format";
+        case OMC_ERR_SIZE: return "bad size or offsets";
+        case OMC_ERR_ALIGN: return "misaligned pointer or offset";
+        case OMC_ERR_WORKSPACE: return "workspace missing or too small";
+        case OMC_ERR_OPT: return "bad optimizer or missing state";
+        case OMC_ERR_DEVICE: return "HIP launch failed";
+        case OMC_ERR_PLAN: return "corrupt or foreign plan";
+    }
+    return "unknown status";
+}
+
+omc_status omc_format_validate(omc_format f) { return format_ok(f) ? OMC_OK : OMC_ERR_FORMAT; }
+
+uint32_t omc_format_bits(omc_format f) { return format_ok(f) ? 1u + f.exp_bits + f.man_bits : 0u; }
+
+float omc_format_max(omc_format f) {
+    FmtParams p;
+    return make_fmt_params(f, &p) ? p.maxval : 0.0f;
+}
+
+size_t omc_packed_bytes(omc_format f, uint64_t n) {
+    if (!format_ok(f) || n == 0 || n > kMaxElems) return 0;
+    return packed_bytes_u(1u + f.exp_bits + f.man_bits, n);
+}
+
+size_t omc_compress_workspace_bytes(uint64_t n) {
+    if (n == 0 || n > kMaxElems) return 0;
+    return static_cast<size_t>((n + kChunkElems - 1) / kChunkElems) * sizeof(Partial);
+}
+
+omc_status omc_compress(const float *v, uint64_t n, omc_format f, int use_pvt, void *codes, float *sb,
+                        void *ws, size_t ws_bytes, void *stream) {
+    if (!v || !codes || !sb) return OMC_ERR_NULL;
+    FmtParams fp;
+    if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
+    if (n == 0 || n > kMaxElems) return OMC_ERR_SIZE;
+    if (!aligned16(v) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return OMC_ERR_ALIGN;
+    const size_t need = omc_compress_workspace_bytes(n);
+    if (!ws || ws_bytes < need) return OMC_ERR_WORKSPACE;
+    if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    const size_t pb = packed_bytes_u(fp.bits, n);
+    const uintptr_t v0 = reinterpret_cast<uintptr_t>(v), c0 = reinterpret_cast<uintptr_t>(codes);
+    if (v0 < c0 + pb && c0 < v0 + 4 * n) return OMC_ERR_SIZE;  // input and output overlap
+    VarArgs va{n, pb / 4, fp};
+    const int rc = launch_compress(v, va, use_pvt, codes, sb, static_cast<Partial *>(ws), stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+omc_status omc_decompress(const void *codes, uint64_t n, omc_format f, const float *sb, float *out,
+                          void *stream) {
+    if (!codes || !out) return OMC_ERR_NULL;
+    FmtParams fp;
+    if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
+    if (n == 0 || n > kMaxElems) return OMC_ERR_SIZE;
+    if (!aligned16(codes) || !aligned16(out) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return OMC_ERR_ALIGN;
+    const size_t pb = packed_bytes_u(fp.bits, n);
+    const uintptr_t o0 = reinterpret_cast<uintptr_t>(out), c0 = reinterpret_cast<uintptr_t>(codes);
+    if (o0 < c0 + pb && c0 < o0 + 4 * n) return OMC_ERR_SIZE;
+    VarArgs va{n, pb / 4, fp};
+    const int rc = launch_decompress(codes, va, sb, out, stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+size_t omc_plan_bytes(const omc_var *vars_host, uint32_t nvars) {
+    PlanLayout pl;
+    if (plan_layout(vars_host, nvars, &pl) != OMC_OK) return 0;
+    return static_cast<size_t>(pl.total);
+}
+
+omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_host, size_t plan_bytes) {
+    if (!plan_host) return OMC_ERR_NULL;
+    PlanLayout pl;
+    const omc_status st = plan_layout(vars_host, nvars, &pl);
+    if (st != OMC_OK) return st;
+    if (plan_bytes < pl.total) return OMC_ERR_SIZE;
+    uint8_t *base = static_cast<uint8_t *>(plan_host);
+    std::memset(base, 0, pl.total);
+    PlanHeader *ph = reinterpret_cast<PlanHeader *>(base);
+    PlanVar *pv = reinterpret_cast<PlanVar *>(base + pl.var_off);
+    PlanItem *items = reinterpret_cast<PlanItem *>(base + pl.item_off);
+    PlanGroup *groups = reinterpret_cast<PlanGroup *>(base + pl.group_off);
+    uint64_t arena_bytes = 0, aux_elems = 0;
+    for (uint32_t i = 0; i < nvars; ++i) {
+        const omc_var &v = vars_host[i];
+        PlanVar &d = pv[i];
+        d.data_offset = v.data_offset;
+        d.aux_offset = v.aux_offset;
+        d.n = v.n;
+        d.flags = v.flags;
+        uint64_t bytes;
+        if (v.flags & OMC_VAR_QUANTIZED) {
+            make_fmt_params(v.fmt, &d.fp);
+            bytes = packed_bytes_u(d.fp.bits, v.n);
+            d.total_dwords = bytes / 4;
+        } else {
+            bytes = 4 * v.n;
+        }
+        d.nitems = static_cast<uint32_t>((v.n + kChunkElems - 1) / kChunkElems);
+        arena_bytes = std::max(arena_bytes, v.data_offset + bytes);
+        aux_elems = std::max(aux_elems, v.aux_offset + v.n);
+    }
+    uint32_t next = 0;
+    for (uint32_t gi = 0; gi < pl.ngroups; ++gi) {
+        const uint32_t bits = pl.group_bits[gi];
+        groups[gi].bits = bits;
+        groups[gi].first_item = next;
+        for (uint32_t i = 0; i < nvars; ++i) {
+            const bool q = (vars_host[i].flags & OMC_VAR_QUANTIZED) != 0;
+            if (bits == 0 ? q : (!q || pv[i].fp.bits != bits)) continue;
+            pv[i].first_item = next;
+            for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
+        }
+        groups[gi].nitems = next - groups[gi].first_item;
+    }
+    ph->magic = kPlanMagic;
+    ph->version = kPlanVersion;
+    ph->nvars = nvars;
+    ph->nitems = pl.nitems;
+    ph->ngroups = pl.ngroups;
+    ph->nquant = pl.nquant;
+    ph->total_bytes = pl.total;
+    ph->var_off = pl.var_off;
+    ph->item_off = pl.item_off;
+    ph->group_off = pl.group_off;
+    ph->arena_bytes = arena_bytes;
+    ph->aux_elems = aux_elems;
+    ph->ws_bytes = std::max<uint64_t>(16, static_cast<uint64_t>(pl.nitems) * sizeof(Partial));
+    ph->checksum = 0;
+    return OMC_OK;
+}
+
+size_t omc_plan_workspace_bytes(const void *plan_host) {
+    const PlanHeader *ph = plan_check(plan_host);
+    return ph ? static_cast<size_t>(ph->ws_bytes) : 0;
+}
+
+size_t omc_plan_arena_bytes(const void *plan_host) {
+    const PlanHeader *ph = plan_check(plan_host);
+    return ph ? static_cast<size_t>(ph->arena_bytes) : 0;
+}
+
+uint64_t omc_plan_aux_elems(const void *plan_host) {
+    const PlanHeader *ph = plan_check(plan_host);
+    return ph ? ph->aux_elems : 0;
+}
+
+omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const void *plan_host,
+                                      const void *plan_dev, float *sb_table, const float *grads,
+                                      float *state0, float *state1, uint64_t aux_elems,
+                                      const omc_opt *opt, void *ws, size_t ws_bytes, void *stream) {
+    if (!arena || !plan_host || !plan_dev || !sb_table || !grads || !opt) return OMC_ERR_NULL;
+    const PlanHeader *ph = plan_check(plan_host);
+    if (!ph) return OMC_ERR_PLAN;
+    if (opt->kind != OMC_SGD && opt->kind != OMC_MOMENTUM && opt->kind != OMC_ADAM) return OMC_ERR_OPT;
+    if (opt->kind >= OMC_MOMENTUM && !state0) return OMC_ERR_OPT;
+    if (opt->kind == OMC_ADAM && !state1) return OMC_ERR_OPT;
+    if (arena_bytes < ph->arena_bytes || aux_elems < ph->aux_elems) return OMC_ERR_SIZE;
+    if (!aligned16(arena) || !aligned16(grads) || !aligned16(plan_dev) ||
+        (reinterpret_cast<uintptr_t>(sb_table) & 7u))
+        return OMC_ERR_ALIGN;
+    if (opt->kind >= OMC_MOMENTUM && !aligned16(state0)) return OMC_ERR_ALIGN;
+    if (opt->kind == OMC_ADAM && !aligned16(state1)) return OMC_ERR_ALIGN;
+    if (!ws || ws_bytes < ph->ws_bytes) return OMC_ERR_WORKSPACE;
+    if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    const int rc = launch_step(arena, ph, plan_dev, sb_table, grads, state0, state1, *opt,
+                               static_cast<Partial *>(ws), stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+size_t omc_dequant_gemm_workspace_bytes(uint32_t M) {
+    return M == 0 ? 0 : (static_cast<size_t>(M) * sizeof(float) + 15) / 16 * 16;
+}
+
+omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, const float *sb, float *C,
+                            uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes, void *stream) {
+    if (!A || !codes || !C) return OMC_ERR_NULL;
+    FmtParams fp;
+    if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
+    if (fp.man_bits > 7) return OMC_ERR_FORMAT;
+    if (M == 0 || N == 0 || K == 0 || M % 256 != 0 || N % 256 != 0 || K % 64 != 0) return OMC_ERR_SIZE;
+    if (!aligned16(A) || !aligned16(codes) || !aligned16(C) || (reinterpret_cast<uintptr_t>(sb) & 3u))
+        return OMC_ERR_ALIGN;
+    if (!ws || ws_bytes < omc_dequant_gemm_workspace_bytes(M)) return OMC_ERR_WORKSPACE;
+    if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    const int rc = launch_dequant_gemm(A, codes, fp, sb, C, M, N, K, static_cast<float *>(ws), stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+}  // extern "C"

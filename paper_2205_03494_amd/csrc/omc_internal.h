@@ -1,0 +1,103 @@
+// Shared host/device declarations of libomc (not part of the public ABI).
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+#include "omc.h"
+
+namespace omc {
+
+// Work decomposition of the streaming kernels.  One wavefront owns one tile at a time:
+// 64 lanes x 32 consecutive elements.  32 elements of a B-bit format are exactly B dwords, so a
+// lane's share of the packed stream is B whole dwords for every B and no dword is shared
+// between lanes, tiles or variables.
+constexpr int kLaneElems = 32;
+constexpr int kTileElems = 64 * kLaneElems;           // 2048
+constexpr int kTilesPerChunk = 4;                     // tiles reduced into one partial
+constexpr int kChunkElems = kTileElems * kTilesPerChunk;
+constexpr int kLdsDwords = kTileElems + kTileElems / 32;  // padded code tile for B = 32
+
+// Constants derived from a format once on the host; uniform per variable (scalar registers).
+struct FmtParams {
+    uint32_t bits;           // B = 1 + E + M
+    uint32_t exp_bits;       // E
+    uint32_t man_bits;       // M
+    uint32_t bias;
+    uint32_t sh;             // 23 - M: fp32 mantissa bits below the format's mantissa
+    uint32_t asr;            // 8 - E
+    uint32_t keep_mask;      // fp32 bit positions that carry [sign | e | m] after alignment
+    uint32_t min_norm_bits;  // fp32 bit pattern of 2^(1 - bias), the smallest normal
+    uint32_t magic_off;      // (23 - M) << 23
+    uint32_t wide;           // 1: round with ldexp/rint (top binade + 23 - M would overflow fp32, or M == 23)
+    int32_t exp_adj;         // 127 + M
+    float dec_scale;         // 2^(127 - bias)
+    float enc_scale;         // 2^(bias - 127)
+    float maxval;            // largest representable magnitude
+};
+
+// Per-chunk partial sums of the least-squares fit (paper Sec. 2.3).
+struct Partial {
+    double sV, sT, sVT, sTT;
+    float tmin, tmax;
+    uint32_t pad[2];
+};
+static_assert(sizeof(Partial) == 48, "Partial layout");
+
+// ---- plan blob ---------------------------------------------------------------------------
+constexpr uint32_t kPlanMagic = 0x434d4f50u;  // "POMC"
+constexpr uint32_t kPlanVersion = 1;
+
+struct PlanHeader {
+    uint32_t magic, version;
+    uint32_t nvars, nitems, ngroups, nquant;
+    uint64_t total_bytes;
+    uint64_t var_off, item_off, group_off;  // byte offsets of the three tables inside the blob
+    uint64_t arena_bytes;                   // extent of the arena the plan addresses
+    uint64_t aux_elems;                     // extent of grads / state
+    uint64_t ws_bytes;
+    uint64_t checksum;                      // over everything after the header
+};
+
+struct PlanVar {
+    uint64_t data_offset, aux_offset, n;
+    uint64_t total_dwords;   // packed buffer length in dwords (multiple of 4); 0 for fp32
+    uint32_t flags;          // OMC_VAR_*
+    uint32_t first_item;     // index of this variable's first work item / partial
+    uint32_t nitems;
+    uint32_t pad;
+    FmtParams fp;
+};
+
+struct PlanItem {
+    uint32_t var;
+    uint32_t chunk;
+};
+
+struct PlanGroup {
+    uint32_t bits;           // code width of the group's variables; 0 = fp32 variables
+    uint32_t first_item;
+    uint32_t nitems;
+    uint32_t pad;
+};
+
+// ---- host helpers (omc_host.cpp) -----------------------------------------------------------
+bool make_fmt_params(omc_format f, FmtParams *out);
+const PlanHeader *plan_check(const void *plan_host);
+
+// ---- launchers, one translation unit each (device code) -----------------------------------
+// Arguments already validated.  Return hipError_t as int.
+struct VarArgs {
+    uint64_t n;
+    uint64_t total_dwords;
+    FmtParams fp;
+};
+
+int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb,
+                    Partial *ws, void *stream);
+int launch_decompress(const void *codes, const VarArgs &va, const float *sb, float *out, void *stream);
+int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table,
+                const float *grads, float *state0, float *state1, const omc_opt &opt, Partial *ws,
+                void *stream);
+int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb,
+                        float *C, uint32_t M, uint32_t N, uint32_t K, float *rowsum, void *stream);
+
+}  // namespace omc

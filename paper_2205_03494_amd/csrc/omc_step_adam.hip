@@ -1,0 +1,8 @@
+// Fused decompress -> adam update -> recompress kernels, one per code width.
+#include "omc_step_impl.h"
+
+namespace omc {
+int launch_step_group_adam(uint32_t bits, const StepArgs &sa, hipStream_t st) {
+    return launch_step_group_mode<kStepAdam>(bits, sa, st);
+}
+}  // namespace omc

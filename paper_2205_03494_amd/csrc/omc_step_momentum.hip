@@ -1,0 +1,8 @@
+// Fused decompress -> momentum update -> recompress kernels, one per code width.
+#include "omc_step_impl.h"
+
+namespace omc {
+int launch_step_group_momentum(uint32_t bits, const StepArgs &sa, hipStream_t st) {
+    return launch_step_group_mode<kStepMomentum>(bits, sa, st);
+}
+}  // namespace omc

@@ -1,0 +1,210 @@
+"""Thin binding over libomc (include/omc.h): argument marshalling only.
+
+Every step of the method runs inside the library's HIP kernels; PyTorch appears here only as the
+owner of device memory and of the stream.  The functions carry the C names.  Tensors must be
+contiguous and live on the GPU; nothing here falls back to a CPU path, and importing this module
+fails loudly when the shared library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libomc.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `make -C paper_2205_03494_amd/csrc` "
+        "(or __graft_entry__.build()); there is no fallback implementation")
+
+_lib = C.CDLL(LIB_PATH)
+
+OMC_OK = 0
+OMC_VAR_QUANTIZED = 1
+OMC_VAR_NO_PVT = 2
+OMC_SGD, OMC_MOMENTUM, OMC_ADAM = 0, 1, 2
+OMC_BIAS_DEFAULT = -1
+
+
+class omc_format(C.Structure):
+    _fields_ = [("exp_bits", C.c_uint8), ("man_bits", C.c_uint8), ("exp_bias", C.c_int16)]
+
+
+class omc_var(C.Structure):
+    _fields_ = [("data_offset", C.c_uint64), ("aux_offset", C.c_uint64), ("n", C.c_uint64),
+                ("fmt", omc_format), ("flags", C.c_uint32)]
+
+
+class omc_opt(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("momentum", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("one_minus_beta1", C.c_float), ("one_minus_beta2", C.c_float),
+                ("bias_corr1", C.c_float), ("bias_corr2", C.c_float)]
+
+
+def _sig(name, restype, *argtypes):
+    fn = getattr(_lib, name)
+    fn.restype = restype
+    fn.argtypes = list(argtypes)
+    return fn
+
+
+_vp = C.c_void_p
+_status_string = _sig("omc_status_string", C.c_char_p, C.c_int)
+_format_validate = _sig("omc_format_validate", C.c_int, omc_format)
+_format_bits = _sig("omc_format_bits", C.c_uint32, omc_format)
+_format_max = _sig("omc_format_max", C.c_float, omc_format)
+_packed_bytes = _sig("omc_packed_bytes", C.c_size_t, omc_format, C.c_uint64)
+_compress_ws = _sig("omc_compress_workspace_bytes", C.c_size_t, C.c_uint64)
+_compress = _sig("omc_compress", C.c_int, _vp, C.c_uint64, omc_format, C.c_int, _vp, _vp, _vp, C.c_size_t, _vp)
+_decompress = _sig("omc_decompress", C.c_int, _vp, C.c_uint64, omc_format, _vp, _vp, _vp)
+_plan_bytes = _sig("omc_plan_bytes", C.c_size_t, _vp, C.c_uint32)
+_plan_build = _sig("omc_plan_build", C.c_int, _vp, C.c_uint32, _vp, C.c_size_t)
+_plan_ws = _sig("omc_plan_workspace_bytes", C.c_size_t, _vp)
+_plan_arena = _sig("omc_plan_arena_bytes", C.c_size_t, _vp)
+_plan_aux = _sig("omc_plan_aux_elems", C.c_uint64, _vp)
+_step = _sig("omc_step_update_recompress", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, _vp, _vp,
+             C.c_uint64, C.POINTER(omc_opt), _vp, C.c_size_t, _vp)
+_gemm_ws = _sig("omc_dequant_gemm_workspace_bytes", C.c_size_t, C.c_uint32)
+_gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
+             C.c_uint32, _vp, C.c_size_t, _vp)
+
+EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_format_max",
+            "omc_packed_bytes", "omc_compress_workspace_bytes", "omc_compress", "omc_decompress",
+            "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_plan_arena_bytes",
+            "omc_plan_aux_elems", "omc_step_update_recompress", "omc_dequant_gemm_workspace_bytes",
+            "omc_dequant_gemm"]
+
+
+class OmcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({_status_string(status).decode()})")
+
+
+def _check(status: int, where: str):
+    if status != OMC_OK:
+        raise OmcError(status, where)
+
+
+def fmt(exp_bits: int, man_bits: int, bias: int = OMC_BIAS_DEFAULT) -> omc_format:
+    return omc_format(exp_bits, man_bits, bias)
+
+
+def opt(kind: int, lr: float, momentum: float = 0.9, beta1: float = 0.9, beta2: float = 0.999,
+        eps: float = 1e-8, t: int = 1) -> omc_opt:
+    """Hyper-parameters; the derived constants are computed in fp64 here and rounded once (omc.h)."""
+    return omc_opt(kind, lr, momentum, beta1, beta2, eps, 1.0 - beta1, 1.0 - beta2,
+                   1.0 - beta1 ** t, 1.0 - beta2 ** t)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("libomc takes contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+# ------------------------------------------------------------------ host-only helpers
+def omc_format_validate(f: omc_format) -> int:
+    return _format_validate(f)
+
+
+def omc_format_bits(f: omc_format) -> int:
+    return _format_bits(f)
+
+
+def omc_format_max(f: omc_format) -> float:
+    return _format_max(f)
+
+
+def omc_packed_bytes(f: omc_format, n: int) -> int:
+    return _packed_bytes(f, n)
+
+
+def omc_compress_workspace_bytes(n: int) -> int:
+    return _compress_ws(n)
+
+
+def omc_dequant_gemm_workspace_bytes(M: int) -> int:
+    return _gemm_ws(M)
+
+
+# ------------------------------------------------------------------ single variable
+def omc_compress(v: torch.Tensor, n: int, f: omc_format, use_pvt: bool, codes: torch.Tensor,
+                 sb: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    _check(_compress(_ptr(v), n, f, int(use_pvt), _ptr(codes), _ptr(sb), _ptr(ws),
+                     ws.numel() * ws.element_size(), _stream(stream)), "omc_compress")
+
+
+def omc_decompress(codes: torch.Tensor, n: int, f: omc_format, sb: Optional[torch.Tensor],
+                   out: torch.Tensor, stream=None) -> None:
+    _check(_decompress(_ptr(codes), n, f, _ptr(sb), _ptr(out), _stream(stream)), "omc_decompress")
+
+
+# ------------------------------------------------------------------ variable sets
+@dataclass
+class Plan:
+    """Host and device copies of a plan blob (omc_plan_build)."""
+    host: np.ndarray            # uint8
+    dev: torch.Tensor           # uint8, same bytes on the GPU
+    nvars: int
+
+    @property
+    def workspace_bytes(self) -> int:
+        return _plan_ws(self.host.ctypes.data)
+
+    @property
+    def arena_bytes(self) -> int:
+        return _plan_arena(self.host.ctypes.data)
+
+    @property
+    def aux_elems(self) -> int:
+        return _plan_aux(self.host.ctypes.data)
+
+
+def make_var_table(vars_: Sequence[dict]):
+    tab = (omc_var * len(vars_))()
+    for i, v in enumerate(vars_):
+        flags = (OMC_VAR_QUANTIZED if v["quantized"] else 0) | (0 if v.get("use_pvt", True) else OMC_VAR_NO_PVT)
+        f = v.get("fmt") or omc_format(8, 23, OMC_BIAS_DEFAULT)
+        tab[i] = omc_var(int(v["data_offset"]), int(v["aux_offset"]), int(v["n"]), f, flags)
+    return tab
+
+
+def omc_plan_build(var_table, device="cuda") -> Plan:
+    nvars = len(var_table)
+    size = _plan_bytes(C.cast(var_table, _vp), nvars)
+    host = np.zeros(max(size, 1), dtype=np.uint8)
+    _check(_plan_build(C.cast(var_table, _vp), nvars, host.ctypes.data, size), "omc_plan_build")
+    dev = torch.from_numpy(host).to(device)
+    return Plan(host, dev, nvars)
+
+
+def omc_step_update_recompress(arena: torch.Tensor, plan: Plan, sb_table: torch.Tensor,
+                               grads: torch.Tensor, state0: Optional[torch.Tensor],
+                               state1: Optional[torch.Tensor], o: omc_opt, ws: torch.Tensor,
+                               stream=None) -> None:
+    _check(_step(_ptr(arena), arena.numel() * arena.element_size(), plan.host.ctypes.data,
+                 _ptr(plan.dev), _ptr(sb_table), _ptr(grads), _ptr(state0), _ptr(state1),
+                 grads.numel(), C.byref(o), _ptr(ws), ws.numel() * ws.element_size(),
+                 _stream(stream)), "omc_step_update_recompress")
+
+
+# ------------------------------------------------------------------ forward path
+def omc_dequant_gemm(A: torch.Tensor, codes: torch.Tensor, f: omc_format, sb: Optional[torch.Tensor],
+                     Cout: torch.Tensor, M: int, N: int, K: int, ws: torch.Tensor, stream=None) -> None:
+    _check(_gemm(_ptr(A), _ptr(codes), f, _ptr(sb), _ptr(Cout), M, N, K, _ptr(ws),
+                 ws.numel() * ws.element_size(), _stream(stream)), "omc_dequant_gemm")

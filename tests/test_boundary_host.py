@@ -1,0 +1,148 @@
+"""Host-side checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching a device.  No compute calls are made."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import omc_oracle as orc
+from paper_2205_03494_amd import omc, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "omc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(omc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 14
+    lib = C.CDLL(omc.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(omc.EXPORTED)
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(omc.omc_format) == 4
+    assert C.sizeof(omc.omc_var) == 32
+    assert C.sizeof(omc.omc_opt) == 40
+
+
+def test_format_validation_and_constants_agree_with_oracle():
+    for E in range(1, 9):
+        for M in range(0, 24):
+            f = omc.fmt(E, M)
+            assert omc.omc_format_validate(f) == omc.OMC_OK
+            assert omc.omc_format_bits(f) == 1 + E + M
+            assert omc.omc_format_max(f) == np.float32(orc.Format(E, M).max)
+            for n in (1, 31, 2048, 2049, 1234567):
+                assert omc.omc_packed_bytes(f, n) == orc.packed_bytes(n, 1 + E + M)
+    for bad in (omc.fmt(0, 3), omc.fmt(9, 3), omc.fmt(4, 24), omc.fmt(4, 3, 128), omc.fmt(4, 3, -2)):
+        assert omc.omc_format_validate(bad) == 2
+        assert omc.omc_format_bits(bad) == 0 and omc.omc_packed_bytes(bad, 10) == 0
+    assert omc.omc_packed_bytes(omc.fmt(4, 3), 0) == 0
+    assert omc.omc_format_max(omc.fmt(4, 3, 4)) == np.float32(orc.Format(4, 3, 4).max)
+
+
+def _table(vs):
+    return omc.make_var_table(vs)
+
+
+def _plan_status(vs):
+    tab = _table(vs)
+    size = omc._plan_bytes(C.cast(tab, C.c_void_p), len(vs))
+    buf = np.zeros(max(size, 4096), np.uint8)
+    return size, omc._plan_build(C.cast(tab, C.c_void_p), len(vs), buf.ctypes.data, buf.size), buf
+
+
+def test_plan_build_validates_the_table():
+    f = omc.fmt(3, 7)
+    good = [dict(data_offset=0, aux_offset=0, n=5000, fmt=f, quantized=True),
+            dict(data_offset=6880, aux_offset=5000, n=100, quantized=False)]
+    size, st, buf = _plan_status(good)
+    assert st == 0 and size > 0
+    assert omc._plan_ws(buf.ctypes.data) == 48 * 2
+    assert omc._plan_arena(buf.ctypes.data) == 6880 + 400
+    assert omc._plan_aux(buf.ctypes.data) == 5100
+    # misaligned offsets
+    assert _plan_status([dict(good[0], data_offset=8)])[1] == 4
+    assert _plan_status([dict(good[0], aux_offset=2)])[1] == 4
+    # n == 0, bad format
+    assert _plan_status([dict(good[0], n=0)])[1] == 3
+    assert _plan_status([dict(good[0], fmt=omc.fmt(9, 1))])[1] == 2
+    # overlap in the arena (packed 5000 x 11 bits = 6875 -> 6880 bytes) and in aux
+    assert _plan_status([good[0], dict(good[1], data_offset=6864)])[1] == 3
+    assert _plan_status([good[0], dict(good[1], aux_offset=4996)])[1] == 3
+    # corrupt blob
+    buf2 = buf.copy()
+    buf2[0] ^= 0xFF
+    assert omc._plan_ws(buf2.ctypes.data) == 0
+    # empty table / NULL
+    assert omc._plan_build(None, 1, buf.ctypes.data, buf.size) == 1
+    assert omc._plan_bytes(C.cast(_table(good), C.c_void_p), 0) == 0
+
+
+def test_plan_item_list_covers_every_chunk_once():
+    specs = synth.conformer_varset(64, 2, 256, 8, frontend=False)
+    mask = synth.ppq_mask(specs, 0.5, 1)
+    f = omc.fmt(4, 3)
+    lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(f, n))
+    vs = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=f,
+               quantized=bool(mask[i])) for i, s in enumerate(specs)]
+    size, st, buf = _plan_status(vs)
+    assert st == 0
+    hdr = np.frombuffer(buf[:32].tobytes(), dtype=np.uint32)
+    nvars, nitems, ngroups, nquant = (int(x) for x in hdr[2:6])
+    assert nvars == len(specs) and ngroups == 2 and nquant == int(mask.sum())
+    offs = np.frombuffer(buf[32:56].tobytes(), dtype=np.uint64)
+    item_off = int(offs[1])
+    items = np.frombuffer(buf[item_off:item_off + 8 * nitems].tobytes(), dtype=np.uint32).reshape(-1, 2)
+    want = sorted((i, c) for i, s in enumerate(specs) for c in range((s.n + 8191) // 8192))
+    assert sorted(map(tuple, items.tolist())) == want
+
+
+def test_entry_points_reject_bad_arguments_without_a_device():
+    f = omc.fmt(4, 3)
+    A = 0x1000  # a fake, aligned, never dereferenced address
+    # NULL pointers
+    assert omc._compress(None, 10, f, 1, A, A, A, 48, None) == 1
+    assert omc._decompress(None, 10, f, None, A, None) == 1
+    # bad format / size / alignment / workspace
+    assert omc._compress(A, 10, omc.fmt(0, 0), 1, 0x100000, A, A, 48, None) == 2
+    assert omc._compress(A, 0, f, 1, 0x100000, A, A, 48, None) == 3
+    assert omc._compress(A + 4, 10, f, 1, 0x100000, A, A, 48, None) == 4
+    assert omc._compress(A, 10, f, 1, 0x100000, A, None, 0, None) == 5
+    assert omc._compress(A, 10000, f, 1, 0x100000, A, 0x200000, 48, None) == 5
+    assert omc._compress(A, 10, f, 1, A, A, 0x200000, 48, None) == 3          # in == out
+    assert omc._decompress(A, 10, f, None, A + 8, None) == 4
+    # step: plan / optimizer / sizes
+    vs = [dict(data_offset=0, aux_offset=0, n=5000, fmt=f, quantized=True)]
+    size, st, buf = _plan_status(vs)
+    o = omc.opt(omc.OMC_ADAM, 1e-3)
+    args = lambda **kw: dict(dict(arena=A, ab=1 << 20, ph=buf.ctypes.data, pd=A, sb=A, g=A, s0=A, s1=A,
+                                  aux=5000, o=o, ws=A, wsb=4096), **kw)
+
+    def call(**kw):
+        a = args(**kw)
+        return omc._step(a["arena"], a["ab"], a["ph"], a["pd"], a["sb"], a["g"], a["s0"], a["s1"],
+                         a["aux"], C.byref(a["o"]), a["ws"], a["wsb"], None)
+    assert call(arena=None) == 1
+    assert call(s1=None) == 6
+    assert call(o=omc.opt(7, 1e-3)) == 6
+    assert call(ab=100) == 3
+    assert call(aux=10) == 3
+    assert call(wsb=8) == 5
+    assert call(g=A + 4) == 4
+    bad = buf.copy()
+    bad[4] ^= 1
+    assert call(ph=bad.ctypes.data) == 8
+    # gemm
+    assert omc._gemm(A, A, omc.fmt(5, 10), None, A, 256, 256, 64, A, 4096, None) == 2
+    assert omc._gemm(A, A, f, None, A, 100, 256, 64, A, 4096, None) == 3
+    assert omc._gemm(A, A, f, None, A, 256, 256, 64, A, 16, None) == 5
