@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the OMC hot path on one MI355X.
+
+A "step" is one training iteration over the whole variable set: for every quantized weight
+matrix decompress -> SGD update -> recompress (fused in one kernel), for every fp32 variable the
+update alone, then the per-variable (s, b) finalize -- i.e. one omc_step_update_recompress call.
+The workload is the Conformer-encoder-shaped set of about 115 M weight-matrix parameters
+(17 blocks, d_model 512, FFN 2048, depthwise kernel 32, plus a front end), every weight matrix in
+the 8-bit S1E4M3 code with the per-variable transformation, biases and norm vectors in fp32,
+values N(0, 1/sqrt(fan_in)), gradients N(0, 1e-3), all seeded and synthetic and resident in HBM
+before the timed region.
+
+Prints one JSON line.  `value` is compressed-parameter GB/s (packed bytes of the quantized
+variables stepped per second); `roofline` prices the dominant kernel's algorithmic HBM bytes
+(6 B per 8-bit element: code in, gradient in, code out) against 8 TB/s; `cpu_baseline` is the CPU
+oracle timed on a bounded sample of the same variable set on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def build_workload(torch, omc, synth, blocks, d_model, ffn, seed=0):
+    """Config-2 variable set, compressed on the GPU by the library itself."""
+    import numpy as np
+    specs = synth.conformer_varset(d_model, blocks, ffn, 32, frontend=True)
+    mask = np.array([s.is_matrix for s in specs])
+    gf = omc.fmt(4, 3)
+    lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(gf, n))
+    vals = synth.init_values(lay, seed)
+    vals_d = torch.from_numpy(vals).cuda()
+    arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
+    sb = torch.zeros((len(specs), 2), dtype=torch.float32, device="cuda")
+    sb[:, 0] = 1.0
+    nmax = max(s.n for s in specs)
+    ws = torch.empty(max(omc.omc_compress_workspace_bytes(nmax), 16), dtype=torch.uint8, device="cuda")
+    table = []
+    for i, s in enumerate(specs):
+        a, d = int(lay.aux_offset[i]), int(lay.data_offset[i])
+        if mask[i]:
+            nb = omc.omc_packed_bytes(gf, s.n)
+            omc.omc_compress(vals_d[a:a + s.n], s.n, gf, True, arena[d:d + nb], sb[i], ws)
+        else:
+            arena[d:d + 4 * s.n] = vals_d[a:a + s.n].view(torch.uint8)
+        table.append(dict(data_offset=d, aux_offset=a, n=s.n, fmt=gf, quantized=bool(mask[i])))
+    plan = omc.omc_plan_build(omc.make_var_table(table))
+    torch.cuda.synchronize()
+    return dict(specs=specs, mask=mask, lay=lay, vals=vals, arena=arena, sb=sb, plan=plan, table=table)
+
+
+def cpu_baseline(wl, synth, sample_blocks, iters, threads, gpu_after=None):
+    """The oracle as it stands on a bounded sample: the variables of the first `sample_blocks`
+    Conformer blocks, `iters` iterations.  Also returns the oracle's state for a parity check."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import omc_oracle as orc
+    specs, lay, mask = wl["specs"], wl["lay"], wl["mask"]
+    of = orc.Format(4, 3)
+    pick = [i for i, s in enumerate(specs)
+            if s.name.startswith("block") and int(s.name.split("/")[0][5:]) < sample_blocks]
+    sub_specs = [specs[i] for i in pick]
+    sub_mask = mask[pick]
+    sub_lay = synth.make_layout(sub_specs, sub_mask, lambda n: orc.packed_bytes(n, of.bits))
+    arena = np.zeros(sub_lay.arena_bytes, np.uint8)
+    sbt = np.zeros((len(pick), 2), np.float32)
+    sbt[:, 0] = 1.0
+
+    def init(j):
+        i = pick[j]
+        s = specs[i]
+        a = int(lay.aux_offset[i])
+        x = wl["vals"][a:a + s.n]
+        d = int(sub_lay.data_offset[j])
+        if sub_mask[j]:
+            p, sb = orc.compress(x, of)
+            arena[d:d + p.size] = p
+            sbt[j] = sb
+        else:
+            arena[d:d + 4 * s.n] = x.view(np.uint8)
+
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(init, range(len(pick))))
+    table = orc.make_var_table(dict(data_offset=int(sub_lay.data_offset[j]), aux_offset=int(sub_lay.aux_offset[j]),
+                                    n=specs[i].n, fmt=of, quantized=bool(sub_mask[j]))
+                               for j, i in enumerate(pick))
+    grads = []
+    for gset in wl["grads_host"]:
+        g = np.zeros(sub_lay.aux_elems, np.float32)
+        for j, i in enumerate(pick):
+            a, b = int(lay.aux_offset[i]), int(sub_lay.aux_offset[j])
+            g[b:b + specs[i].n] = gset[a:a + specs[i].n]
+        grads.append(g)
+    n_elems = sum(specs[i].n for i in pick)
+    packed_bytes = sum(orc.packed_bytes(specs[i].n, 8) for j, i in enumerate(pick) if sub_mask[j])
+    first = None
+    t0 = time.perf_counter()
+    for t in range(iters):
+        orc.step_varset(arena, table, sbt, grads[t % len(grads)], None, None,
+                        orc.Opt(kind=0, lr=0.01, t=t + 1), threads=threads)
+        if t == 0:
+            first = (arena.copy(), sbt.copy())
+    dt = (time.perf_counter() - t0) / iters
+    return dict(pick=pick, sub_lay=sub_lay, sub_mask=sub_mask, first=first, sec_per_iter=dt,
+                n_elems=n_elems, packed_bytes=packed_bytes)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--blocks", type=int, default=17, help="Conformer blocks (17 = the benchmark workload)")
+    ap.add_argument("--cpu-sample-blocks", type=int, default=4)
+    ap.add_argument("--cpu-iters", type=int, default=3)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device-to-device copy of known size (1 GiB read + 1 GiB written "
+                         "per launch) to calibrate profiler byte counters and show the copy ceiling")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+                 "(no collectives or sharding exist in this library)")
+
+    import numpy as np
+    import torch
+    from paper_2205_03494_amd import omc, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = 1 << 28                                   # 2^28 floats = 1 GiB
+        src = torch.randn(n, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 20
+        print(json.dumps({"copy_kernel": "torch Tensor.copy_ fp32", "bytes_read": 4 * n, "bytes_written": 4 * n,
+                          "ms": ms, "GBps": 8 * n / (ms * 1e-3) / 1e9}))
+        return
+    wl = build_workload(torch, omc, synth, args.blocks, 512, 2048)
+    specs, mask, lay, plan = wl["specs"], wl["mask"], wl["lay"], wl["plan"]
+    # a ring of two pre-generated gradient sets, resident in HBM
+    wl["grads_host"] = [synth.gradients(lay, 1e-3, 1000 + k) for k in range(2)]
+    grads = [torch.from_numpy(g).cuda() for g in wl["grads_host"]]
+    ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    o = omc.opt(omc.OMC_SGD, 0.01)
+    arena, sb = wl["arena"], wl["sb"]
+    arena0, sb0 = arena.clone(), sb.clone()
+
+    n_q = int(sum(s.n for s, q in zip(specs, mask) if q))
+    n_f = int(sum(s.n for s, q in zip(specs, mask) if not q))
+    packed_bytes = int(sum(omc.omc_packed_bytes(omc.fmt(4, 3), s.n) for s, q in zip(specs, mask) if q))
+    alg_bytes_q = 6.0 * n_q            # per element: 1 B code in + 4 B gradient in + 1 B code out
+    alg_bytes_step = alg_bytes_q + 12.0 * n_f + 8.0 * int(mask.sum())
+
+    def step(k):
+        omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], None, None, o, ws)
+
+    # ---- parity spot check + CPU baseline (oracle) on a bounded sample ------------------------
+    cpu = None
+    parity = None
+    if not args.no_cpu:
+        threads = min(16, os.cpu_count() or 1)
+        cpu = cpu_baseline(wl, synth, min(args.cpu_sample_blocks, args.blocks), args.cpu_iters, threads)
+        step(0)
+        torch.cuda.synchronize()
+        ga, gs = arena.cpu().numpy(), sb.cpu().numpy()
+        oa, osb = cpu["first"]
+        parity = True
+        for j, i in enumerate(cpu["pick"]):
+            d, e = int(lay.data_offset[i]), int(cpu["sub_lay"].data_offset[j])
+            nb = omc.omc_packed_bytes(omc.fmt(4, 3), specs[i].n) if mask[i] else 4 * specs[i].n
+            parity &= bool(np.array_equal(ga[d:d + nb], oa[e:e + nb]))
+            if mask[i]:
+                parity &= bool(np.array_equal(gs[i], osb[j]))
+        arena.copy_(arena0)
+        sb.copy_(sb0)
+
+    # ---- timed region: whole steps ---------------------------------------------------------------
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+
+    # ---- the same steps again with an event pair around every launch: per-kernel durations ------
+    nl = plan.launches
+    ev = omc.HipEvents(2 * nl * args.steps)
+    for k in range(args.steps):
+        omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], None, None, o, ws, ev,
+                                              first=k * 2 * nl)
+    torch.cuda.synchronize()
+    kern_ms = [0.0] * nl
+    for k in range(args.steps):
+        for j in range(nl):
+            kern_ms[j] += ev.elapsed_ms(k * 2 * nl + 2 * j, k * 2 * nl + 2 * j + 1)
+    kern_ms = [x / args.steps for x in kern_ms]
+    dom_ms = kern_ms[0]                                     # launch 0: the 8-bit fused step kernel
+    achieved = alg_bytes_q / (dom_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "compressed-param GB/s per decompress+update+recompress step; % HBM peak",
+        "value": packed_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"conformer-encoder-shaped set, {args.blocks} blocks d_model=512 ffn=2048 conv_k=32 "
+                               f"+ front end, {n_q} weight-matrix params in S1E4M3 (8-bit) with per-variable "
+                               f"transformation, {n_f} fp32 bias/norm params, SGD lr=0.01, grads N(0,1e-3)",
+                   "n_quantized_params": n_q, "n_fp32_params": n_f, "n_variables": len(specs),
+                   "packed_bytes": packed_bytes, "algorithmic_bytes_per_step": alg_bytes_step,
+                   "step_GBps_algorithmic": alg_bytes_step / (ms_per_step * 1e-3) / 1e9,
+                   "Gparam_per_s": (n_q + n_f) / (ms_per_step * 1e-3) / 1e9,
+                   "kernel_ms": {"step_kernel<8,sgd>": kern_ms[0],
+                                 "step_fp32_kernel<sgd>": kern_ms[1] if nl > 2 else None,
+                                 "finalize_plan_kernel": kern_ms[-1]},
+                   "parity_vs_oracle_on_sample": parity},
+        "roofline": {"bound": "hbm", "kernel": "step_kernel<8,sgd>", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None},
+    }
+    if cpu is not None:
+        out["cpu_baseline"] = {
+            "value": cpu["packed_bytes"] / cpu["sec_per_iter"] / 1e9, "unit": "GB/s",
+            "cores": min(16, os.cpu_count() or 1), "kind": "oracle",
+            "sample": f"first {min(args.cpu_sample_blocks, args.blocks)} Conformer blocks of the same set "
+                      f"({cpu['n_elems']} params), {args.cpu_iters} iterations, "
+                      f"{1e3 * cpu['sec_per_iter']:.0f} ms per iteration",
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

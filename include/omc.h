@@ -188,6 +188,23 @@ omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const voi
                                       float *state0, float *state1, uint64_t aux_elems,
                                       const omc_opt *opt, void *ws, size_t ws_bytes, void *stream);
 
+/* Measurement aid.  Same work as omc_step_update_recompress; additionally records caller-owned HIP
+ * events (hipEvent_t passed as void*) on the stream around every kernel launch, so that a
+ * benchmark can time each kernel by itself: events[2k] before and events[2k+1] after the k-th
+ * launch.  Launch order: the full-tile kernels, one per distinct code width among the quantized
+ * variables of at least 2048 elements, in ascending width (two for a width whose formats need
+ * both rounding variants: formats with man_bits == 23 or a top binade of 2^(105+man_bits) or more
+ * use the second); then up to two kernels for the ragged tails (n % 2048 != 0) of quantized
+ * variables; then one kernel for the fp32 variables, if any; then the per-variable
+ * finalize, if any variable is quantized.  omc_plan_launches gives the count; nevents must be at
+ * least twice that (OMC_ERR_SIZE otherwise).  Results are identical to the plain call. */
+uint32_t omc_plan_launches(const void *plan_host);
+omc_status omc_step_update_recompress_events(void *arena, size_t arena_bytes, const void *plan_host,
+                                             const void *plan_dev, float *sb_table, const float *grads,
+                                             float *state0, float *state1, uint64_t aux_elems,
+                                             const omc_opt *opt, void *ws, size_t ws_bytes, void *stream,
+                                             void *const *events, uint32_t nevents);
+
 /* ---- forward path ------------------------------------------------------------------------ */
 
 /* Workspace (device bytes) for omc_dequant_gemm with M activation rows. */

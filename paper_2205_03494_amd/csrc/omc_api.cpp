@@ -77,14 +77,17 @@ const PlanHeader *plan_check(const void *plan_host) {
 struct PlanLayout {
     uint64_t var_off, item_off, group_off, total;
     uint32_t nitems, ngroups, nquant;
-    std::vector<uint32_t> group_bits;  // ascending code widths present, then 0 if fp32 variables exist
+    // launches in order: full-tile kernels by ascending 2*bits + wide, tail kernels (narrow, wide),
+    // the fp32 kernel
+    std::vector<PlanGroup> groups;
 };
 
 // Validates the table; returns OMC_OK and the layout, or the first error.
 static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *pl) {
     if (!vars) return OMC_ERR_NULL;
     if (nvars == 0) return OMC_ERR_SIZE;
-    bool present[33] = {false};
+    bool present[66] = {false};
+    bool tails[2] = {false, false};
     bool any_fp32 = false;
     uint64_t nitems = 0;
     uint32_t nquant = 0;
@@ -99,16 +102,20 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
         if (v.flags & OMC_VAR_QUANTIZED) {
             if (!format_ok(v.fmt)) return OMC_ERR_FORMAT;
             const uint32_t bits = 1u + v.fmt.exp_bits + v.fmt.man_bits;
-            present[bits] = true;
+            FmtParams fp;
+            make_fmt_params(v.fmt, &fp);
+            if (v.n >= kTileElems) present[2 * bits + fp.wide] = true;
+            if (v.n % kTileElems) tails[fp.wide] = true;
             bytes = packed_bytes_u(bits, v.n);
             ++nquant;
+            nitems += (v.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk + (v.n % kTileElems ? 1 : 0);
         } else {
             any_fp32 = true;
             bytes = 4 * v.n;
+            nitems += (v.n + kChunkElems - 1) / kChunkElems;
         }
         data[i] = {v.data_offset, v.data_offset + bytes};
         aux[i] = {v.aux_offset, v.aux_offset + v.n};
-        nitems += (v.n + kChunkElems - 1) / kChunkElems;
     }
     if (nitems > 0x7fffffffull) return OMC_ERR_SIZE;
     auto overlaps = [](std::vector<Span> s) {
@@ -118,12 +125,14 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
         return false;
     };
     if (overlaps(data) || overlaps(aux)) return OMC_ERR_SIZE;
-    pl->group_bits.clear();
-    for (uint32_t b = 2; b <= 32; ++b)
-        if (present[b]) pl->group_bits.push_back(b);
-    if (any_fp32) pl->group_bits.push_back(0);
+    pl->groups.clear();
+    for (uint32_t k = 4; k < 66; ++k)
+        if (present[k]) pl->groups.push_back(PlanGroup{kGroupFull, k >> 1, k & 1u, 0, 0, 0});
+    for (uint32_t w = 0; w < 2; ++w)
+        if (tails[w]) pl->groups.push_back(PlanGroup{kGroupTail, 0, w, 0, 0, 0});
+    if (any_fp32) pl->groups.push_back(PlanGroup{kGroupFp32, 0, 0, 0, 0, 0});
     pl->nitems = static_cast<uint32_t>(nitems);
-    pl->ngroups = static_cast<uint32_t>(pl->group_bits.size());
+    pl->ngroups = static_cast<uint32_t>(pl->groups.size());
     pl->nquant = nquant;
     pl->var_off = sizeof(PlanHeader);
     pl->item_off = pl->var_off + static_cast<uint64_t>(nvars) * sizeof(PlanVar);
@@ -171,7 +180,7 @@ size_t omc_packed_bytes(omc_format f, uint64_t n) {
 
 size_t omc_compress_workspace_bytes(uint64_t n) {
     if (n == 0 || n > kMaxElems) return 0;
-    return static_cast<size_t>((n + kChunkElems - 1) / kChunkElems) * sizeof(Partial);
+    return static_cast<size_t>((n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk + 1) * sizeof(Partial);
 }
 
 omc_status omc_compress(const float *v, uint64_t n, omc_format f, int use_pvt, void *codes, float *sb,
@@ -241,22 +250,37 @@ omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_h
         } else {
             bytes = 4 * v.n;
         }
-        d.nitems = static_cast<uint32_t>((v.n + kChunkElems - 1) / kChunkElems);
+        d.first_item = kNoItem;
+        d.nitems = 0;
+        d.tail_item = kNoItem;
         arena_bytes = std::max(arena_bytes, v.data_offset + bytes);
         aux_elems = std::max(aux_elems, v.aux_offset + v.n);
     }
     uint32_t next = 0;
     for (uint32_t gi = 0; gi < pl.ngroups; ++gi) {
-        const uint32_t bits = pl.group_bits[gi];
-        groups[gi].bits = bits;
-        groups[gi].first_item = next;
+        PlanGroup g = pl.groups[gi];
+        g.first_item = next;
         for (uint32_t i = 0; i < nvars; ++i) {
-            const bool q = (vars_host[i].flags & OMC_VAR_QUANTIZED) != 0;
-            if (bits == 0 ? q : (!q || pv[i].fp.bits != bits)) continue;
-            pv[i].first_item = next;
-            for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
+            const omc_var &v = vars_host[i];
+            const bool q = (v.flags & OMC_VAR_QUANTIZED) != 0;
+            if (g.kind == kGroupFull) {
+                if (!q || pv[i].fp.bits != g.bits || pv[i].fp.wide != g.wide || v.n < kTileElems) continue;
+                pv[i].first_item = next;
+                pv[i].nitems = static_cast<uint32_t>((v.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
+                for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
+            } else if (g.kind == kGroupTail) {
+                if (!q || pv[i].fp.wide != g.wide || v.n % kTileElems == 0) continue;
+                pv[i].tail_item = next;
+                items[next++] = PlanItem{i, 0};
+            } else {
+                if (q) continue;
+                pv[i].first_item = next;
+                pv[i].nitems = static_cast<uint32_t>((v.n + kChunkElems - 1) / kChunkElems);
+                for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
+            }
         }
-        groups[gi].nitems = next - groups[gi].first_item;
+        g.nitems = next - g.first_item;
+        groups[gi] = g;
     }
     ph->magic = kPlanMagic;
     ph->version = kPlanVersion;
@@ -290,10 +314,25 @@ uint64_t omc_plan_aux_elems(const void *plan_host) {
     return ph ? ph->aux_elems : 0;
 }
 
-omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const void *plan_host,
-                                      const void *plan_dev, float *sb_table, const float *grads,
-                                      float *state0, float *state1, uint64_t aux_elems,
-                                      const omc_opt *opt, void *ws, size_t ws_bytes, void *stream) {
+static uint32_t plan_launches(const PlanHeader *ph) {
+    const uint8_t *b = reinterpret_cast<const uint8_t *>(ph);
+    const PlanGroup *groups = reinterpret_cast<const PlanGroup *>(b + ph->group_off);
+    uint32_t k = ph->nquant > 0 ? 1u : 0u;
+    for (uint32_t g = 0; g < ph->ngroups; ++g)
+        if (groups[g].nitems > 0) ++k;
+    return k;
+}
+
+uint32_t omc_plan_launches(const void *plan_host) {
+    const PlanHeader *ph = plan_check(plan_host);
+    return ph ? plan_launches(ph) : 0;
+}
+
+omc_status omc_step_update_recompress_events(void *arena, size_t arena_bytes, const void *plan_host,
+                                             const void *plan_dev, float *sb_table, const float *grads,
+                                             float *state0, float *state1, uint64_t aux_elems,
+                                             const omc_opt *opt, void *ws, size_t ws_bytes, void *stream,
+                                             void *const *events, uint32_t nevents) {
     if (!arena || !plan_host || !plan_dev || !sb_table || !grads || !opt) return OMC_ERR_NULL;
     const PlanHeader *ph = plan_check(plan_host);
     if (!ph) return OMC_ERR_PLAN;
@@ -308,9 +347,24 @@ omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const voi
     if (opt->kind == OMC_ADAM && !aligned16(state1)) return OMC_ERR_ALIGN;
     if (!ws || ws_bytes < ph->ws_bytes) return OMC_ERR_WORKSPACE;
     if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    if (events) {
+        const uint32_t need = 2 * plan_launches(ph);
+        if (nevents < need) return OMC_ERR_SIZE;
+        for (uint32_t i = 0; i < need; ++i)
+            if (!events[i]) return OMC_ERR_NULL;
+    }
     const int rc = launch_step(arena, ph, plan_dev, sb_table, grads, state0, state1, *opt,
-                               static_cast<Partial *>(ws), stream);
+                               static_cast<Partial *>(ws), stream, events);
     return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const void *plan_host,
+                                      const void *plan_dev, float *sb_table, const float *grads,
+                                      float *state0, float *state1, uint64_t aux_elems,
+                                      const omc_opt *opt, void *ws, size_t ws_bytes, void *stream) {
+    return omc_step_update_recompress_events(arena, arena_bytes, plan_host, plan_dev, sb_table, grads,
+                                             state0, state1, aux_elems, opt, ws, ws_bytes, stream,
+                                             nullptr, 0);
 }
 
 size_t omc_dequant_gemm_workspace_bytes(uint32_t M) {

@@ -44,7 +44,7 @@ static_assert(sizeof(Partial) == 48, "Partial layout");
 
 // ---- plan blob ---------------------------------------------------------------------------
 constexpr uint32_t kPlanMagic = 0x434d4f50u;  // "POMC"
-constexpr uint32_t kPlanVersion = 1;
+constexpr uint32_t kPlanVersion = 2;
 
 struct PlanHeader {
     uint32_t magic, version;
@@ -61,9 +61,9 @@ struct PlanVar {
     uint64_t data_offset, aux_offset, n;
     uint64_t total_dwords;   // packed buffer length in dwords (multiple of 4); 0 for fp32
     uint32_t flags;          // OMC_VAR_*
-    uint32_t first_item;     // index of this variable's first work item / partial
-    uint32_t nitems;
-    uint32_t pad;
+    uint32_t first_item;     // index of this variable's first full-tile work item / partial
+    uint32_t nitems;         // number of those (0 when n < 2048)
+    uint32_t tail_item;      // index of the ragged-tail item / partial, kNoItem if n % 2048 == 0
     FmtParams fp;
 };
 
@@ -72,8 +72,14 @@ struct PlanItem {
     uint32_t chunk;
 };
 
+constexpr uint32_t kNoItem = 0xffffffffu;
+
+// One kernel launch: a run of work items that the same kernel instance serves.
+enum GroupKind : uint32_t { kGroupFull = 0, kGroupTail = 1, kGroupFp32 = 2 };
 struct PlanGroup {
-    uint32_t bits;           // code width of the group's variables; 0 = fp32 variables
+    uint32_t kind;           // GroupKind
+    uint32_t bits;           // kGroupFull: code width of the group's variables
+    uint32_t wide;           // kGroupFull / kGroupTail: FmtParams::wide of the group's variables
     uint32_t first_item;
     uint32_t nitems;
     uint32_t pad;
@@ -96,7 +102,7 @@ int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes,
 int launch_decompress(const void *codes, const VarArgs &va, const float *sb, float *out, void *stream);
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table,
                 const float *grads, float *state0, float *state1, const omc_opt &opt, Partial *ws,
-                void *stream);
+                void *stream, void *const *events);
 int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb,
                         float *C, uint32_t M, uint32_t N, uint32_t K, float *rowsum, void *stream);
 

@@ -9,8 +9,8 @@ template <int MODE>
 __global__ __launch_bounds__(64) void step_fp32_kernel(StepArgs sa) {
     const PlanItem *items = reinterpret_cast<const PlanItem *>(sa.plan + sa.item_off);
     const PlanVar *vars = reinterpret_cast<const PlanVar *>(sa.plan + sa.var_off);
-    const PlanItem it = items[sa.first_item + blockIdx.x];
-    const PlanVar &pv = vars[it.var];
+    const PlanItem it = to_scalar_regs(items[sa.first_item + blockIdx.x]);
+    const PlanVar pv = to_scalar_regs(vars[it.var]);
     const uint32_t lane = threadIdx.x;
     float *__restrict__ w = reinterpret_cast<float *>(sa.arena + pv.data_offset);
     const float *__restrict__ g = sa.grads + pv.aux_offset;
@@ -65,6 +65,34 @@ __global__ __launch_bounds__(64) void step_fp32_kernel(StepArgs sa) {
     }
 }
 
+// Ragged tails of quantized variables, one wave each (code width read from the plan).
+template <int MODE, bool WIDE>
+__global__ __launch_bounds__(64) void step_tail_kernel(StepArgs sa) {
+    const PlanItem *items = reinterpret_cast<const PlanItem *>(sa.plan + sa.item_off);
+    const PlanVar *vars = reinterpret_cast<const PlanVar *>(sa.plan + sa.var_off);
+    const uint32_t item = sa.first_item + blockIdx.x;
+    const PlanItem it = to_scalar_regs(items[item]);
+    const PlanVar pv = to_scalar_regs(vars[it.var]);
+    TileArgs a{};
+    a.codes = reinterpret_cast<uint32_t *>(sa.arena + pv.data_offset);
+    a.total_dwords = pv.total_dwords;
+    a.grad = sa.grads + pv.aux_offset;
+    a.st0 = sa.st0 ? sa.st0 + pv.aux_offset : nullptr;
+    a.st1 = sa.st1 ? sa.st1 + pv.aux_offset : nullptr;
+    a.n = pv.n;
+    a.s = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var)]);
+    a.b = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var) + 1]);
+    const FmtParams fp = pv.fp;
+    do_tail<MODE, WIDE>(a, fp, sa.oc, sa.ws + item);
+}
+
+template <int MODE>
+static int launch_tail(bool wide, const StepArgs &sa, hipStream_t st) {
+    if (wide) step_tail_kernel<MODE, true><<<dim3(sa.nitems), dim3(64), 0, st>>>(sa);
+    else step_tail_kernel<MODE, false><<<dim3(sa.nitems), dim3(64), 0, st>>>(sa);
+    return static_cast<int>(hipGetLastError());
+}
+
 // One wave per variable: new (s, b) of every quantized variable from its chunks' partials.
 __global__ __launch_bounds__(64) void finalize_plan_kernel(const uint8_t *__restrict__ plan, uint64_t var_off,
                                                            const Partial *__restrict__ ws,
@@ -72,13 +100,20 @@ __global__ __launch_bounds__(64) void finalize_plan_kernel(const uint8_t *__rest
     const PlanVar *vars = reinterpret_cast<const PlanVar *>(plan + var_off);
     const PlanVar &pv = vars[blockIdx.x];
     if (!(pv.flags & OMC_VAR_QUANTIZED)) return;
-    finalize_variable(ws + pv.first_item, pv.nitems, pv.n, !(pv.flags & OMC_VAR_NO_PVT),
-                      sb_table + 2 * static_cast<uint64_t>(blockIdx.x));
+    finalize_variable(pv.nitems ? ws + pv.first_item : ws, pv.nitems,
+                      pv.tail_item != kNoItem ? ws + pv.tail_item : nullptr, pv.n,
+                      !(pv.flags & OMC_VAR_NO_PVT), sb_table + 2 * static_cast<uint64_t>(blockIdx.x));
 }
 
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table, const float *grads,
-                float *state0, float *state1, const omc_opt &opt, Partial *ws, void *stream) {
+                float *state0, float *state1, const omc_opt &opt, Partial *ws, void *stream,
+                void *const *events) {
     hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t launch = 0;
+    auto mark = [&](uint32_t which) -> int {   // optional caller-owned events around each launch
+        if (!events) return 0;
+        return static_cast<int>(hipEventRecord(static_cast<hipEvent_t>(events[2 * launch + which]), st));
+    };
     const uint8_t *ph_bytes = reinterpret_cast<const uint8_t *>(ph);
     const PlanGroup *groups = reinterpret_cast<const PlanGroup *>(ph_bytes + ph->group_off);
     StepArgs sa{};
@@ -98,24 +133,36 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
         if (g.nitems == 0) continue;
         sa.first_item = g.first_item;
         sa.nitems = g.nitems;
-        int rc;
-        if (g.bits == 0) {
+        int rc = mark(0);
+        if (rc != 0) return rc;
+        if (g.kind == kGroupTail) {
+            if (opt.kind == OMC_SGD) rc = launch_tail<kStepSgd>(g.wide != 0, sa, st);
+            else if (opt.kind == OMC_MOMENTUM) rc = launch_tail<kStepMomentum>(g.wide != 0, sa, st);
+            else rc = launch_tail<kStepAdam>(g.wide != 0, sa, st);
+        } else if (g.kind == kGroupFp32) {
             if (opt.kind == OMC_SGD) step_fp32_kernel<kStepSgd><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             else if (opt.kind == OMC_MOMENTUM) step_fp32_kernel<kStepMomentum><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             else step_fp32_kernel<kStepAdam><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             rc = static_cast<int>(hipGetLastError());
         } else if (opt.kind == OMC_SGD) {
-            rc = launch_step_group_sgd(g.bits, sa, st);
+            rc = launch_step_group_sgd(g.bits, g.wide != 0, sa, st);
         } else if (opt.kind == OMC_MOMENTUM) {
-            rc = launch_step_group_momentum(g.bits, sa, st);
+            rc = launch_step_group_momentum(g.bits, g.wide != 0, sa, st);
         } else {
-            rc = launch_step_group_adam(g.bits, sa, st);
+            rc = launch_step_group_adam(g.bits, g.wide != 0, sa, st);
         }
         if (rc != 0) return rc;
+        rc = mark(1);
+        if (rc != 0) return rc;
+        ++launch;
     }
     if (ph->nquant > 0) {
+        int rc = mark(0);
+        if (rc != 0) return rc;
         finalize_plan_kernel<<<dim3(ph->nvars), dim3(64), 0, st>>>(sa.plan, ph->var_off, ws, sb_table);
-        return static_cast<int>(hipGetLastError());
+        rc = static_cast<int>(hipGetLastError());
+        if (rc != 0) return rc;
+        return mark(1);
     }
     return 0;
 }

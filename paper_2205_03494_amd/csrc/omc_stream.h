@@ -1,12 +1,16 @@
 // Device side of the streaming kernels: unpack / decode / transform / update / round / pack
-// for one 2048-element tile per wavefront (paper Sec. 2.1 cycle, Sec. 2.2 format, Sec. 2.3 fit).
+// (paper Sec. 2.1 cycle, Sec. 2.2 format, Sec. 2.3 fit).
 //
-// Data movement.  Every global access is coalesced: a wave reads or writes whole contiguous
-// runs (packed codes as dwords, fp32 streams as 16-byte pieces).  Each lane, however, works on
-// 32 *consecutive* elements, because 32 codes of any width B are exactly B dwords: all shift
-// amounts are then compile-time constants and no dword is shared between lanes.  The change of
-// ownership between the two layouts goes through LDS (one wave, one private LDS region), with
-// padding / XOR swizzles chosen so that both sides are free of bank conflicts.
+// Work split.  A variable of n elements is cut into full tiles of 2048 elements (64 lanes x 32)
+// plus, when n is not a multiple of 2048, one ragged tail.  Full tiles are processed by kernels
+// templated on the code width B, with no bounds checks at all; tails by a small generic kernel.
+//
+// Data movement of the full-tile path.  Every global access is coalesced and 16 bytes per lane.
+// Each lane, however, works on 32 *consecutive* elements, because 32 codes of any width B are
+// exactly B dwords: all shift amounts are then compile-time constants and no dword is shared
+// between lanes.  The change of ownership between the two layouts goes through LDS (one wave,
+// one private LDS region), with padding / XOR swizzles chosen so that both sides are free of
+// bank conflicts.
 //
 // Arithmetic.  fp32 operations are written one per statement and the file is compiled with
 // contraction off, so that each is rounded on its own.  Rounding to the format is done in the
@@ -20,11 +24,57 @@
 
 namespace omc {
 
+// Native 16-byte vectors (first-class values for the optimizer, unlike the HIP struct types).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 enum Mode : int { kCompress = 0, kDecompress = 1, kStepSgd = 2, kStepMomentum = 3, kStepAdam = 4 };
 
 struct OptConst {
     float lr, momentum, beta1, beta2, eps, omb1, omb2, bc1, bc2;
 };
+
+// Per-mode tuning: occupancy target (waves per SIMD; bounds the register budget the compiler may
+// use) and whether the next tile's loads are issued before the current tile is computed.
+#ifndef OMC_TUNE_WAVES_LIGHT
+#define OMC_TUNE_WAVES_LIGHT 4
+#endif
+#ifndef OMC_TUNE_SCHED_GROUP
+#define OMC_TUNE_SCHED_GROUP 4
+#endif
+#ifndef OMC_TUNE_PREFETCH
+#define OMC_TUNE_PREFETCH 1
+#endif
+template <int MODE, int B>
+struct Tuning {
+    static constexpr int light = (B <= 12) ? OMC_TUNE_WAVES_LIGHT : (OMC_TUNE_WAVES_LIGHT > 3 ? 3 : OMC_TUNE_WAVES_LIGHT);
+    static constexpr int waves = (MODE == kStepAdam) ? 2 : (MODE == kStepMomentum) ? 3 : light;
+    static constexpr bool prefetch = (OMC_TUNE_PREFETCH != 0) && MODE <= kStepSgd;  // heavier modes lack the registers
+};
+
+// A value that is the same in every lane (read through a vector load, e.g. from the plan) moved
+// to scalar registers, so that it does not occupy a vector register per field.
+template <typename T>
+__device__ __forceinline__ T to_scalar_regs(const T &v) {
+    static_assert(sizeof(T) % 4 == 0, "dword-sized types only");
+    uint32_t tmp[sizeof(T) / 4];
+    __builtin_memcpy(tmp, &v, sizeof(T));
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(T) / 4; ++i) tmp[i] = __builtin_amdgcn_readfirstlane(tmp[i]);
+    T out;
+    __builtin_memcpy(&out, tmp, sizeof(T));
+    return out;
+}
+
+// An empty, ordered asm statement that "modifies" a register.  Work that produces the value must
+// precede it and work that consumes it must follow, and such statements keep their program order:
+// placed at the start and end of a group of elements they keep the compiler from hoisting every
+// element's arithmetic ahead of the (serial) fp64 accumulation, which would hold two live
+// registers per element for the whole tile.
+template <typename T>
+__device__ __forceinline__ void pin(T &v) {
+    asm volatile("" : "+v"(v));
+}
 
 // ---- LDS layouts ----------------------------------------------------------------------------
 // Packed tile of 64*B dwords.  Lane l owns dwords [l*B, l*B+B).  With B = 2^t * odd, a stride of
@@ -56,94 +106,90 @@ __device__ __forceinline__ uint32_t piece_slot_own(uint32_t k, uint32_t lane) {
 
 __device__ __forceinline__ void lds_fence() { __syncthreads(); }  // one wave per workgroup
 
-// ---- global <-> registers, coalesced ---------------------------------------------------------
-template <bool FULL>
-__device__ __forceinline__ void load_f32_pieces(const float *__restrict__ src, uint32_t valid,
-                                                uint32_t lane, float4 (&g)[8]) {
+// ---- global <-> registers, coalesced, full tiles only --------------------------------------------
+__device__ __forceinline__ void load_f32_pieces(const float *__restrict__ src, uint32_t lane, f32x4 (&g)[8]) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        uint32_t e = (j * 64u + lane) * 4u;
-        if (FULL) {
-            g[j] = *reinterpret_cast<const float4 *>(src + e);
-        } else {
-            g[j].x = (e + 0 < valid) ? src[e + 0] : 0.0f;
-            g[j].y = (e + 1 < valid) ? src[e + 1] : 0.0f;
-            g[j].z = (e + 2 < valid) ? src[e + 2] : 0.0f;
-            g[j].w = (e + 3 < valid) ? src[e + 3] : 0.0f;
-        }
-    }
+    for (int j = 0; j < 8; ++j) g[j] = reinterpret_cast<const f32x4 *>(src)[j * 64u + lane];
 }
 
-template <bool FULL>
-__device__ __forceinline__ void store_f32_pieces(float *__restrict__ dst, uint32_t valid,
-                                                 uint32_t lane, const float4 (&g)[8]) {
+__device__ __forceinline__ void store_f32_pieces(float *__restrict__ dst, uint32_t lane, const f32x4 (&g)[8]) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        uint32_t e = (j * 64u + lane) * 4u;
-        if (FULL) {
-            *reinterpret_cast<float4 *>(dst + e) = g[j];
-        } else {
-            if (e + 0 < valid) dst[e + 0] = g[j].x;
-            if (e + 1 < valid) dst[e + 1] = g[j].y;
-            if (e + 2 < valid) dst[e + 2] = g[j].z;
-            if (e + 3 < valid) dst[e + 3] = g[j].w;
-        }
-    }
+    for (int j = 0; j < 8; ++j) reinterpret_cast<f32x4 *>(dst)[j * 64u + lane] = g[j];
 }
 
 // coalesced pieces -> each lane's 32 consecutive floats
-__device__ __forceinline__ void pieces_to_lanes(const float4 (&g)[8], float (&r)[32], uint32_t *lds,
+__device__ __forceinline__ void pieces_to_lanes(const f32x4 (&g)[8], float (&r)[32], uint32_t *lds,
                                                 uint32_t lane) {
-    float4 *l4 = reinterpret_cast<float4 *>(lds);
+    f32x4 *l4 = reinterpret_cast<f32x4 *>(lds);
 #pragma unroll
     for (int j = 0; j < 8; ++j) l4[piece_slot_flat(j, lane)] = g[j];
     lds_fence();
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-        float4 t = l4[piece_slot_own(k, lane)];
+        f32x4 t = l4[piece_slot_own(k, lane)];
         r[4 * k + 0] = t.x; r[4 * k + 1] = t.y; r[4 * k + 2] = t.z; r[4 * k + 3] = t.w;
     }
     lds_fence();
 }
 
 // each lane's 32 consecutive floats -> coalesced pieces
-__device__ __forceinline__ void lanes_to_pieces(const float (&r)[32], float4 (&g)[8], uint32_t *lds,
+__device__ __forceinline__ void lanes_to_pieces(const float (&r)[32], f32x4 (&g)[8], uint32_t *lds,
                                                 uint32_t lane) {
-    float4 *l4 = reinterpret_cast<float4 *>(lds);
+    f32x4 *l4 = reinterpret_cast<f32x4 *>(lds);
 #pragma unroll
     for (int k = 0; k < 8; ++k)
-        l4[piece_slot_own(k, lane)] = make_float4(r[4 * k + 0], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]);
+        l4[piece_slot_own(k, lane)] = f32x4{r[4 * k + 0], r[4 * k + 1], r[4 * k + 2], r[4 * k + 3]};
     lds_fence();
 #pragma unroll
     for (int j = 0; j < 8; ++j) g[j] = l4[piece_slot_flat(j, lane)];
     lds_fence();
 }
 
-template <int B, bool FULL>
-__device__ __forceinline__ void load_code_dwords(const uint32_t *__restrict__ src, uint64_t dwords_left,
-                                                 uint32_t lane, uint32_t (&cw)[B]) {
-#pragma unroll
-    for (int j = 0; j < B; ++j) {
-        uint32_t p = j * 64u + lane;
-        cw[j] = (FULL || p < dwords_left) ? src[p] : 0u;
+// Packed tile as 16-byte pieces: 16*B of them, piece q = 64 j + lane in round j.
+template <int B>
+struct CodePieces {
+    static constexpr int total = 16 * B;
+    static constexpr int rounds = (total + 63) / 64;
+    __device__ static __forceinline__ bool in_tile(int j, uint32_t q) {
+        return (j * 64 + 64 <= total) || q < static_cast<uint32_t>(total);
     }
-}
+};
 
-template <int B, bool FULL>
-__device__ __forceinline__ void store_code_dwords(uint32_t *__restrict__ dst, uint64_t dwords_left,
-                                                  uint32_t lane, const uint32_t (&cw)[B]) {
+template <int B>
+__device__ __forceinline__ void load_code_pieces(const uint32_t *__restrict__ src, uint32_t lane,
+                                                 u32x4 (&cq)[CodePieces<B>::rounds]) {
 #pragma unroll
-    for (int j = 0; j < B; ++j) {
-        uint32_t p = j * 64u + lane;
-        if (FULL || p < dwords_left) dst[p] = cw[j];
+    for (int j = 0; j < CodePieces<B>::rounds; ++j) {
+        const uint32_t q = j * 64u + lane;
+        if (CodePieces<B>::in_tile(j, q))
+            cq[j] = reinterpret_cast<const u32x4 *>(src)[q];
+        else
+            cq[j] = u32x4{0u, 0u, 0u, 0u};
     }
 }
 
 template <int B>
-__device__ __forceinline__ void code_dwords_to_lanes(const uint32_t (&cw)[B], uint32_t (&w)[B],
+__device__ __forceinline__ void store_code_pieces(uint32_t *__restrict__ dst, uint32_t lane,
+                                                  const u32x4 (&cq)[CodePieces<B>::rounds]) {
+#pragma unroll
+    for (int j = 0; j < CodePieces<B>::rounds; ++j) {
+        const uint32_t q = j * 64u + lane;
+        if (CodePieces<B>::in_tile(j, q)) reinterpret_cast<u32x4 *>(dst)[q] = cq[j];
+    }
+}
+
+// coalesced pieces -> each lane's B consecutive dwords
+template <int B>
+__device__ __forceinline__ void code_pieces_to_lanes(const u32x4 (&cq)[CodePieces<B>::rounds], uint32_t (&w)[B],
                                                      uint32_t *lds, uint32_t lane) {
 #pragma unroll
-    for (int j = 0; j < B; ++j) lds[CodeLds<B>::flat(j * 64u + lane)] = cw[j];
+    for (int j = 0; j < CodePieces<B>::rounds; ++j) {
+        const uint32_t q = j * 64u + lane;
+        if (CodePieces<B>::in_tile(j, q)) {
+            const uint32_t a = CodeLds<B>::flat(4u * q);   // a piece never straddles a spare dword
+            lds[a + 0] = cq[j].x; lds[a + 1] = cq[j].y; lds[a + 2] = cq[j].z; lds[a + 3] = cq[j].w;
+        }
+    }
     lds_fence();
     const uint32_t base = CodeLds<B>::lane_base(lane);
 #pragma unroll
@@ -151,15 +197,24 @@ __device__ __forceinline__ void code_dwords_to_lanes(const uint32_t (&cw)[B], ui
     lds_fence();
 }
 
+// each lane's B consecutive dwords -> coalesced pieces
 template <int B>
-__device__ __forceinline__ void lanes_to_code_dwords(const uint32_t (&o)[B], uint32_t (&cw)[B],
+__device__ __forceinline__ void lanes_to_code_pieces(const uint32_t (&o)[B], u32x4 (&cq)[CodePieces<B>::rounds],
                                                      uint32_t *lds, uint32_t lane) {
     const uint32_t base = CodeLds<B>::lane_base(lane);
 #pragma unroll
     for (int j = 0; j < B; ++j) lds[base + j] = o[j];
     lds_fence();
 #pragma unroll
-    for (int j = 0; j < B; ++j) cw[j] = lds[CodeLds<B>::flat(j * 64u + lane)];
+    for (int j = 0; j < CodePieces<B>::rounds; ++j) {
+        const uint32_t q = j * 64u + lane;
+        if (CodePieces<B>::in_tile(j, q)) {
+            const uint32_t a = CodeLds<B>::flat(4u * q);
+            cq[j] = u32x4{lds[a + 0], lds[a + 1], lds[a + 2], lds[a + 3]};
+        } else {
+            cq[j] = u32x4{0u, 0u, 0u, 0u};
+        }
+    }
     lds_fence();
 }
 
@@ -183,6 +238,7 @@ __device__ __forceinline__ float decode_top(uint32_t t, const FmtParams &fp) {
 }
 
 // Nearest code to x (ties to even significand, saturating) and the value tq of that code.
+template <bool WIDE>
 __device__ __forceinline__ void encode(float x, const FmtParams &fp, uint32_t &code, float &tq) {
     const uint32_t xb = __float_as_uint(x);
     // |x| clamped to the largest magnitude, compared as integers so that Inf and NaN saturate too
@@ -190,7 +246,7 @@ __device__ __forceinline__ void encode(float x, const FmtParams &fp, uint32_t &c
     const float a = __uint_as_float(ab);
     const uint32_t exb = max(ab, fp.min_norm_bits) & 0x7f800000u;  // binade of a, at least the first normal one
     float r;
-    if (fp.wide) {
+    if (WIDE) {
         const int k = static_cast<int>(exb >> 23) - fp.exp_adj;    // ulp = 2^k
         r = ldexpf(rintf(ldexpf(a, -k)), k);
     } else {
@@ -246,11 +302,14 @@ __device__ __forceinline__ float apply_update(float w, float g, float &m, float 
 // ---- fit accumulators -----------------------------------------------------------------------------
 struct FitAcc {
     double sV, sT, sVT, sTT;
-    float tmin, tmax;
+    uint32_t t0;     // bit pattern of the first decompressed value this lane saw
+    uint32_t diff;   // OR of (bits ^ t0) over all values this lane saw
+    bool have;
     __device__ __forceinline__ void clear() {
         sV = sT = sVT = sTT = 0.0;
-        tmin = __builtin_huge_valf();
-        tmax = -__builtin_huge_valf();
+        t0 = 0u;
+        diff = 0u;
+        have = false;
     }
     __device__ __forceinline__ void add(float x, float tq) {
         const double dx = static_cast<double>(x), dt = static_cast<double>(tq);
@@ -258,12 +317,26 @@ struct FitAcc {
         sT += dt;
         sVT = fma(dx, dt, sVT);   // the product of two fp32 values is exact in fp64
         sTT = fma(dt, dt, sTT);
-        tmin = fminf(tmin, tq);
-        tmax = fmaxf(tmax, tq);
+        diff |= __float_as_uint(tq) ^ t0;
+    }
+    __device__ __forceinline__ void seed(float tq) {   // before the first add
+        if (!have) t0 = __float_as_uint(tq);
+        have = true;
+    }
+    // Range of the decompressed values as (min, max): exact when all of the lane's values are
+    // equal (+0 and -0 count as equal), otherwise (-inf, +inf), which is all the fit needs.
+    __device__ __forceinline__ void lane_range(float &tmin, float &tmax) const {
+        const float inf = __builtin_huge_valf();
+        if (!have) { tmin = inf; tmax = -inf; return; }
+        const bool equal = diff == 0u || (diff == 0x80000000u && (t0 & 0x7fffffffu) == 0u);
+        tmin = equal ? __uint_as_float(t0) : -inf;
+        tmax = equal ? __uint_as_float(t0) : inf;
     }
     // butterfly over the 64 lanes; every lane ends with the same totals, in an order that does
-    // not depend on scheduling
-    __device__ __forceinline__ void wave_reduce() {
+    // not depend on scheduling; lane 0 stores them
+    __device__ __forceinline__ void reduce_and_store(Partial *out) {
+        float tmin, tmax;
+        lane_range(tmin, tmax);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             sV += __shfl_xor(sV, off);
@@ -273,12 +346,18 @@ struct FitAcc {
             tmin = fminf(tmin, __shfl_xor(tmin, off));
             tmax = fmaxf(tmax, __shfl_xor(tmax, off));
         }
+        if (threadIdx.x == 0) {
+            Partial p;
+            p.sV = sV; p.sT = sT; p.sVT = sVT; p.sTT = sTT;
+            p.tmin = tmin; p.tmax = tmax; p.pad[0] = p.pad[1] = 0;
+            *out = p;
+        }
     }
 };
 
-// ---- one tile ---------------------------------------------------------------------------------------
+// ---- one variable as the kernels see it ---------------------------------------------------------------
 struct TileArgs {
-    uint32_t *codes;          // variable's packed stream (nullptr for fp32 input of kCompress: unused)
+    uint32_t *codes;          // variable's packed stream
     uint64_t total_dwords;    // its length in dwords
     const float *vin;         // kCompress: values to compress
     float *vout;              // kDecompress: output
@@ -288,37 +367,67 @@ struct TileArgs {
     uint64_t n;
 };
 
-template <int B, int MODE, bool FULL>
-__device__ __forceinline__ void do_tile(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
-                                        uint64_t e0, uint32_t valid, uint32_t lane, uint32_t *lds,
-                                        FitAcc &acc) {
+// Registers that receive a tile's global loads (coalesced layout).
+template <int B, int MODE>
+struct Stage {
+    u32x4 cq[CodePieces<B>::rounds];
+    f32x4 gq[8], mq[8], vq[8];
+};
+
+template <int B, int MODE>
+__device__ __forceinline__ void issue_loads(const TileArgs &a, uint64_t e0, uint32_t lane, Stage<B, MODE> &st) {
     const uint64_t dw0 = (e0 >> 5) * B;                   // first dword of the tile
-    const uint64_t dw_left = a.total_dwords - dw0;
+    if (MODE != kCompress) load_code_pieces<B>(a.codes + dw0, lane, st.cq);
+    if (MODE == kCompress) load_f32_pieces(a.vin + e0, lane, st.gq);
+    if (MODE >= kStepSgd) load_f32_pieces(a.grad + e0, lane, st.gq);
+    if (MODE >= kStepMomentum) load_f32_pieces(a.st0 + e0, lane, st.mq);
+    if (MODE == kStepAdam) load_f32_pieces(a.st1 + e0, lane, st.vq);
+}
 
-    // 1. all global loads first, so that they are in flight together
-    uint32_t cw[B];
-    float4 gq[8], mq[8], vq[8];
-    if (MODE != kCompress) load_code_dwords<B, FULL>(a.codes + dw0, dw_left, lane, cw);
-    if (MODE == kCompress) load_f32_pieces<FULL>(a.vin + e0, valid, lane, gq);
-    if (MODE >= kStepSgd) load_f32_pieces<FULL>(a.grad + e0, valid, lane, gq);
-    if (MODE >= kStepMomentum) load_f32_pieces<FULL>(a.st0 + e0, valid, lane, mq);
-    if (MODE == kStepAdam) load_f32_pieces<FULL>(a.st1 + e0, valid, lane, vq);
-
-    // 2. hand every lane its 32 consecutive elements
+// Everything after the loads of the full tile at e0 have been issued into `st`.  When PREFETCH,
+// the loads of the next tile are issued into the same registers as soon as they are free, so
+// that they are in flight while this tile is computed.
+template <int B, int MODE, bool WIDE, bool PREFETCH>
+__device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
+                                            uint64_t e0, uint32_t lane, uint32_t *lds, Stage<B, MODE> &st,
+                                            FitAcc &acc) {
+    // hand every lane its 32 consecutive elements
     uint32_t w[B];
     float rg[32], rm[32], rv[32];
-    if (MODE != kCompress) code_dwords_to_lanes<B>(cw, w, lds, lane);
-    if (MODE == kCompress || MODE >= kStepSgd) pieces_to_lanes(gq, rg, lds, lane);
-    if (MODE >= kStepMomentum) pieces_to_lanes(mq, rm, lds, lane);
-    if (MODE == kStepAdam) pieces_to_lanes(vq, rv, lds, lane);
+    if (MODE != kCompress) code_pieces_to_lanes<B>(st.cq, w, lds, lane);
+    if (MODE == kCompress || MODE >= kStepSgd) pieces_to_lanes(st.gq, rg, lds, lane);
+    if (MODE >= kStepMomentum) pieces_to_lanes(st.mq, rm, lds, lane);
+    if (MODE == kStepAdam) pieces_to_lanes(st.vq, rv, lds, lane);
 
-    // 3. the cycle, element by element
+    if (PREFETCH) issue_loads<B, MODE>(a, e0 + kTileElems, lane, st);
+
+    // the cycle, element by element
     uint32_t o[B];
 #pragma unroll
     for (int j = 0; j < B; ++j) o[j] = 0u;
-    const uint32_t first = lane * kLaneElems;
 #pragma unroll
     for (int i = 0; i < kLaneElems; ++i) {
+#if OMC_TUNE_SCHED_GROUP > 0
+        if (i % OMC_TUNE_SCHED_GROUP == 0) {              // group start: pin the group's inputs
+            constexpr int G = OMC_TUNE_SCHED_GROUP;
+            if (MODE != kCompress) {
+#pragma unroll
+                for (int j = (i * B) >> 5; j <= (((i + G) * B - 1) >> 5); ++j) pin(w[j]);
+            }
+            if (MODE != kDecompress) {
+#pragma unroll
+                for (int e = i; e < i + G; ++e) pin(rg[e]);
+            }
+            if (MODE >= kStepMomentum) {
+#pragma unroll
+                for (int e = i; e < i + G; ++e) pin(rm[e]);
+            }
+            if (MODE == kStepAdam) {
+#pragma unroll
+                for (int e = i; e < i + G; ++e) pin(rv[e]);
+            }
+        }
+#endif
         float x;
         if (MODE != kCompress) {
             const float vt = decode_top(code_at_top<B>(w, i), fp);
@@ -336,59 +445,142 @@ __device__ __forceinline__ void do_tile(const TileArgs &a, const FmtParams &fp, 
             x = apply_update<MODE>(x, rg[i], MODE >= kStepMomentum ? rm[i] : mdummy,
                                    MODE == kStepAdam ? rv[i] : vdummy, oc);
         }
-        const bool live = FULL || (first + i < valid);
-        if (!live) x = 0.0f;                             // padding elements pack as zero bits
         uint32_t code;
         float tq;
-        encode(x, fp, code, tq);
+        encode<WIDE>(x, fp, code, tq);
         pack_at<B>(o, i, code);
-        if (live) acc.add(x, tq);
+        if (i == 0) acc.seed(tq);
+        acc.add(x, tq);
+#if OMC_TUNE_SCHED_GROUP > 0
+        if ((i + 1) % OMC_TUNE_SCHED_GROUP == 0) {        // group end: pin what the group produced
+            constexpr int G = OMC_TUNE_SCHED_GROUP;
+            pin(acc.sV); pin(acc.sT); pin(acc.sVT); pin(acc.sTT); pin(acc.diff);
+            pin(o[((i + 1) * B - 1) >> 5]);
+            if (MODE >= kStepMomentum) {
+#pragma unroll
+                for (int e = i + 1 - G; e <= i; ++e) pin(rm[e]);
+            }
+            if (MODE == kStepAdam) {
+#pragma unroll
+                for (int e = i + 1 - G; e <= i; ++e) pin(rv[e]);
+            }
+        }
+#endif
     }
 
-    // 4. back to the coalesced layouts and out
+    // back to the coalesced layouts and out
     if (MODE == kDecompress) {
-        lanes_to_pieces(rg, gq, lds, lane);
-        store_f32_pieces<FULL>(a.vout + e0, valid, lane, gq);
+        f32x4 out[8];
+        lanes_to_pieces(rg, out, lds, lane);
+        store_f32_pieces(a.vout + e0, lane, out);
         return;
     }
     if (MODE >= kStepMomentum) {
-        lanes_to_pieces(rm, mq, lds, lane);
-        store_f32_pieces<FULL>(a.st0 + e0, valid, lane, mq);
+        f32x4 out[8];
+        lanes_to_pieces(rm, out, lds, lane);
+        store_f32_pieces(a.st0 + e0, lane, out);
     }
     if (MODE == kStepAdam) {
-        lanes_to_pieces(rv, vq, lds, lane);
-        store_f32_pieces<FULL>(a.st1 + e0, valid, lane, vq);
+        f32x4 out[8];
+        lanes_to_pieces(rv, out, lds, lane);
+        store_f32_pieces(a.st1 + e0, lane, out);
     }
-    lanes_to_code_dwords<B>(o, cw, lds, lane);
-    store_code_dwords<B, FULL>(a.codes + dw0, dw_left, lane, cw);
+    u32x4 cout[CodePieces<B>::rounds];
+    lanes_to_code_pieces<B>(o, cout, lds, lane);
+    store_code_pieces<B>(a.codes + (e0 >> 5) * B, lane, cout);
 }
 
-// One work item: up to kTilesPerChunk tiles of one variable, reduced into one Partial.
-template <int B, int MODE>
+// One work item of the full-tile kernels: tiles [chunk*kTilesPerChunk, ...) of one variable, as far
+// as full tiles go, reduced into one Partial.  The caller guarantees at least one full tile.
+template <int B, int MODE, bool WIDE>
 __device__ __forceinline__ void do_chunk(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
                                          uint32_t chunk, uint32_t *lds, Partial *partial_out) {
     const uint32_t lane = threadIdx.x;
     FitAcc acc;
     acc.clear();
-    const uint64_t begin = static_cast<uint64_t>(chunk) * kChunkElems;
-    for (int t = 0; t < kTilesPerChunk; ++t) {
+    const uint64_t first_tile = static_cast<uint64_t>(chunk) * kTilesPerChunk;
+    const uint64_t full_tiles = a.n / kTileElems;
+    const uint32_t ntiles = static_cast<uint32_t>(
+        (full_tiles - first_tile < kTilesPerChunk) ? full_tiles - first_tile : kTilesPerChunk);
+    const uint64_t begin = first_tile * kTileElems;
+    Stage<B, MODE> st;
+    issue_loads<B, MODE>(a, begin, lane, st);
+    for (uint32_t t = 0; t + 1 < ntiles; ++t) {
         const uint64_t e0 = begin + static_cast<uint64_t>(t) * kTileElems;
-        if (e0 >= a.n) break;
-        const uint64_t left = a.n - e0;
-        if (left >= kTileElems)
-            do_tile<B, MODE, true>(a, fp, oc, e0, kTileElems, lane, lds, acc);
-        else
-            do_tile<B, MODE, false>(a, fp, oc, e0, static_cast<uint32_t>(left), lane, lds, acc);
+        finish_tile<B, MODE, WIDE, Tuning<MODE, B>::prefetch>(a, fp, oc, e0, lane, lds, st, acc);
+        if (!Tuning<MODE, B>::prefetch) issue_loads<B, MODE>(a, e0 + kTileElems, lane, st);
     }
-    if (MODE != kDecompress) {
-        acc.wave_reduce();
-        if (lane == 0) {
-            Partial p;
-            p.sV = acc.sV; p.sT = acc.sT; p.sVT = acc.sVT; p.sTT = acc.sTT;
-            p.tmin = acc.tmin; p.tmax = acc.tmax; p.pad[0] = p.pad[1] = 0;
-            *partial_out = p;
+    finish_tile<B, MODE, WIDE, false>(a, fp, oc, begin + static_cast<uint64_t>(ntiles - 1) * kTileElems, lane,
+                                      lds, st, acc);
+    if (MODE != kDecompress) acc.reduce_and_store(partial_out);
+}
+
+// ---- the ragged tail of a variable ----------------------------------------------------------------------
+// Elements [e0, n) with e0 a multiple of 2048 and n - e0 < 2048, by one wave.  Same ownership as
+// a full tile (lane l: elements e0 + 32 l ...), same arithmetic, but the code width is a run-time
+// value, every access is bounds-checked and goes straight to global memory.  Lanes past the end
+// write zero bits up to the end of the (16-byte padded) packed buffer.
+template <int MODE, bool WIDE>
+__device__ __forceinline__ void do_tail(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
+                                        Partial *partial_out) {
+    const uint32_t lane = threadIdx.x;
+    const uint32_t B = fp.bits;
+    const uint64_t e0 = (a.n / kTileElems) * kTileElems;
+    const uint64_t lane_e0 = e0 + static_cast<uint64_t>(lane) * kLaneElems;
+    const uint64_t lane_dw0 = (lane_e0 >> 5) * B;            // the lane's first dword
+    const uint32_t cmask = (B == 32) ? 0xffffffffu : ((1u << B) - 1u);
+    FitAcc acc;
+    acc.clear();
+    uint64_t outbits = 0;
+    uint32_t fill = 0, outidx = 0;
+    for (uint32_t i = 0; i < kLaneElems; ++i) {
+        const uint64_t e = lane_e0 + i;
+        const bool live = e < a.n;
+        float x;
+        if (MODE != kCompress) {
+            const uint32_t bit = i * B, idx = bit >> 5, off = bit & 31u;
+            const uint64_t d = lane_dw0 + idx;
+            const uint32_t lo = (d < a.total_dwords) ? a.codes[d] : 0u;
+            const uint32_t hi = (idx + 1 < B && d + 1 < a.total_dwords) ? a.codes[d + 1] : 0u;
+            const uint64_t both = (static_cast<uint64_t>(hi) << 32) | lo;
+            const uint32_t code = static_cast<uint32_t>(both >> off) & cmask;
+            const float vt = decode_top(code << (32u - B), fp);
+            const float sv = a.s * vt;
+            x = sv + a.b;
+        } else {
+            x = live ? a.vin[e] : 0.0f;
+        }
+        if (MODE == kDecompress) {
+            if (live) a.vout[e] = x;
+            continue;
+        }
+        if (MODE >= kStepSgd) {
+            float g = live ? a.grad[e] : 0.0f;
+            float m = (MODE >= kStepMomentum && live) ? a.st0[e] : 0.0f;
+            float v = (MODE == kStepAdam && live) ? a.st1[e] : 0.0f;
+            x = apply_update<MODE>(x, g, m, v, oc);
+            if (MODE >= kStepMomentum && live) a.st0[e] = m;
+            if (MODE == kStepAdam && live) a.st1[e] = v;
+        }
+        if (!live) x = 0.0f;                                  // padding elements pack as zero bits
+        uint32_t code;
+        float tq;
+        encode<WIDE>(x, fp, code, tq);
+        if (live) {
+            acc.seed(tq);
+            acc.add(x, tq);
+        }
+        outbits |= static_cast<uint64_t>(code) << fill;
+        fill += B;
+        if (fill >= 32u) {                                    // one more dword of the lane is complete
+            const uint64_t d = lane_dw0 + outidx;
+            if (d < a.total_dwords) a.codes[d] = static_cast<uint32_t>(outbits);
+            outbits >>= 32;
+            fill -= 32u;
+            ++outidx;
         }
     }
+    if (MODE != kDecompress) acc.reduce_and_store(partial_out);
 }
 
 // ---- finalize: per-variable (s, b) from the partials (paper Sec. 2.3) -----------------------------
@@ -413,10 +605,12 @@ __device__ __forceinline__ DD dd_shfl_xor(DD a, int off) {
     return r;
 }
 
-// Called by one full wave.  Sums the variable's partials in a fixed order with compensated
-// additions, evaluates the closed form in fp64 and stores (s, b) as fp32.
+// Called by one full wave.  Sums the variable's partials (a run of `nparts` from the full-tile
+// kernels and, if `tail` is not null, one more from the tail kernel) in a fixed order with
+// compensated additions, evaluates the closed form in fp64 and stores (s, b) as fp32.
 __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ parts, uint32_t nparts,
-                                                  uint64_t n, bool use_pvt, float *sb_out) {
+                                                  const Partial *__restrict__ tail, uint64_t n, bool use_pvt,
+                                                  float *sb_out) {
     const uint32_t lane = threadIdx.x;
     if (!use_pvt) {
         if (lane == 0) { sb_out[0] = 1.0f; sb_out[1] = 0.0f; }
@@ -425,8 +619,9 @@ __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ pa
     DD sV{0, 0}, sT{0, 0}, sVT{0, 0}, sTT{0, 0};
     float tmin = __builtin_huge_valf(), tmax = -__builtin_huge_valf();
     bool finite = true;
-    for (uint32_t i = lane; i < nparts; i += 64) {
-        const Partial p = parts[i];
+    const uint32_t total = nparts + (tail ? 1u : 0u);
+    for (uint32_t i = lane; i < total; i += 64) {
+        const Partial p = (i < nparts) ? parts[i] : *tail;
         finite = finite && isfinite(p.sV);
         if (finite) {
             sV = dd_add(sV, p.sV);

@@ -71,6 +71,9 @@ _plan_arena = _sig("omc_plan_arena_bytes", C.c_size_t, _vp)
 _plan_aux = _sig("omc_plan_aux_elems", C.c_uint64, _vp)
 _step = _sig("omc_step_update_recompress", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, _vp, _vp,
              C.c_uint64, C.POINTER(omc_opt), _vp, C.c_size_t, _vp)
+_plan_launches = _sig("omc_plan_launches", C.c_uint32, _vp)
+_step_ev = _sig("omc_step_update_recompress_events", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, _vp,
+                _vp, C.c_uint64, C.POINTER(omc_opt), _vp, C.c_size_t, _vp, _vp, C.c_uint32)
 _gemm_ws = _sig("omc_dequant_gemm_workspace_bytes", C.c_size_t, C.c_uint32)
 _gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
              C.c_uint32, _vp, C.c_size_t, _vp)
@@ -78,7 +81,8 @@ _gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_ui
 EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_format_max",
             "omc_packed_bytes", "omc_compress_workspace_bytes", "omc_compress", "omc_decompress",
             "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_plan_arena_bytes",
-            "omc_plan_aux_elems", "omc_step_update_recompress", "omc_dequant_gemm_workspace_bytes",
+            "omc_plan_aux_elems", "omc_plan_launches", "omc_step_update_recompress",
+            "omc_step_update_recompress_events", "omc_dequant_gemm_workspace_bytes",
             "omc_dequant_gemm"]
 
 
@@ -167,6 +171,10 @@ class Plan:
         return _plan_ws(self.host.ctypes.data)
 
     @property
+    def launches(self) -> int:
+        return _plan_launches(self.host.ctypes.data)
+
+    @property
     def arena_bytes(self) -> int:
         return _plan_arena(self.host.ctypes.data)
 
@@ -201,6 +209,46 @@ def omc_step_update_recompress(arena: torch.Tensor, plan: Plan, sb_table: torch.
                  _ptr(plan.dev), _ptr(sb_table), _ptr(grads), _ptr(state0), _ptr(state1),
                  grads.numel(), C.byref(o), _ptr(ws), ws.numel() * ws.element_size(),
                  _stream(stream)), "omc_step_update_recompress")
+
+
+class HipEvents:
+    """Caller-owned HIP events for omc_step_update_recompress_events (plain HIP runtime calls)."""
+
+    def __init__(self, count: int):
+        self._hip = C.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [C.POINTER(_vp)]
+        self._hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), _vp, _vp]
+        self._hip.hipEventSynchronize.argtypes = [_vp]
+        self._hip.hipEventDestroy.argtypes = [_vp]
+        self.handles = (_vp * count)()
+        for i in range(count):
+            h = _vp()
+            if self._hip.hipEventCreate(C.byref(h)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.handles[i] = h
+
+    def elapsed_ms(self, i: int, j: int) -> float:
+        self._hip.hipEventSynchronize(self.handles[j])
+        ms = C.c_float()
+        if self._hip.hipEventElapsedTime(C.byref(ms), self.handles[i], self.handles[j]) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value
+
+    def __del__(self):
+        for h in self.handles:
+            if h:
+                self._hip.hipEventDestroy(h)
+
+
+def omc_step_update_recompress_events(arena, plan: Plan, sb_table, grads, state0, state1, o: omc_opt,
+                                      ws, events: HipEvents, first: int = 0, stream=None) -> None:
+    """`first`: index of the first event handle to use (2 * plan.launches handles are consumed)."""
+    _check(_step_ev(_ptr(arena), arena.numel() * arena.element_size(), plan.host.ctypes.data,
+                    _ptr(plan.dev), _ptr(sb_table), _ptr(grads), _ptr(state0), _ptr(state1),
+                    grads.numel(), C.byref(o), _ptr(ws), ws.numel() * ws.element_size(),
+                    _stream(stream), C.cast(C.byref(events.handles, first * C.sizeof(_vp)), _vp),
+                    len(events.handles) - first),
+           "omc_step_update_recompress_events")
 
 
 # ------------------------------------------------------------------ forward path

@@ -67,7 +67,8 @@ def test_plan_build_validates_the_table():
             dict(data_offset=6880, aux_offset=5000, n=100, quantized=False)]
     size, st, buf = _plan_status(good)
     assert st == 0 and size > 0
-    assert omc._plan_ws(buf.ctypes.data) == 48 * 2
+    # 5000 quantized elements: one item for the two full tiles, one for the ragged tail; one fp32 item
+    assert omc._plan_ws(buf.ctypes.data) == 48 * 3
     assert omc._plan_arena(buf.ctypes.data) == 6880 + 400
     assert omc._plan_aux(buf.ctypes.data) == 5100
     # misaligned offsets
@@ -99,12 +100,20 @@ def test_plan_item_list_covers_every_chunk_once():
     assert st == 0
     hdr = np.frombuffer(buf[:32].tobytes(), dtype=np.uint32)
     nvars, nitems, ngroups, nquant = (int(x) for x in hdr[2:6])
-    assert nvars == len(specs) and ngroups == 2 and nquant == int(mask.sum())
+    assert nvars == len(specs) and nquant == int(mask.sum())
+    assert ngroups == 2 + (1 if any(s.n % 2048 and q for s, q in zip(specs, mask)) else 0)
     offs = np.frombuffer(buf[32:56].tobytes(), dtype=np.uint64)
     item_off = int(offs[1])
     items = np.frombuffer(buf[item_off:item_off + 8 * nitems].tobytes(), dtype=np.uint32).reshape(-1, 2)
-    want = sorted((i, c) for i, s in enumerate(specs) for c in range((s.n + 8191) // 8192))
-    assert sorted(map(tuple, items.tolist())) == want
+    def n_items(s, q):      # quantized: chunks of 4 full 2048-element tiles, plus one item for a ragged tail
+        return ((s.n // 2048 + 3) // 4 + (1 if s.n % 2048 else 0)) if q else (s.n + 8191) // 8192
+    counts = {}
+    for v, c in items.tolist():
+        counts.setdefault(v, []).append(c)
+    assert sorted(counts) == list(range(len(specs)))
+    for i, s in enumerate(specs):
+        assert len(counts[i]) == n_items(s, mask[i])
+    assert nitems == sum(n_items(s, q) for s, q in zip(specs, mask))
 
 
 def test_entry_points_reject_bad_arguments_without_a_device():
