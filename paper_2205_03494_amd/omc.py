@@ -16,7 +16,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libomc.so")
+LIB_PATH = os.environ.get("OMC_LIBRARY_PATH", os.path.join(_HERE, "libomc.so"))  # override: another build of libomc
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
