@@ -215,6 +215,15 @@ def main():
     kern_ms = [x / args.steps for x in kern_ms]
     dom_ms = kern_ms[0]                                     # launch 0: the 8-bit fused step kernel
     achieved = alg_bytes_q / (dom_ms * 1e-3) / 1e9
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same command and
+    # scaled by a plain copy's reading (summary and commands: profiles/step_kernel_sgd8_conformer115m.md)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "step_kernel_sgd8_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            tj = json.load(fh)
+        if tj.get("n_quantized_params") == n_q:
+            traffic = tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"]
 
     out = {
         "metric": "compressed-param GB/s per decompress+update+recompress step; % HBM peak",
@@ -242,7 +251,7 @@ def main():
                    "parity_vs_oracle_on_sample": parity},
         "roofline": {"bound": "hbm", "kernel": "step_kernel<8,sgd>", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None},
+                     "algorithmic_bytes_per_launch": alg_bytes_q, "traffic": traffic},
     }
     if cpu is not None:
         out["cpu_baseline"] = {

@@ -45,11 +45,21 @@ struct OptConst {
 #ifndef OMC_TUNE_PREFETCH
 #define OMC_TUNE_PREFETCH 1
 #endif
+#ifndef OMC_TUNE_WAVES_MOMENTUM
+#define OMC_TUNE_WAVES_MOMENTUM 2
+#endif
+#ifndef OMC_TUNE_WAVES_ADAM
+#define OMC_TUNE_WAVES_ADAM 1
+#endif
+#ifndef OMC_TUNE_PREFETCH_HEAVY
+#define OMC_TUNE_PREFETCH_HEAVY 0
+#endif
 template <int MODE, int B>
 struct Tuning {
     static constexpr int light = (B <= 12) ? OMC_TUNE_WAVES_LIGHT : (OMC_TUNE_WAVES_LIGHT > 3 ? 3 : OMC_TUNE_WAVES_LIGHT);
-    static constexpr int waves = (MODE == kStepAdam) ? 2 : (MODE == kStepMomentum) ? 3 : light;
-    static constexpr bool prefetch = (OMC_TUNE_PREFETCH != 0) && MODE <= kStepSgd;  // heavier modes lack the registers
+    static constexpr int waves = (MODE == kStepAdam) ? OMC_TUNE_WAVES_ADAM
+                                 : (MODE == kStepMomentum) ? OMC_TUNE_WAVES_MOMENTUM : light;
+    static constexpr bool prefetch = (MODE <= kStepSgd) ? (OMC_TUNE_PREFETCH != 0) : (OMC_TUNE_PREFETCH_HEAVY != 0);
 };
 
 // A value that is the same in every lane (read through a vector load, e.g. from the plan) moved
