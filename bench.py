@@ -111,6 +111,36 @@ def cpu_baseline(wl, synth, sample_blocks, iters, threads, gpu_after=None):
                 n_elems=n_elems, packed_bytes=packed_bytes)
 
 
+def gemm_leg(torch, omc, synth, iters=20):
+    """Forward-path dequant-fused GEMM (BASELINE config 5): bf16 activations [8192 x 1024] times S1E4M3
+    weights [1024 x 4096], and [8192 x 4096] times [4096 x 1024]; fp32 accumulate and output."""
+    import numpy as np
+    gf = omc.fmt(4, 3)
+    out = []
+    for (M, N, K) in ((8192, 4096, 1024), (8192, 1024, 4096)):
+        A = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 11)).view(np.int16)).cuda()
+        W = torch.from_numpy(synth.normal_f32(K * N, 1.0 / np.sqrt(K), 12)).cuda()
+        codes = torch.zeros(omc.omc_packed_bytes(gf, K * N), dtype=torch.uint8, device="cuda")
+        sb = torch.zeros(2, device="cuda")
+        wsc = torch.empty(omc.omc_compress_workspace_bytes(K * N), dtype=torch.uint8, device="cuda")
+        omc.omc_compress(W, K * N, gf, True, codes, sb, wsc)
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        ws = torch.empty(omc.omc_dequant_gemm_workspace_bytes(M), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            omc.omc_dequant_gemm(A, codes, gf, sb, C, M, N, K, ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            omc.omc_dequant_gemm(A, codes, gf, sb, C, M, N, K, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        out.append({"M": M, "N": N, "K": K, "ms": ms, "TFLOPs": tf, "frac_of_bf16_mfma_peak": tf / 2500.0,
+                    "hbm_bytes": 2 * M * K + K * N + 4 * M * N})
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,6 +150,7 @@ def main():
     ap.add_argument("--cpu-sample-blocks", type=int, default=4)
     ap.add_argument("--cpu-iters", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
+    ap.add_argument("--gemm-only", action="store_true", help="only the forward GEMM leg (for profiler runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device-to-device copy of known size (1 GiB read + 1 GiB written "
                          "per launch) to calibrate profiler byte counters and show the copy ceiling")
@@ -150,6 +181,9 @@ def main():
         ms = e0.elapsed_time(e1) / 20
         print(json.dumps({"copy_kernel": "torch Tensor.copy_ fp32", "bytes_read": 4 * n, "bytes_written": 4 * n,
                           "ms": ms, "GBps": 8 * n / (ms * 1e-3) / 1e9}))
+        return
+    if args.gemm_only:
+        print(json.dumps({"gemm": gemm_leg(torch, omc, synth)}))
         return
     wl = build_workload(torch, omc, synth, args.blocks, 512, 2048)
     specs, mask, lay, plan = wl["specs"], wl["mask"], wl["lay"], wl["plan"]
@@ -253,6 +287,9 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": alg_bytes_q, "traffic": traffic},
     }
+    del grads, arena0
+    torch.cuda.empty_cache()
+    out["forward_gemm"] = gemm_leg(torch, omc, synth)
     if cpu is not None:
         out["cpu_baseline"] = {
             "value": cpu["packed_bytes"] / cpu["sec_per_iter"] / 1e9, "unit": "GB/s",

@@ -219,7 +219,9 @@ size_t omc_dequant_gemm_workspace_bytes(uint32_t M);
  *   C        device, M*N floats, row-major; fp32 accumulation
  *   ws       device workspace of omc_dequant_gemm_workspace_bytes(M) bytes
  * Uses  A*(s*Vt + b*1) = s*(A*Vt) + b*rowsum(A)*1^T.  Requires man_bits <= 7 (every Vtilde is then
- * exactly a bfloat16), M % 256 == 0, N % 256 == 0, K % 64 == 0 (OMC_ERR_FORMAT / OMC_ERR_SIZE). */
+ * exactly a bfloat16), M % 256 == 0, N % 128 == 0, K % 32 == 0 (OMC_ERR_FORMAT / OMC_ERR_SIZE).
+ * Values of the format below 2^-126 (possible only with a bias near 127) may be flushed to zero by
+ * the matrix cores. */
 omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, const float *sb,
                             float *C, uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes,
                             void *stream);

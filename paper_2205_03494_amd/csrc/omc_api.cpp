@@ -377,7 +377,7 @@ omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, 
     FmtParams fp;
     if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
     if (fp.man_bits > 7) return OMC_ERR_FORMAT;
-    if (M == 0 || N == 0 || K == 0 || M % 256 != 0 || N % 256 != 0 || K % 64 != 0) return OMC_ERR_SIZE;
+    if (M == 0 || N == 0 || K == 0 || M % 256 != 0 || N % 128 != 0 || K % 32 != 0) return OMC_ERR_SIZE;
     if (!aligned16(A) || !aligned16(codes) || !aligned16(C) || (reinterpret_cast<uintptr_t>(sb) & 3u))
         return OMC_ERR_ALIGN;
     if (!ws || ws_bytes < omc_dequant_gemm_workspace_bytes(M)) return OMC_ERR_WORKSPACE;

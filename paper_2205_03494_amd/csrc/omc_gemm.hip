@@ -1,9 +1,220 @@
-// placeholder until the MFMA kernel lands
+// omc_dequant_gemm: C = A * decompress(W) with the weights expanded on chip (paper Sec. 2.1,
+// forward path: the layer's parameters are decompressed on the fly and consumed at once).
+//
+// The affine per-variable transformation (Sec. 2.3) factors out of the contraction:
+//     A (s Vt + b 1 1^T) = s (A Vt) + b rowsum(A) 1^T,
+// and every code value Vt of a format with at most 7 mantissa bits is exactly a bfloat16, so the
+// matrix cores run on exact images of the codes: bf16 x bf16 MFMA with fp32 accumulation.
+//
+// Tiling.  Workgroup = 4 waves, output tile 256 (M) x 128 (N), K step 32.  Wave w owns rows
+// [64 w, 64 w + 64) and all 128 columns: 2 x 4 MFMA tiles of 32x32 (v_mfma_f32_32x32x16_bf16),
+// 128 accumulator registers.  Both operands sit in LDS as [k-chunk of 8][row or column][16 bytes],
+// which is what one lane of the MFMA consumes, so fragment reads are 16-byte, contiguous across
+// lanes and free of bank conflicts.
+//   A: global 16-byte pieces -> LDS, rows XOR-swizzled by the chunk so that the stores do not collide.
+//   W: each thread takes a 4 (k) x 4 (n) patch of codes, decodes the 16 values in registers
+//      (same bit-domain decode as the streaming kernels, fp32 -> top 16 bits, exact) and stores the
+//      four k-values of each column as 8 bytes.  Column c = 4 cg + i is kept at slot 32 i + cg, so
+//      that MFMA tile i covers the columns == i (mod 4): the stores of 16 neighbouring lanes then
+//      fill 128 contiguous bytes, and in the epilogue a lane holds four adjacent columns of C,
+//      one 16-byte store per row.
+// Global loads of the next K step are issued into registers before the current step is computed.
 #include <hip/hip_runtime.h>
 #include "omc_internal.h"
+
+#pragma clang fp contract(off)
+
 namespace omc {
-int launch_dequant_gemm(const uint16_t *, const void *, const FmtParams &, const float *, float *, uint32_t,
-                        uint32_t, uint32_t, float *, void *) {
-    return static_cast<int>(hipErrorNotSupported);
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBM = 256, kBN = 128, kBK = 32;
+constexpr int kAChunkBytes = kBM * 16;   // one k-chunk (8 bf16) of all rows
+constexpr int kWChunkBytes = kBN * 16;
+constexpr int kLdsBytes = 4 * kAChunkBytes + 4 * kWChunkBytes;   // 24 KB
+
+// One wave per activation row: rowsum[m] = sum_k A[m][k] in fp32 (lane-strided, then a butterfly).
+__global__ __launch_bounds__(256) void gemm_rowsum_kernel(const uint16_t *__restrict__ A, float *__restrict__ rowsum,
+                                                          uint32_t M, uint32_t K) {
+    const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const uint16_t *a = A + static_cast<uint64_t>(row) * K;
+    float s = 0.0f;
+    for (uint32_t k = lane * 8; k < K; k += 512) {
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(a + k);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s += __uint_as_float(v[i] << 16);
+            s += __uint_as_float(v[i] & 0xffff0000u);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) rowsum[row] = s;
 }
+
+// fp32 value of a code given with its sign bit at bit 31 (see the streaming kernels)
+__device__ __forceinline__ uint32_t decode_bits(uint32_t top, const FmtParams &fp) {
+    int32_t u = static_cast<int32_t>(top) >> fp.asr;
+    u &= static_cast<int32_t>(fp.keep_mask);
+    return __float_as_uint(__uint_as_float(static_cast<uint32_t>(u)) * fp.dec_scale);
+}
+
+// Four consecutive codes (elements e .. e+3 of the packed stream) as bytes-at-top of four words.
+template <bool BYTE>
+__device__ __forceinline__ void load_codes4(const uint32_t *__restrict__ codes, uint64_t total_dwords, uint64_t e,
+                                            uint32_t B, uint32_t (&raw)[3], uint32_t &off) {
+    if (BYTE) {
+        raw[0] = codes[e >> 2];          // e is a multiple of 4
+        off = 0;
+    } else {
+        const uint64_t bit = e * B;
+        const uint64_t dw = bit >> 5;
+        off = static_cast<uint32_t>(bit & 31u);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) raw[i] = (dw + i < total_dwords) ? codes[dw + i] : 0u;
+    }
+}
+template <bool BYTE>
+__device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32_t off, uint32_t B, int i) {
+    if (BYTE) return raw[0] << (24 - 8 * i);
+    const uint32_t sh = off + i * B;                       // < 32 + 3 * 16
+    const uint64_t lo = (static_cast<uint64_t>(raw[1]) << 32) | raw[0];
+    const uint64_t hi = (static_cast<uint64_t>(raw[2]) << 32) | raw[1];
+    const uint32_t c = (sh < 32) ? static_cast<uint32_t>(lo >> sh) : static_cast<uint32_t>(hi >> (sh - 32));
+    return c << (32 - B);
+}
+
+template <bool BYTE>
+__global__ __launch_bounds__(256, 2) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
+                                                              const uint32_t *__restrict__ codes, uint64_t total_dwords,
+                                                              FmtParams fp, const float *__restrict__ sb,
+                                                              const float *__restrict__ rowsum, float *__restrict__ C,
+                                                              uint32_t M, uint32_t N, uint32_t K) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
+    uint8_t *ldsA = lds;
+    uint8_t *ldsW = lds + 4 * kAChunkBytes;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63, wave = tid >> 6;
+    // consecutive workgroups share the W column block and walk down M
+    const uint32_t m0 = blockIdx.x * kBM, n0 = blockIdx.y * kBN;
+
+    // ---- roles in the loads ------------------------------------------------------------------
+    // A: piece q = tid + 256 p (p = 0..3): row = q / 4, chunk = q % 4
+    // W: patch (kg, cg): kg = 2 wave + (lane & 1), cg = lane >> 1
+    const uint32_t w_h = lane & 1u, w_cg = lane >> 1;
+    const uint32_t w_kg = 2 * wave + w_h;
+    const uint64_t w_col = n0 + 4 * w_cg;
+
+    u32x4 a_reg[4];
+    uint32_t w_raw[4][3], w_off[4];
+
+    auto load_stage = [&](uint32_t k0) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
+            a_reg[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint64_t e = static_cast<uint64_t>(k0 + 4 * w_kg + r) * N + w_col;
+            load_codes4<BYTE>(codes, total_dwords, e, fp.bits, w_raw[r], w_off[r]);
+        }
+    };
+
+    auto store_stage = [&]() {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
+            *reinterpret_cast<u32x4 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4)) = a_reg[p];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                       // column 4 cg + i of the patch
+            uint32_t v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = decode_bits(code_top_of<BYTE>(w_raw[r], w_off[r], fp.bits, i), fp);
+            u32x2 out;
+            out[0] = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);   // bf16(v0) | bf16(v1) << 16
+            out[1] = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
+            *reinterpret_cast<u32x2 *>(ldsW + wave * kWChunkBytes + ((32u * i + w_cg) << 4) + 8u * w_h) = out;
+        }
+    };
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+    const uint32_t f_row = lane & 31u, f_half = lane >> 5;   // fragment roles
+    load_stage(0);
+    for (uint32_t k0 = 0; k0 < K; k0 += kBK) {
+        __syncthreads();                                     // everyone is done reading the previous stage
+        store_stage();
+        __syncthreads();
+        if (k0 + kBK < K) load_stage(k0 + kBK);             // in flight while this stage is multiplied
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const uint32_t chunk = 2 * ks + f_half;
+            bf16x8 fa[2], fb[4];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const uint32_t row = 64 * wave + 32 * mi + f_row;
+                fa[mi] = *reinterpret_cast<const bf16x8 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4));
+            }
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                fb[ni] = *reinterpret_cast<const bf16x8 *>(ldsW + chunk * kWChunkBytes + ((32u * ni + f_row) << 4));
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue: C = s * acc + b * rowsum --------------------------------------------------------
+    const float s = sb ? sb[0] : 1.0f;
+    const float b = sb ? sb[1] : 0.0f;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t row = m0 + 64 * wave + 32 * mi + 8 * (v >> 2) + 4 * f_half + (v & 3);
+            const float add = sb ? b * rowsum[row] : 0.0f;
+            f32x4 out;
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) out[ni] = s * acc[mi][ni][v] + add;
+            __builtin_nontemporal_store(out, reinterpret_cast<f32x4 *>(C + static_cast<uint64_t>(row) * N + n0 + 4 * f_row));
+        }
+    }
+}
+
+int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb, float *C,
+                        uint32_t M, uint32_t N, uint32_t K, float *rowsum, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (sb) {
+        gemm_rowsum_kernel<<<dim3((M + 3) / 4), dim3(256), 0, st>>>(A, rowsum, M, K);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return static_cast<int>(e);
+    }
+    const uint64_t n = static_cast<uint64_t>(K) * N;
+    const uint64_t total_dwords = ((n * fp.bits + 7) / 8 + 15) / 16 * 4;
+    const dim3 grid(M / kBM, N / kBN);
+    const uint32_t *c = static_cast<const uint32_t *>(codes);
+    if (fp.bits == 8)
+        dequant_gemm_kernel<true><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+    else
+        dequant_gemm_kernel<false><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+    return static_cast<int>(hipGetLastError());
+}
+
 }  // namespace omc
