@@ -194,8 +194,9 @@ omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const voi
  * launch.  Launch order: the full-tile kernels, one per distinct code width among the quantized
  * variables of at least 2048 elements, in ascending width (two for a width whose formats need
  * both rounding variants: formats with man_bits == 23 or a top binade of 2^(105+man_bits) or more
- * use the second); then up to two kernels for the ragged tails (n % 2048 != 0) of quantized
- * variables; then one kernel for the fp32 variables, if any; then the per-variable
+ * use the second), the first of them also serving the fp32 variables as extra workgroups; then
+ * up to two kernels for the ragged tails (n % 2048 != 0) of quantized variables; then, only if no
+ * full-tile kernel ran, one kernel for the fp32 variables; then the per-variable
  * finalize, if any variable is quantized.  omc_plan_launches gives the count; nevents must be at
  * least twice that (OMC_ERR_SIZE otherwise).  Results are identical to the plain call. */
 uint32_t omc_plan_launches(const void *plan_host);

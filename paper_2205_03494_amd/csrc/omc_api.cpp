@@ -318,8 +318,14 @@ static uint32_t plan_launches(const PlanHeader *ph) {
     const uint8_t *b = reinterpret_cast<const uint8_t *>(ph);
     const PlanGroup *groups = reinterpret_cast<const PlanGroup *>(b + ph->group_off);
     uint32_t k = ph->nquant > 0 ? 1u : 0u;
-    for (uint32_t g = 0; g < ph->ngroups; ++g)
-        if (groups[g].nitems > 0) ++k;
+    bool full = false, fp32 = false;
+    for (uint32_t g = 0; g < ph->ngroups; ++g) {
+        if (groups[g].nitems == 0) continue;
+        ++k;
+        full = full || groups[g].kind == kGroupFull;
+        fp32 = fp32 || groups[g].kind == kGroupFp32;
+    }
+    if (full && fp32) --k;   // the fp32 variables share the first full-tile launch
     return k;
 }
 

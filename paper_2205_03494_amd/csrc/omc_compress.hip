@@ -32,10 +32,12 @@ __global__ __launch_bounds__(64) void compress_tail_kernel(const float *__restri
     do_tail<kCompress, WIDE>(a, va.fp, oc, tail_partial);
 }
 
-__global__ __launch_bounds__(64) void finalize_single_kernel(const Partial *__restrict__ ws, uint32_t nparts,
-                                                             int has_tail, uint64_t n, int use_pvt,
-                                                             float *__restrict__ sb) {
-    finalize_variable(ws, nparts, has_tail ? ws + nparts : nullptr, n, use_pvt != 0, sb);
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void finalize_single_kernel(const Partial *__restrict__ ws, uint32_t nparts,
+                                                                  int has_tail, uint64_t n, int use_pvt,
+                                                                  float *__restrict__ sb) {
+    __shared__ double red[NW * 10];
+    finalize_variable<NW>(ws, nparts, has_tail ? ws + nparts : nullptr, n, use_pvt != 0, sb, red);
 }
 
 int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb, Partial *ws,
@@ -65,7 +67,11 @@ int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes,
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return static_cast<int>(e);
     }
-    finalize_single_kernel<<<dim3(1), dim3(64), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
+    // the width of the reduction depends on the size alone, so results do not depend on the run
+    if (nchunks <= 256)
+        finalize_single_kernel<1><<<dim3(1), dim3(64), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
+    else
+        finalize_single_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
     return static_cast<int>(hipGetLastError());
 }
 

@@ -4,65 +4,9 @@
 
 namespace omc {
 
-// Variables kept in fp32 (paper Sec. 2.4, 2.5): the update alone, 16-byte pieces, coalesced.
 template <int MODE>
 __global__ __launch_bounds__(64) void step_fp32_kernel(StepArgs sa) {
-    const PlanItem *items = reinterpret_cast<const PlanItem *>(sa.plan + sa.item_off);
-    const PlanVar *vars = reinterpret_cast<const PlanVar *>(sa.plan + sa.var_off);
-    const PlanItem it = to_scalar_regs(items[sa.first_item + blockIdx.x]);
-    const PlanVar pv = to_scalar_regs(vars[it.var]);
-    const uint32_t lane = threadIdx.x;
-    float *__restrict__ w = reinterpret_cast<float *>(sa.arena + pv.data_offset);
-    const float *__restrict__ g = sa.grads + pv.aux_offset;
-    float *__restrict__ m = sa.st0 ? sa.st0 + pv.aux_offset : nullptr;
-    float *__restrict__ v = sa.st1 ? sa.st1 + pv.aux_offset : nullptr;
-    const uint64_t n = pv.n;
-    const uint64_t begin = static_cast<uint64_t>(it.chunk) * kChunkElems;
-    constexpr int kIters = kChunkElems / 256;
-#pragma unroll 4
-    for (int j = 0; j < kIters; ++j) {
-        const uint64_t e = begin + (static_cast<uint64_t>(j) * 64 + lane) * 4;
-        if (e >= n) continue;
-        float xw[4], xg[4], xm[4] = {0, 0, 0, 0}, xv[4] = {0, 0, 0, 0};
-        const bool full = e + 4 <= n;
-        if (full) {
-            const float4 tw = *reinterpret_cast<const float4 *>(w + e);
-            const float4 tg = *reinterpret_cast<const float4 *>(g + e);
-            xw[0] = tw.x; xw[1] = tw.y; xw[2] = tw.z; xw[3] = tw.w;
-            xg[0] = tg.x; xg[1] = tg.y; xg[2] = tg.z; xg[3] = tg.w;
-            if (MODE >= kStepMomentum) {
-                const float4 tm = *reinterpret_cast<const float4 *>(m + e);
-                xm[0] = tm.x; xm[1] = tm.y; xm[2] = tm.z; xm[3] = tm.w;
-            }
-            if (MODE == kStepAdam) {
-                const float4 tv = *reinterpret_cast<const float4 *>(v + e);
-                xv[0] = tv.x; xv[1] = tv.y; xv[2] = tv.z; xv[3] = tv.w;
-            }
-        } else {
-            for (int c = 0; c < 4; ++c) {
-                const bool ok = e + c < n;
-                xw[c] = ok ? w[e + c] : 0.0f;
-                xg[c] = ok ? g[e + c] : 0.0f;
-                if (MODE >= kStepMomentum) xm[c] = ok ? m[e + c] : 0.0f;
-                if (MODE == kStepAdam) xv[c] = ok ? v[e + c] : 0.0f;
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) xw[c] = apply_update<MODE>(xw[c], xg[c], xm[c], xv[c], sa.oc);
-        if (full) {
-            *reinterpret_cast<float4 *>(w + e) = make_float4(xw[0], xw[1], xw[2], xw[3]);
-            if (MODE >= kStepMomentum) *reinterpret_cast<float4 *>(m + e) = make_float4(xm[0], xm[1], xm[2], xm[3]);
-            if (MODE == kStepAdam) *reinterpret_cast<float4 *>(v + e) = make_float4(xv[0], xv[1], xv[2], xv[3]);
-        } else {
-            for (int c = 0; c < 4; ++c) {
-                if (e + c < n) {
-                    w[e + c] = xw[c];
-                    if (MODE >= kStepMomentum) m[e + c] = xm[c];
-                    if (MODE == kStepAdam) v[e + c] = xv[c];
-                }
-            }
-        }
-    }
+    do_fp32_item<MODE>(sa, sa.first_item + blockIdx.x);
 }
 
 // Ragged tails of quantized variables, one wave each (code width read from the plan).
@@ -94,15 +38,19 @@ static int launch_tail(bool wide, const StepArgs &sa, hipStream_t st) {
 }
 
 // One wave per variable: new (s, b) of every quantized variable from its chunks' partials.
-__global__ __launch_bounds__(64) void finalize_plan_kernel(const uint8_t *__restrict__ plan, uint64_t var_off,
-                                                           const Partial *__restrict__ ws,
-                                                           float *__restrict__ sb_table) {
+constexpr int kFinalizeWaves = 4;
+__global__ __launch_bounds__(64 * kFinalizeWaves) void finalize_plan_kernel(const uint8_t *__restrict__ plan,
+                                                                            uint64_t var_off,
+                                                                            const Partial *__restrict__ ws,
+                                                                            float *__restrict__ sb_table) {
+    __shared__ double red[kFinalizeWaves * 10];
     const PlanVar *vars = reinterpret_cast<const PlanVar *>(plan + var_off);
-    const PlanVar &pv = vars[blockIdx.x];
+    const PlanVar pv = to_scalar_regs(vars[blockIdx.x]);
     if (!(pv.flags & OMC_VAR_QUANTIZED)) return;
-    finalize_variable(pv.nitems ? ws + pv.first_item : ws, pv.nitems,
-                      pv.tail_item != kNoItem ? ws + pv.tail_item : nullptr, pv.n,
-                      !(pv.flags & OMC_VAR_NO_PVT), sb_table + 2 * static_cast<uint64_t>(blockIdx.x));
+    finalize_variable<kFinalizeWaves>(pv.nitems ? ws + pv.first_item : ws, pv.nitems,
+                                      pv.tail_item != kNoItem ? ws + pv.tail_item : nullptr, pv.n,
+                                      !(pv.flags & OMC_VAR_NO_PVT),
+                                      sb_table + 2 * static_cast<uint64_t>(blockIdx.x), red);
 }
 
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table, const float *grads,
@@ -128,11 +76,28 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     sa.ws = ws;
     sa.oc = OptConst{opt.lr, opt.momentum, opt.beta1, opt.beta2, opt.eps, opt.one_minus_beta1,
                      opt.one_minus_beta2, opt.bias_corr1, opt.bias_corr2};
+    // the fp32 variables ride along with the first full-tile launch as extra workgroups
+    const PlanGroup *fp32_group = nullptr;
+    bool fuse = false;
+    for (uint32_t gi = 0; gi < ph->ngroups; ++gi) {
+        if (groups[gi].kind == kGroupFp32 && groups[gi].nitems > 0) fp32_group = &groups[gi];
+        if (groups[gi].kind == kGroupFull && groups[gi].nitems > 0) fuse = true;
+    }
+    fuse = fuse && fp32_group != nullptr;
+    bool fused_done = false;
     for (uint32_t gi = 0; gi < ph->ngroups; ++gi) {
         const PlanGroup &g = groups[gi];
         if (g.nitems == 0) continue;
+        if (fuse && g.kind == kGroupFp32) continue;
         sa.first_item = g.first_item;
         sa.nitems = g.nitems;
+        sa.fp32_first = 0;
+        sa.fp32_nitems = 0;
+        if (fuse && g.kind == kGroupFull && !fused_done) {
+            sa.fp32_first = fp32_group->first_item;
+            sa.fp32_nitems = fp32_group->nitems;
+            fused_done = true;
+        }
         int rc = mark(0);
         if (rc != 0) return rc;
         if (g.kind == kGroupTail) {
@@ -159,7 +124,7 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     if (ph->nquant > 0) {
         int rc = mark(0);
         if (rc != 0) return rc;
-        finalize_plan_kernel<<<dim3(ph->nvars), dim3(64), 0, st>>>(sa.plan, ph->var_off, ws, sb_table);
+        finalize_plan_kernel<<<dim3(ph->nvars), dim3(64 * kFinalizeWaves), 0, st>>>(sa.plan, ph->var_off, ws, sb_table);
         rc = static_cast<int>(hipGetLastError());
         if (rc != 0) return rc;
         return mark(1);

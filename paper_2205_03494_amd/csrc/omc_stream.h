@@ -624,22 +624,25 @@ __device__ __forceinline__ DD dd_shfl_xor(DD a, int off) {
     return r;
 }
 
-// Called by one full wave.  Sums the variable's partials (a run of `nparts` from the full-tile
-// kernels and, if `tail` is not null, one more from the tail kernel) in a fixed order with
-// compensated additions, evaluates the closed form in fp64 and stores (s, b) as fp32.
+// Called by a whole workgroup of NW waves (blockDim.x == 64 * NW).  Sums the variable's partials
+// (a run of `nparts` from the full-tile kernels and, if `tail` is not null, one more from the tail
+// kernel) with compensated additions in an order fixed by (nparts, NW) alone: thread t takes
+// partials t, t + 64 NW, ...; lanes combine by a butterfly; waves combine in index order.  Then the
+// closed form in fp64, stored as fp32.  `red` is LDS scratch of NW * 10 doubles.
+template <int NW>
 __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ parts, uint32_t nparts,
                                                   const Partial *__restrict__ tail, uint64_t n, bool use_pvt,
-                                                  float *sb_out) {
-    const uint32_t lane = threadIdx.x;
+                                                  float *sb_out, double *red) {
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     if (!use_pvt) {
-        if (lane == 0) { sb_out[0] = 1.0f; sb_out[1] = 0.0f; }
+        if (tid == 0) { sb_out[0] = 1.0f; sb_out[1] = 0.0f; }
         return;
     }
     DD sV{0, 0}, sT{0, 0}, sVT{0, 0}, sTT{0, 0};
     float tmin = __builtin_huge_valf(), tmax = -__builtin_huge_valf();
     bool finite = true;
     const uint32_t total = nparts + (tail ? 1u : 0u);
-    for (uint32_t i = lane; i < total; i += 64) {
+    for (uint32_t i = tid; i < total; i += 64 * NW) {
         const Partial p = (i < nparts) ? parts[i] : *tail;
         finite = finite && isfinite(p.sV);
         if (finite) {
@@ -661,7 +664,28 @@ __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ pa
         tmax = fmaxf(tmax, __shfl_xor(tmax, off));
         finite = __shfl_xor(static_cast<int>(finite), off) && finite;
     }
-    if (lane != 0) return;
+    if (NW > 1) {
+        if (lane == 0) {
+            double *r = red + wave * 10;
+            r[0] = sV.hi; r[1] = sV.lo; r[2] = sT.hi; r[3] = sT.lo; r[4] = sVT.hi; r[5] = sVT.lo;
+            r[6] = sTT.hi; r[7] = sTT.lo;
+            r[8] = static_cast<double>(tmin);
+            r[9] = finite ? static_cast<double>(tmax) : __builtin_nan("");   // NaN marks a poisoned wave
+        }
+        __syncthreads();
+        if (tid != 0) return;
+        for (int w = 1; w < NW; ++w) {
+            const double *r = red + w * 10;
+            sV = dd_add(sV, DD{r[0], r[1]});
+            sT = dd_add(sT, DD{r[2], r[3]});
+            sVT = dd_add(sVT, DD{r[4], r[5]});
+            sTT = dd_add(sTT, DD{r[6], r[7]});
+            tmin = fminf(tmin, static_cast<float>(r[8]));
+            if (r[9] != r[9]) finite = false; else tmax = fmaxf(tmax, static_cast<float>(r[9]));
+        }
+    } else if (tid != 0) {
+        return;
+    }
     if (!finite) {                                   // a non-finite input value poisons the fit
         sb_out[0] = __builtin_nanf("");
         sb_out[1] = __builtin_nanf("");
