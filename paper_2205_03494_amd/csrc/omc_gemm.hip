@@ -18,7 +18,10 @@
 //      that MFMA tile i covers the columns == i (mod 4): the stores of 16 neighbouring lanes then
 //      fill 128 contiguous bytes, and in the epilogue a lane holds four adjacent columns of C,
 //      one 16-byte store per row.
-// Global loads of the next K step are issued into registers before the current step is computed.
+// The K loop is double-buffered in LDS: while the matrix cores work on one K step, the codes of the
+// next one are decoded and stored into the other buffer, and the global loads of the step after
+// that are in flight into registers; one workgroup barrier per K step.  When the 256-row tiling
+// would leave compute units idle, a 128-row variant (wave = 32 rows) doubles the number of workgroups.
 #include <hip/hip_runtime.h>
 #include "omc_internal.h"
 
@@ -32,10 +35,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBM = 256, kBN = 128, kBK = 32;
-constexpr int kAChunkBytes = kBM * 16;   // one k-chunk (8 bf16) of all rows
-constexpr int kWChunkBytes = kBN * 16;
-constexpr int kLdsBytes = 4 * kAChunkBytes + 4 * kWChunkBytes;   // 24 KB
+constexpr int kBN = 128, kBK = 32;
+constexpr int kWChunkBytes = kBN * 16;   // one k-chunk (8 bf16) of all columns
 
 // One wave per activation row: rowsum[m] = sum_k A[m][k] in fp32 (lane-strided, then a butterfly).
 __global__ __launch_bounds__(256) void gemm_rowsum_kernel(const uint16_t *__restrict__ A, float *__restrict__ rowsum,
@@ -90,34 +91,36 @@ __device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32
     return c << (32 - B);
 }
 
-template <bool BYTE>
+template <int BM, bool BYTE>
 __global__ __launch_bounds__(256, 2) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
                                                               const uint32_t *__restrict__ codes, uint64_t total_dwords,
                                                               FmtParams fp, const float *__restrict__ sb,
                                                               const float *__restrict__ rowsum, float *__restrict__ C,
                                                               uint32_t M, uint32_t N, uint32_t K) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
-    uint8_t *ldsA = lds;
-    uint8_t *ldsW = lds + 4 * kAChunkBytes;
+    constexpr int kAChunkBytes = BM * 16;                 // one k-chunk (8 bf16) of all rows
+    constexpr int kStageBytes = 4 * kAChunkBytes + 4 * kWChunkBytes;
+    constexpr int MI = BM / 128;                          // 32-row MFMA tiles per wave
+    constexpr int AP = BM / 64;                           // 16-byte pieces of A per thread and stage
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kStageBytes];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63, wave = tid >> 6;
     // consecutive workgroups share the W column block and walk down M
-    const uint32_t m0 = blockIdx.x * kBM, n0 = blockIdx.y * kBN;
+    const uint32_t m0 = blockIdx.x * BM, n0 = blockIdx.y * kBN;
 
     // ---- roles in the loads ------------------------------------------------------------------
-    // A: piece q = tid + 256 p (p = 0..3): row = q / 4, chunk = q % 4
+    // A: piece q = tid + 256 p (p < AP): row = q / 4, chunk = q % 4
     // W: patch (kg, cg): kg = 2 wave + (lane & 1), cg = lane >> 1
     const uint32_t w_h = lane & 1u, w_cg = lane >> 1;
     const uint32_t w_kg = 2 * wave + w_h;
     const uint64_t w_col = n0 + 4 * w_cg;
 
-    u32x4 a_reg[4];
+    u32x4 a_reg[AP];
     uint32_t w_raw[4][3], w_off[4];
 
     auto load_stage = [&](uint32_t k0) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < AP; ++p) {
             const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
             a_reg[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
         }
@@ -128,9 +131,10 @@ __global__ __launch_bounds__(256, 2) void dequant_gemm_kernel(const uint16_t *__
         }
     };
 
-    auto store_stage = [&]() {
+    auto store_stage = [&](uint8_t *ldsA) {
+        uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < AP; ++p) {
             const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
             *reinterpret_cast<u32x4 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4)) = a_reg[p];
         }
@@ -146,49 +150,55 @@ __global__ __launch_bounds__(256, 2) void dequant_gemm_kernel(const uint16_t *__
         }
     };
 
-    f32x16 acc[2][4];
+    f32x16 acc[MI][4];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
     const uint32_t f_row = lane & 31u, f_half = lane >> 5;   // fragment roles
+    const uint32_t nk = K / kBK;
     load_stage(0);
-    for (uint32_t k0 = 0; k0 < K; k0 += kBK) {
-        __syncthreads();                                     // everyone is done reading the previous stage
-        store_stage();
-        __syncthreads();
-        if (k0 + kBK < K) load_stage(k0 + kBK);             // in flight while this stage is multiplied
+    store_stage(lds);
+    __syncthreads();
+    if (nk > 1) load_stage(kBK);
+    for (uint32_t it = 0; it < nk; ++it) {
+        const uint8_t *ldsA = lds + (it & 1u) * kStageBytes;
+        const uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const uint32_t chunk = 2 * ks + f_half;
-            bf16x8 fa[2], fb[4];
+            bf16x8 fa[MI], fb[4];
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                const uint32_t row = 64 * wave + 32 * mi + f_row;
+            for (int mi = 0; mi < MI; ++mi) {
+                const uint32_t row = 32 * MI * wave + 32 * mi + f_row;
                 fa[mi] = *reinterpret_cast<const bf16x8 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4));
             }
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni)
                 fb[ni] = *reinterpret_cast<const bf16x8 *>(ldsW + chunk * kWChunkBytes + ((32u * ni + f_row) << 4));
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < 4; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
         }
+        // the next K step goes into the other buffer (nobody reads it any more: barrier of the previous round)
+        if (it + 1 < nk) store_stage(lds + ((it + 1) & 1u) * kStageBytes);
+        __syncthreads();
+        if (it + 2 < nk) load_stage((it + 2) * kBK);
     }
 
     // ---- epilogue: C = s * acc + b * rowsum --------------------------------------------------------
     const float s = sb ? sb[0] : 1.0f;
     const float b = sb ? sb[1] : 0.0f;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi) {
+    for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const uint32_t row = m0 + 64 * wave + 32 * mi + 8 * (v >> 2) + 4 * f_half + (v & 3);
+            const uint32_t row = m0 + 32 * MI * wave + 32 * mi + 8 * (v >> 2) + 4 * f_half + (v & 3);
             const float add = sb ? b * rowsum[row] : 0.0f;
             f32x4 out;
 #pragma unroll
@@ -208,12 +218,22 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
     }
     const uint64_t n = static_cast<uint64_t>(K) * N;
     const uint64_t total_dwords = ((n * fp.bits + 7) / 8 + 15) / 16 * 4;
-    const dim3 grid(M / kBM, N / kBN);
     const uint32_t *c = static_cast<const uint32_t *>(codes);
-    if (fp.bits == 8)
-        dequant_gemm_kernel<true><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
-    else
-        dequant_gemm_kernel<false><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+    // 256-row tiles unless they would leave fewer than two workgroups per compute unit
+    const bool small = static_cast<uint64_t>(M / 256) * (N / kBN) < 512;
+    if (!small) {
+        const dim3 grid(M / 256, N / kBN);
+        if (fp.bits == 8)
+            dequant_gemm_kernel<256, true><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+        else
+            dequant_gemm_kernel<256, false><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+    } else {
+        const dim3 grid(M / 128, N / kBN);
+        if (fp.bits == 8)
+            dequant_gemm_kernel<128, true><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+        else
+            dequant_gemm_kernel<128, false><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+    }
     return static_cast<int>(hipGetLastError());
 }
 
