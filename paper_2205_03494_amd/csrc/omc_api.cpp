@@ -43,6 +43,7 @@ bool make_fmt_params(omc_format f, FmtParams *out) {
     p.magic_off = static_cast<uint32_t>(23 - M) << 23;
     const int top_exp = top_field(f) - bias;
     p.wide = (M == 23 || top_exp + 23 - M > 127) ? 1u : 0u;
+    p.variant = (E == 4 && M == 3 && bias == 7) ? 2u : p.wide;
     p.exp_adj = 127 + M;
     p.dec_scale = std::ldexp(1.0f, 127 - bias);
     p.enc_scale = std::ldexp(1.0f, bias - 127);
@@ -86,7 +87,7 @@ struct PlanLayout {
 static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *pl) {
     if (!vars) return OMC_ERR_NULL;
     if (nvars == 0) return OMC_ERR_SIZE;
-    bool present[66] = {false};
+    bool present[99] = {false};   // 3 * bits + variant
     bool tails[2] = {false, false};
     bool any_fp32 = false;
     uint64_t nitems = 0;
@@ -104,7 +105,7 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
             const uint32_t bits = 1u + v.fmt.exp_bits + v.fmt.man_bits;
             FmtParams fp;
             make_fmt_params(v.fmt, &fp);
-            if (v.n >= kTileElems) present[2 * bits + fp.wide] = true;
+            if (v.n >= kTileElems) present[3 * bits + fp.variant] = true;
             if (v.n % kTileElems) tails[fp.wide] = true;
             bytes = packed_bytes_u(bits, v.n);
             ++nquant;
@@ -126,8 +127,8 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
     };
     if (overlaps(data) || overlaps(aux)) return OMC_ERR_SIZE;
     pl->groups.clear();
-    for (uint32_t k = 4; k < 66; ++k)
-        if (present[k]) pl->groups.push_back(PlanGroup{kGroupFull, k >> 1, k & 1u, 0, 0, 0});
+    for (uint32_t k = 6; k < 99; ++k)
+        if (present[k]) pl->groups.push_back(PlanGroup{kGroupFull, k / 3, k % 3, 0, 0, 0});
     for (uint32_t w = 0; w < 2; ++w)
         if (tails[w]) pl->groups.push_back(PlanGroup{kGroupTail, 0, w, 0, 0, 0});
     if (any_fp32) pl->groups.push_back(PlanGroup{kGroupFp32, 0, 0, 0, 0, 0});
@@ -264,7 +265,7 @@ omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_h
             const omc_var &v = vars_host[i];
             const bool q = (v.flags & OMC_VAR_QUANTIZED) != 0;
             if (g.kind == kGroupFull) {
-                if (!q || pv[i].fp.bits != g.bits || pv[i].fp.wide != g.wide || v.n < kTileElems) continue;
+                if (!q || pv[i].fp.bits != g.bits || pv[i].fp.variant != g.wide || v.n < kTileElems) continue;
                 pv[i].first_item = next;
                 pv[i].nitems = static_cast<uint32_t>((v.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
                 for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};

@@ -3,7 +3,7 @@
 
 namespace omc {
 
-template <int B, bool WIDE>
+template <int B, int VARIANT>
 __global__ __launch_bounds__(64, (Tuning<kCompress, B>::waves)) void compress_kernel(
     const float *__restrict__ v, uint32_t *__restrict__ codes, VarArgs va, Partial *__restrict__ ws) {
     __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
@@ -15,7 +15,7 @@ __global__ __launch_bounds__(64, (Tuning<kCompress, B>::waves)) void compress_ke
     a.s = 1.0f;
     a.b = 0.0f;
     OptConst oc{};
-    do_chunk<B, kCompress, WIDE>(a, va.fp, oc, blockIdx.x, lds, ws + blockIdx.x);
+    do_chunk<B, kCompress, VARIANT>(a, va.fp, oc, blockIdx.x, lds, ws + blockIdx.x);
 }
 
 template <bool WIDE>
@@ -46,12 +46,16 @@ int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes,
     const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
     const bool has_tail = (va.n % kTileElems) != 0;
     uint32_t *c = static_cast<uint32_t *>(codes);
-    if (nchunks > 0) {
+    if (nchunks > 0 && va.fp.variant == 2) {
+        compress_kernel<8, 2><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return static_cast<int>(e);
+    } else if (nchunks > 0) {
         switch (va.fp.bits) {
 #define X(BITS)                                                                                 \
     case BITS:                                                                                  \
-        if (va.fp.wide) compress_kernel<BITS, true><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws); \
-        else compress_kernel<BITS, false><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws);    \
+        if (va.fp.variant == 1) compress_kernel<BITS, 1><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws); \
+        else compress_kernel<BITS, 0><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws);        \
         break;
             OMC_FOR_EACH_BITS(X)
 #undef X

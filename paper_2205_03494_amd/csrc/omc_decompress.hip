@@ -15,7 +15,7 @@ __global__ __launch_bounds__(64, (Tuning<kDecompress, B>::waves)) void decompres
     a.s = sb ? to_scalar_regs(sb[0]) : 1.0f;
     a.b = sb ? to_scalar_regs(sb[1]) : 0.0f;
     OptConst oc{};
-    do_chunk<B, kDecompress, false>(a, va.fp, oc, blockIdx.x, lds, nullptr);
+    do_chunk<B, kDecompress, 0>(a, va.fp, oc, blockIdx.x, lds, nullptr);
 }
 
 __global__ __launch_bounds__(64) void decompress_tail_kernel(const uint32_t *__restrict__ codes, VarArgs va,

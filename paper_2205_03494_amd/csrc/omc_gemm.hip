@@ -35,6 +35,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+#ifndef OMC_GEMM_WAVES
+#define OMC_GEMM_WAVES 2
+#endif
 constexpr int kBN = 128, kBK = 32;
 constexpr int kWChunkBytes = kBN * 16;   // one k-chunk (8 bf16) of all columns
 
@@ -92,7 +95,7 @@ __device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32
 }
 
 template <int BM, bool BYTE>
-__global__ __launch_bounds__(256, 2) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
+__global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
                                                               const uint32_t *__restrict__ codes, uint64_t total_dwords,
                                                               FmtParams fp, const float *__restrict__ sb,
                                                               const float *__restrict__ rowsum, float *__restrict__ C,

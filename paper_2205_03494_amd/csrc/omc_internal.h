@@ -28,6 +28,8 @@ struct FmtParams {
     uint32_t min_norm_bits;  // fp32 bit pattern of 2^(1 - bias), the smallest normal
     uint32_t magic_off;      // (23 - M) << 23
     uint32_t wide;           // 1: round with ldexp/rint (top binade + 23 - M would overflow fp32, or M == 23)
+    uint32_t variant;        // kernel variant: 0 add/subtract rounding, 1 = wide, 2 = the format is OCP FP8 E4M3
+                             // except for its top code (S1E4M3, bias 7): hardware conversions apply
     int32_t exp_adj;         // 127 + M
     float dec_scale;         // 2^(127 - bias)
     float enc_scale;         // 2^(bias - 127)
@@ -44,7 +46,7 @@ static_assert(sizeof(Partial) == 48, "Partial layout");
 
 // ---- plan blob ---------------------------------------------------------------------------
 constexpr uint32_t kPlanMagic = 0x434d4f50u;  // "POMC"
-constexpr uint32_t kPlanVersion = 2;
+constexpr uint32_t kPlanVersion = 3;
 
 struct PlanHeader {
     uint32_t magic, version;
@@ -79,7 +81,7 @@ enum GroupKind : uint32_t { kGroupFull = 0, kGroupTail = 1, kGroupFp32 = 2 };
 struct PlanGroup {
     uint32_t kind;           // GroupKind
     uint32_t bits;           // kGroupFull: code width of the group's variables
-    uint32_t wide;           // kGroupFull / kGroupTail: FmtParams::wide of the group's variables
+    uint32_t wide;           // kGroupFull: FmtParams::variant, kGroupTail: FmtParams::wide of the group's variables
     uint32_t first_item;
     uint32_t nitems;
     uint32_t pad;

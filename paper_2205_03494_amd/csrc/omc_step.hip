@@ -110,11 +110,11 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
             else step_fp32_kernel<kStepAdam><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             rc = static_cast<int>(hipGetLastError());
         } else if (opt.kind == OMC_SGD) {
-            rc = launch_step_group_sgd(g.bits, g.wide != 0, sa, st);
+            rc = launch_step_group_sgd(g.bits, g.wide, sa, st);
         } else if (opt.kind == OMC_MOMENTUM) {
-            rc = launch_step_group_momentum(g.bits, g.wide != 0, sa, st);
+            rc = launch_step_group_momentum(g.bits, g.wide, sa, st);
         } else {
-            rc = launch_step_group_adam(g.bits, g.wide != 0, sa, st);
+            rc = launch_step_group_adam(g.bits, g.wide, sa, st);
         }
         if (rc != 0) return rc;
         rc = mark(1);

@@ -78,7 +78,7 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
     }
 }
 
-template <int B, int MODE, bool WIDE>
+template <int B, int MODE, int VARIANT>
 __global__ __launch_bounds__(64, (Tuning<MODE, B>::waves)) void step_kernel(StepArgs sa) {
     __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
     if (blockIdx.x >= sa.nitems) {                       // the workgroups past the end serve fp32 variables
@@ -100,16 +100,20 @@ __global__ __launch_bounds__(64, (Tuning<MODE, B>::waves)) void step_kernel(Step
     a.s = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var)]);
     a.b = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var) + 1]);
     const FmtParams fp = pv.fp;
-    do_chunk<B, MODE, WIDE>(a, fp, sa.oc, it.chunk, lds, sa.ws + item);
+    do_chunk<B, MODE, VARIANT>(a, fp, sa.oc, it.chunk, lds, sa.ws + item);
 }
 
 template <int MODE>
-inline int launch_step_group_mode(uint32_t bits, bool wide, const StepArgs &sa, hipStream_t st) {
+inline int launch_step_group_mode(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st) {
+    if (bits == 8 && variant == 2) {
+        step_kernel<8, MODE, 2><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);
+        return static_cast<int>(hipGetLastError());
+    }
     switch (bits) {
 #define X(BITS)                                                              \
     case BITS:                                                               \
-        if (wide) step_kernel<BITS, MODE, true><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);   \
-        else step_kernel<BITS, MODE, false><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);       \
+        if (variant == 1) step_kernel<BITS, MODE, 1><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);   \
+        else step_kernel<BITS, MODE, 0><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);       \
         break;
         OMC_FOR_EACH_BITS(X)
 #undef X
@@ -119,8 +123,8 @@ inline int launch_step_group_mode(uint32_t bits, bool wide, const StepArgs &sa, 
     return static_cast<int>(hipGetLastError());
 }
 
-int launch_step_group_sgd(uint32_t bits, bool wide, const StepArgs &sa, hipStream_t st);
-int launch_step_group_momentum(uint32_t bits, bool wide, const StepArgs &sa, hipStream_t st);
-int launch_step_group_adam(uint32_t bits, bool wide, const StepArgs &sa, hipStream_t st);
+int launch_step_group_sgd(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st);
+int launch_step_group_momentum(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st);
+int launch_step_group_adam(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st);
 
 }  // namespace omc

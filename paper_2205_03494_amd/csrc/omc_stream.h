@@ -37,7 +37,7 @@ struct OptConst {
 // Per-mode tuning: occupancy target (waves per SIMD; bounds the register budget the compiler may
 // use) and whether the next tile's loads are issued before the current tile is computed.
 #ifndef OMC_TUNE_WAVES_LIGHT
-#define OMC_TUNE_WAVES_LIGHT 4
+#define OMC_TUNE_WAVES_LIGHT 3
 #endif
 #ifndef OMC_TUNE_SCHED_GROUP
 #define OMC_TUNE_SCHED_GROUP 4
@@ -418,25 +418,13 @@ __device__ __forceinline__ void issue_loads(const TileArgs &a, uint64_t e0, uint
     if (MODE == kStepAdam) load_f32_pieces<nt_state>(a.st1 + e0, lane, st.vq);
 }
 
-// Everything after the loads of the full tile at e0 have been issued into `st`.  When PREFETCH,
-// the loads of the next tile are issued into the same registers as soon as they are free, so
-// that they are in flight while this tile is computed.
-template <int B, int MODE, bool WIDE, bool PREFETCH>
-__device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
-                                            uint64_t e0, uint32_t lane, uint32_t *lds, Stage<B, MODE> &st,
-                                            FitAcc &acc) {
-    // hand every lane its 32 consecutive elements
-    uint32_t w[B];
-    float rg[32], rm[32], rv[32];
-    if (MODE != kCompress) code_pieces_to_lanes<B>(st.cq, w, lds, lane);
-    if (MODE == kCompress || MODE >= kStepSgd) pieces_to_lanes(st.gq, rg, lds, lane);
-    if (MODE >= kStepMomentum) pieces_to_lanes(st.mq, rm, lds, lane);
-    if (MODE == kStepAdam) pieces_to_lanes(st.vq, rv, lds, lane);
-
-    if (PREFETCH) issue_loads<B, MODE>(a, e0 + kTileElems, lane, st);
-
-    // the cycle, element by element
-    uint32_t o[B];
+// The cycle over a lane's 32 elements, generic formats: decode -> transform -> update -> round ->
+// pack, and the fit's sums.  w: the lane's B code dwords; rg / rm / rv: gradient (or the values to
+// compress) and optimizer state, updated in place; o: the lane's B output dwords.
+template <int B, int MODE, bool WIDE>
+__device__ __forceinline__ void cycle_generic(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
+                                              uint32_t (&w)[B], float (&rg)[32], float (&rm)[32], float (&rv)[32],
+                                              uint32_t (&o)[B], FitAcc &acc) {
 #pragma unroll
     for (int j = 0; j < B; ++j) o[j] = 0u;
 #pragma unroll
@@ -501,6 +489,121 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
         }
 #endif
     }
+}
+
+// gfx950 OCP FP8 (E4M3) conversions; the selectors must be literal constants for the builtins, the
+// switches below fold away once the surrounding loops are unrolled.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float fp8_to_f32(int w, int byte) {
+    switch (byte) {
+        case 0: return __builtin_amdgcn_cvt_f32_fp8(w, 0);
+        case 1: return __builtin_amdgcn_cvt_f32_fp8(w, 1);
+        case 2: return __builtin_amdgcn_cvt_f32_fp8(w, 2);
+        default: return __builtin_amdgcn_cvt_f32_fp8(w, 3);
+    }
+}
+__device__ __forceinline__ int f32x2_to_fp8_half(float x0, float x1, int old, int half) {
+    return half ? __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, old, true) : __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, old, false);
+}
+__device__ __forceinline__ f32x2 fp8_half_to_f32x2(int w, int half) {
+    return half ? __builtin_amdgcn_cvt_pk_f32_fp8(w, true) : __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
+}
+
+// The same cycle for S1E4M3 with bias 7.  That format is OCP FP8 E4M3 in every code but the top
+// one (0x7F / 0xFF: 480 here, NaN there), and gfx950 converts OCP FP8 in hardware: one
+// instruction decodes a byte, one rounds and packs two values (nearest even, gradual underflow;
+// without saturation every overflow yields exactly the top code, which is also what this format
+// wants), one decodes two codes back for the fit.  13 vector instructions per element instead
+// of 30.  What the hardware cannot give is the *value* of a top code: it reads back as NaN, and a
+// NaN input picks a different sign bit.  Both cases leave a NaN in the lane's sums, so the caller
+// checks for that and redoes such a tile with cycle_generic.  Returns false when a redo is needed.
+// New optimizer state goes to rm / rv only when the result is good.
+template <int MODE>
+__device__ __forceinline__ bool cycle_ocp_e4m3(const TileArgs &a, const OptConst &oc, uint32_t (&w)[8],
+                                               float (&rg)[32], float (&rm)[32], float (&rv)[32],
+                                               uint32_t (&o)[8], FitAcc &acc) {
+    const FitAcc saved = acc;
+    float nm[32], nv[32];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {                          // one code dword = 4 elements
+        pin(w[j]);
+#pragma unroll
+        for (int e = 4 * j; e < 4 * j + 4; ++e) {
+            if (MODE != kDecompress) pin(rg[e]);
+            if (MODE >= kStepMomentum) pin(rm[e]);
+            if (MODE == kStepAdam) pin(rv[e]);
+        }
+        int packed = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {                      // one 16-bit half = 2 elements
+            float x[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int i = 4 * j + 2 * h + q;
+                if (MODE != kCompress) {
+                    const float vt = fp8_to_f32(static_cast<int>(w[j]), 2 * h + q);
+                    const float sv = a.s * vt;
+                    x[q] = sv + a.b;
+                } else {
+                    x[q] = rg[i];
+                }
+                if (MODE >= kStepSgd) {
+                    float m = MODE >= kStepMomentum ? rm[i] : 0.0f, v = MODE == kStepAdam ? rv[i] : 0.0f;
+                    x[q] = apply_update<MODE>(x[q], rg[i], m, v, oc);
+                    if (MODE >= kStepMomentum) nm[i] = m;
+                    if (MODE == kStepAdam) nv[i] = v;
+                }
+            }
+            packed = f32x2_to_fp8_half(x[0], x[1], packed, h);
+            const f32x2 t = fp8_half_to_f32x2(packed, h);
+            if (j == 0 && h == 0) acc.seed(t.x);
+            acc.add(x[0], t.x);
+            acc.add(x[1], t.y);
+        }
+        o[j] = static_cast<uint32_t>(packed);
+        pin(acc.sV); pin(acc.sT); pin(acc.sVT); pin(acc.sTT); pin(acc.diff);
+        pin(o[j]);
+    }
+    const bool bad = (acc.sV != acc.sV) || (acc.sT != acc.sT);
+    if (__any(bad)) {
+        acc = saved;
+        return false;
+    }
+    if (MODE >= kStepMomentum) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) rm[i] = nm[i];
+    }
+    if (MODE == kStepAdam) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) rv[i] = nv[i];
+    }
+    return true;
+}
+
+// Everything after the loads of the full tile at e0 have been issued into `st`.  When PREFETCH,
+// the loads of the next tile are issued into the same registers as soon as they are free, so
+// that they are in flight while this tile is computed.
+template <int B, int MODE, int VARIANT, bool PREFETCH>
+__device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
+                                            uint64_t e0, uint32_t lane, uint32_t *lds, Stage<B, MODE> &st,
+                                            FitAcc &acc) {
+    // hand every lane its 32 consecutive elements
+    uint32_t w[B];
+    float rg[32], rm[32], rv[32];
+    if (MODE != kCompress) code_pieces_to_lanes<B>(st.cq, w, lds, lane);
+    if (MODE == kCompress || MODE >= kStepSgd) pieces_to_lanes(st.gq, rg, lds, lane);
+    if (MODE >= kStepMomentum) pieces_to_lanes(st.mq, rm, lds, lane);
+    if (MODE == kStepAdam) pieces_to_lanes(st.vq, rv, lds, lane);
+
+    if (PREFETCH) issue_loads<B, MODE>(a, e0 + kTileElems, lane, st);
+
+    uint32_t o[B];
+    if constexpr (VARIANT == 2 && B == 8 && MODE != kDecompress) {
+        if (!cycle_ocp_e4m3<MODE>(a, oc, w, rg, rm, rv, o, acc))
+            cycle_generic<B, MODE, false>(a, fp, oc, w, rg, rm, rv, o, acc);
+    } else {
+        cycle_generic<B, MODE, VARIANT == 1>(a, fp, oc, w, rg, rm, rv, o, acc);
+    }
 
     // back to the coalesced layouts and out
     if (MODE == kDecompress) {
@@ -526,7 +629,7 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
 
 // One work item of the full-tile kernels: tiles [chunk*kTilesPerChunk, ...) of one variable, as far
 // as full tiles go, reduced into one Partial.  The caller guarantees at least one full tile.
-template <int B, int MODE, bool WIDE>
+template <int B, int MODE, int VARIANT>
 __device__ __forceinline__ void do_chunk(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
                                          uint32_t chunk, uint32_t *lds, Partial *partial_out) {
     const uint32_t lane = threadIdx.x;
@@ -541,10 +644,10 @@ __device__ __forceinline__ void do_chunk(const TileArgs &a, const FmtParams &fp,
     issue_loads<B, MODE>(a, begin, lane, st);
     for (uint32_t t = 0; t + 1 < ntiles; ++t) {
         const uint64_t e0 = begin + static_cast<uint64_t>(t) * kTileElems;
-        finish_tile<B, MODE, WIDE, Tuning<MODE, B>::prefetch>(a, fp, oc, e0, lane, lds, st, acc);
+        finish_tile<B, MODE, VARIANT, Tuning<MODE, B>::prefetch>(a, fp, oc, e0, lane, lds, st, acc);
         if (!Tuning<MODE, B>::prefetch) issue_loads<B, MODE>(a, e0 + kTileElems, lane, st);
     }
-    finish_tile<B, MODE, WIDE, false>(a, fp, oc, begin + static_cast<uint64_t>(ntiles - 1) * kTileElems, lane,
+    finish_tile<B, MODE, VARIANT, false>(a, fp, oc, begin + static_cast<uint64_t>(ntiles - 1) * kTileElems, lane,
                                       lds, st, acc);
     if (MODE != kDecompress) acc.reduce_and_store(partial_out);
 }
