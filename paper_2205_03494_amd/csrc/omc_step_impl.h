@@ -105,7 +105,8 @@ __global__ __launch_bounds__(64, (Tuning<MODE, B>::waves)) void step_kernel(Step
 
 template <int MODE>
 inline int launch_step_group_mode(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st) {
-    if (bits == 8 && variant == 2) {
+    // the hardware-conversion variant pays off where the vector ALU is the limit: plain SGD
+    if (bits == 8 && variant == 2 && MODE == kStepSgd) {
         step_kernel<8, MODE, 2><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);
         return static_cast<int>(hipGetLastError());
     }

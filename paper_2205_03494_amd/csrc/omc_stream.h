@@ -49,7 +49,7 @@ struct OptConst {
 #define OMC_TUNE_WAVES_MOMENTUM 2
 #endif
 #ifndef OMC_TUNE_WAVES_ADAM
-#define OMC_TUNE_WAVES_ADAM 1
+#define OMC_TUNE_WAVES_ADAM 2
 #endif
 #ifndef OMC_TUNE_PREFETCH_HEAVY
 #define OMC_TUNE_PREFETCH_HEAVY 0
