@@ -19,8 +19,8 @@
 //      fill 128 contiguous bytes, and in the epilogue a lane holds four adjacent columns of C,
 //      one 16-byte store per row.
 // The K loop is double-buffered in LDS: while the matrix cores work on one K step, the codes of the
-// next one are decoded and stored into the other buffer, and the global loads of the step after
-// that are in flight into registers; one workgroup barrier per K step.  When the 256-row tiling
+// next one are decoded and stored into the other buffer, and the global loads of the two steps
+// after that are in flight into two register sets; one workgroup barrier per K step.  When the 256-row tiling
 // would leave compute units idle, a 128-row variant (wave = 32 rows) doubles the number of workgroups.
 #include <hip/hip_runtime.h>
 #include "omc_internal.h"
@@ -38,6 +38,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #ifndef OMC_GEMM_WAVES
 #define OMC_GEMM_WAVES 2
 #endif
+
 constexpr int kBN = 128, kBK = 32;
 constexpr int kWChunkBytes = kBN * 16;   // one k-chunk (8 bf16) of all columns
 
@@ -118,34 +119,38 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
     const uint32_t w_kg = 2 * wave + w_h;
     const uint64_t w_col = n0 + 4 * w_cg;
 
-    u32x4 a_reg[AP];
-    uint32_t w_raw[4][3], w_off[4];
+    // two register sets: global loads run two K steps ahead of the matrix cores
+    struct StageRegs {
+        u32x4 a[AP];
+        uint32_t w_raw[4][3], w_off[4];
+    };
+    StageRegs r0, r1;
 
-    auto load_stage = [&](uint32_t k0) {
+    auto load_stage = [&](StageRegs &r, uint32_t k0) {
 #pragma unroll
         for (int p = 0; p < AP; ++p) {
             const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
-            a_reg[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
+            r.a[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint64_t e = static_cast<uint64_t>(k0 + 4 * w_kg + r) * N + w_col;
-            load_codes4<BYTE>(codes, total_dwords, e, fp.bits, w_raw[r], w_off[r]);
+        for (int rr = 0; rr < 4; ++rr) {
+            const uint64_t e = static_cast<uint64_t>(k0 + 4 * w_kg + rr) * N + w_col;
+            load_codes4<BYTE>(codes, total_dwords, e, fp.bits, r.w_raw[rr], r.w_off[rr]);
         }
     };
 
-    auto store_stage = [&](uint8_t *ldsA) {
+    auto store_stage = [&](const StageRegs &r, uint8_t *ldsA) {
         uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
 #pragma unroll
         for (int p = 0; p < AP; ++p) {
             const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
-            *reinterpret_cast<u32x4 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4)) = a_reg[p];
+            *reinterpret_cast<u32x4 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4)) = r.a[p];
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {                       // column 4 cg + i of the patch
             uint32_t v[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] = decode_bits(code_top_of<BYTE>(w_raw[r], w_off[r], fp.bits, i), fp);
+            for (int rr = 0; rr < 4; ++rr) v[rr] = decode_bits(code_top_of<BYTE>(r.w_raw[rr], r.w_off[rr], fp.bits, i), fp);
             u32x2 out;
             out[0] = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);   // bf16(v0) | bf16(v1) << 16
             out[1] = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
@@ -162,13 +167,7 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
     const uint32_t f_row = lane & 31u, f_half = lane >> 5;   // fragment roles
-    const uint32_t nk = K / kBK;
-    load_stage(0);
-    store_stage(lds);
-    __syncthreads();
-    if (nk > 1) load_stage(kBK);
-    for (uint32_t it = 0; it < nk; ++it) {
-        const uint8_t *ldsA = lds + (it & 1u) * kStageBytes;
+    auto multiply_stage = [&](const uint8_t *ldsA) {
         const uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -188,21 +187,47 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
                 for (int ni = 0; ni < 4; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
         }
-        // the next K step goes into the other buffer (nobody reads it any more: barrier of the previous round)
-        if (it + 1 < nk) store_stage(lds + ((it + 1) & 1u) * kStageBytes);
+    };
+
+    const uint32_t nk = K / kBK;
+    uint8_t *buf0 = lds, *buf1 = lds + kStageBytes;
+    load_stage(r0, 0);
+    store_stage(r0, buf0);
+    __syncthreads();
+    if (nk > 1) load_stage(r0, kBK);
+    if (nk > 2) load_stage(r1, 2 * kBK);
+    // Invariant at the top of an even round `it`: buf0 holds K step it, r0 step it+1, r1 step it+2.
+    for (uint32_t it = 0; it < nk; it += 2) {
+        multiply_stage(buf0);
+        if (it + 1 < nk) store_stage(r0, buf1);            // nobody reads buf1 any more (barrier of the round before)
         __syncthreads();
-        if (it + 2 < nk) load_stage((it + 2) * kBK);
+        if (it + 3 < nk) load_stage(r0, (it + 3) * kBK);
+        if (it + 1 < nk) {
+            multiply_stage(buf1);
+            if (it + 2 < nk) store_stage(r1, buf0);
+            __syncthreads();
+            if (it + 4 < nk) load_stage(r1, (it + 4) * kBK);
+        }
     }
 
     // ---- epilogue: C = s * acc + b * rowsum --------------------------------------------------------
     const float s = sb ? sb[0] : 1.0f;
     const float b = sb ? sb[1] : 0.0f;
+    // a lane's accumulators cover rows in runs of four: fetch all row sums it needs in one batch
+    f32x4 rs[MI][4];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t row = m0 + 32 * MI * wave + 32 * mi + 8 * g + 4 * f_half;
+            rs[mi][g] = sb ? *reinterpret_cast<const f32x4 *>(rowsum + row) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const uint32_t row = m0 + 32 * MI * wave + 32 * mi + 8 * (v >> 2) + 4 * f_half + (v & 3);
-            const float add = sb ? b * rowsum[row] : 0.0f;
+            const float add = sb ? b * rs[mi][v >> 2][v & 3] : 0.0f;
             f32x4 out;
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni) out[ni] = s * acc[mi][ni][v] + add;
