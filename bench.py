@@ -39,20 +39,13 @@ def build_workload(torch, omc, synth, blocks, d_model, ffn, seed=0):
     arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
     sb = torch.zeros((len(specs), 2), dtype=torch.float32, device="cuda")
     sb[:, 0] = 1.0
-    nmax = max(s.n for s in specs)
-    ws = torch.empty(max(omc.omc_compress_workspace_bytes(nmax), 16), dtype=torch.uint8, device="cuda")
-    table = []
-    for i, s in enumerate(specs):
-        a, d = int(lay.aux_offset[i]), int(lay.data_offset[i])
-        if mask[i]:
-            nb = omc.omc_packed_bytes(gf, s.n)
-            omc.omc_compress(vals_d[a:a + s.n], s.n, gf, True, arena[d:d + nb], sb[i], ws)
-        else:
-            arena[d:d + 4 * s.n] = vals_d[a:a + s.n].view(torch.uint8)
-        table.append(dict(data_offset=d, aux_offset=a, n=s.n, fmt=gf, quantized=bool(mask[i])))
+    table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gf,
+                  quantized=bool(mask[i])) for i, s in enumerate(specs)]
     plan = omc.omc_plan_build(omc.make_var_table(table))
+    ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    omc.omc_compress_set(vals_d, plan, arena, sb, ws)
     torch.cuda.synchronize()
-    return dict(specs=specs, mask=mask, lay=lay, vals=vals, arena=arena, sb=sb, plan=plan, table=table)
+    return dict(specs=specs, mask=mask, lay=lay, vals=vals, vals_d=vals_d, arena=arena, sb=sb, plan=plan, table=table)
 
 
 def cpu_baseline(wl, synth, sample_blocks, iters, threads, gpu_after=None):
@@ -139,6 +132,33 @@ def gemm_leg(torch, omc, synth, iters=20):
         out.append({"M": M, "N": N, "K": K, "ms": ms, "TFLOPs": tf, "frac_of_bf16_mfma_peak": tf / 2500.0,
                     "hbm_bytes": 2 * M * K + K * N + 4 * M * N})
     return out
+
+
+def set_conversion_leg(torch, omc, wl, n_q, n_f, iters=20):
+    """Whole-set conversions (start / end of a round): fp32 -> packed arena and back, one call each."""
+    lay, plan = wl["lay"], wl["plan"]
+    arena = torch.empty_like(wl["arena"])
+    sb = torch.empty_like(wl["sb"])
+    out = torch.empty(lay.aux_elems, device="cuda")
+    ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    res = {}
+    for name, fn, nbytes in (
+            ("compress_set", lambda: omc.omc_compress_set(wl["vals_d"], plan, arena, sb, ws), 5.0 * n_q + 8.0 * n_f),
+            ("decompress_set", lambda: omc.omc_decompress_set(arena, plan, sb, out), 5.0 * n_q + 8.0 * n_f)):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        res[name] = {"ms": ms, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    res["transport_bytes"] = plan.transport_bytes
+    res["transport_over_fp32"] = plan.transport_bytes / (4.0 * (n_q + n_f))
+    return res
 
 
 def main():
@@ -289,6 +309,7 @@ def main():
     }
     del grads, arena0
     torch.cuda.empty_cache()
+    out["set_conversions"] = set_conversion_leg(torch, omc, wl, n_q, n_f)
     out["forward_gemm"] = gemm_leg(torch, omc, synth)
     if cpu is not None:
         out["cpu_baseline"] = {

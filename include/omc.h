@@ -188,6 +188,26 @@ omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const voi
                                       float *state0, float *state1, uint64_t aux_elems,
                                       const omc_opt *opt, void *ws, size_t ws_bytes, void *stream);
 
+/* Whole-set conversion between fp32 and the plan's storage (the start and the end of a round: a
+ * client receives or returns a model; Sec. 2.5 lets the set of quantized variables change from
+ * round to round, which is a decompress with the old plan followed by a compress with the new one).
+ *   omc_compress_set     for every quantized variable of the plan: compress the n floats at
+ *                        values[aux_offset ..] into the arena and write its (s, b); for every fp32
+ *                        variable: copy its floats into the arena.  Bit-identical to calling
+ *                        omc_compress per variable.
+ *   omc_decompress_set   the reverse: out[aux_offset ..] = decompressed values (or the fp32 copy).
+ * values / out: device, aux_elems floats (at least what the plan addresses), must not overlap the
+ * arena.  ws as for the step.  sb_table: device, 2*nvars floats.
+ *   omc_plan_transport_bytes   bytes that represent the variable set in storage or on the wire
+ *                        (Sec. 1: communication cost equals parameter memory): packed buffer plus
+ *                        8 bytes of (s, b) per quantized variable, 4n per fp32 variable. */
+omc_status omc_compress_set(const float *values, uint64_t aux_elems, const void *plan_host, const void *plan_dev,
+                            void *arena, size_t arena_bytes, float *sb_table, void *ws, size_t ws_bytes,
+                            void *stream);
+omc_status omc_decompress_set(const void *arena, size_t arena_bytes, const void *plan_host, const void *plan_dev,
+                              const float *sb_table, float *out, uint64_t aux_elems, void *stream);
+uint64_t omc_plan_transport_bytes(const void *plan_host);
+
 /* Measurement aid.  Same work as omc_step_update_recompress; additionally records caller-owned HIP
  * events (hipEvent_t passed as void*) on the stream around every kernel launch, so that a
  * benchmark can time each kernel by itself: events[2k] before and events[2k+1] after the k-th

@@ -374,6 +374,50 @@ omc_status omc_step_update_recompress(void *arena, size_t arena_bytes, const voi
                                              nullptr, 0);
 }
 
+omc_status omc_compress_set(const float *values, uint64_t aux_elems, const void *plan_host, const void *plan_dev,
+                            void *arena, size_t arena_bytes, float *sb_table, void *ws, size_t ws_bytes,
+                            void *stream) {
+    if (!values || !plan_host || !plan_dev || !arena || !sb_table) return OMC_ERR_NULL;
+    const PlanHeader *ph = plan_check(plan_host);
+    if (!ph) return OMC_ERR_PLAN;
+    if (arena_bytes < ph->arena_bytes || aux_elems < ph->aux_elems) return OMC_ERR_SIZE;
+    if (!aligned16(values) || !aligned16(arena) || !aligned16(plan_dev) ||
+        (reinterpret_cast<uintptr_t>(sb_table) & 7u))
+        return OMC_ERR_ALIGN;
+    if (!ws || ws_bytes < ph->ws_bytes) return OMC_ERR_WORKSPACE;
+    if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    const uintptr_t v0 = reinterpret_cast<uintptr_t>(values), a0 = reinterpret_cast<uintptr_t>(arena);
+    if (v0 < a0 + ph->arena_bytes && a0 < v0 + 4 * ph->aux_elems) return OMC_ERR_SIZE;   // overlap
+    const int rc = launch_compress_set(values, ph, plan_dev, arena, sb_table, static_cast<Partial *>(ws), stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+omc_status omc_decompress_set(const void *arena, size_t arena_bytes, const void *plan_host, const void *plan_dev,
+                              const float *sb_table, float *out, uint64_t aux_elems, void *stream) {
+    if (!arena || !plan_host || !plan_dev || !sb_table || !out) return OMC_ERR_NULL;
+    const PlanHeader *ph = plan_check(plan_host);
+    if (!ph) return OMC_ERR_PLAN;
+    if (arena_bytes < ph->arena_bytes || aux_elems < ph->aux_elems) return OMC_ERR_SIZE;
+    if (!aligned16(out) || !aligned16(arena) || !aligned16(plan_dev) ||
+        (reinterpret_cast<uintptr_t>(sb_table) & 7u))
+        return OMC_ERR_ALIGN;
+    const uintptr_t o0 = reinterpret_cast<uintptr_t>(out), a0 = reinterpret_cast<uintptr_t>(arena);
+    if (o0 < a0 + ph->arena_bytes && a0 < o0 + 4 * ph->aux_elems) return OMC_ERR_SIZE;   // overlap
+    const int rc = launch_decompress_set(arena, ph, plan_dev, sb_table, out, stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+uint64_t omc_plan_transport_bytes(const void *plan_host) {
+    const PlanHeader *ph = plan_check(plan_host);
+    if (!ph) return 0;
+    const uint8_t *b = reinterpret_cast<const uint8_t *>(ph);
+    const PlanVar *pv = reinterpret_cast<const PlanVar *>(b + ph->var_off);
+    uint64_t total = 0;
+    for (uint32_t i = 0; i < ph->nvars; ++i)
+        total += (pv[i].flags & OMC_VAR_QUANTIZED) ? pv[i].total_dwords * 4 + 8 : 4 * pv[i].n;
+    return total;
+}
+
 size_t omc_dequant_gemm_workspace_bytes(uint32_t M) {
     return M == 0 ? 0 : (static_cast<size_t>(M) * sizeof(float) + 15) / 16 * 16;
 }

@@ -1,36 +1,7 @@
-// omc_compress: fp32 variable -> packed codes + partial sums of the fit, then (s, b).
-#include "omc_stream.h"
+// omc_compress / omc_compress_set: fp32 values -> packed codes + partial sums of the fit, then (s, b).
+#include "omc_codec_impl.h"
 
 namespace omc {
-
-template <int B, int VARIANT>
-__global__ __launch_bounds__(64, (Tuning<kCompress, B>::waves)) void compress_kernel(
-    const float *__restrict__ v, uint32_t *__restrict__ codes, VarArgs va, Partial *__restrict__ ws) {
-    __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
-    TileArgs a{};
-    a.codes = codes;
-    a.total_dwords = va.total_dwords;
-    a.vin = v;
-    a.n = va.n;
-    a.s = 1.0f;
-    a.b = 0.0f;
-    OptConst oc{};
-    do_chunk<B, kCompress, VARIANT>(a, va.fp, oc, blockIdx.x, lds, ws + blockIdx.x);
-}
-
-template <bool WIDE>
-__global__ __launch_bounds__(64) void compress_tail_kernel(const float *__restrict__ v, uint32_t *__restrict__ codes,
-                                                           VarArgs va, Partial *__restrict__ tail_partial) {
-    TileArgs a{};
-    a.codes = codes;
-    a.total_dwords = va.total_dwords;
-    a.vin = v;
-    a.n = va.n;
-    a.s = 1.0f;
-    a.b = 0.0f;
-    OptConst oc{};
-    do_tail<kCompress, WIDE>(a, va.fp, oc, tail_partial);
-}
 
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void finalize_single_kernel(const Partial *__restrict__ ws, uint32_t nparts,
@@ -40,36 +11,53 @@ __global__ __launch_bounds__(64 * NW) void finalize_single_kernel(const Partial 
     finalize_variable<NW>(ws, nparts, has_tail ? ws + nparts : nullptr, n, use_pvt != 0, sb, red);
 }
 
+// One full-tile launch: `grid` workgroups of the kernel for (bits, variant).
+static int launch_full(uint32_t bits, uint32_t variant, uint32_t grid, const CodecArgs &ca, hipStream_t st) {
+    if (bits == 8 && variant == 2) {
+        codec_kernel<8, kCompress, 2><<<dim3(grid), dim3(64), 0, st>>>(ca);
+        return static_cast<int>(hipGetLastError());
+    }
+    switch (bits) {
+#define X(BITS)                                                                                  \
+    case BITS:                                                                                   \
+        if (variant == 1) codec_kernel<BITS, kCompress, 1><<<dim3(grid), dim3(64), 0, st>>>(ca); \
+        else codec_kernel<BITS, kCompress, 0><<<dim3(grid), dim3(64), 0, st>>>(ca);              \
+        break;
+        OMC_FOR_EACH_BITS(X)
+#undef X
+        default:
+            return static_cast<int>(hipErrorInvalidValue);
+    }
+    return static_cast<int>(hipGetLastError());
+}
+
+static int launch_tail(bool wide, uint32_t grid, const CodecArgs &ca, hipStream_t st) {
+    if (wide) codec_tail_kernel<kCompress, true><<<dim3(grid), dim3(64), 0, st>>>(ca);
+    else codec_tail_kernel<kCompress, false><<<dim3(grid), dim3(64), 0, st>>>(ca);
+    return static_cast<int>(hipGetLastError());
+}
+
 int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb, Partial *ws,
                     void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
     const bool has_tail = (va.n % kTileElems) != 0;
-    uint32_t *c = static_cast<uint32_t *>(codes);
-    if (nchunks > 0 && va.fp.variant == 2) {
-        compress_kernel<8, 2><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return static_cast<int>(e);
-    } else if (nchunks > 0) {
-        switch (va.fp.bits) {
-#define X(BITS)                                                                                 \
-    case BITS:                                                                                  \
-        if (va.fp.variant == 1) compress_kernel<BITS, 1><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws); \
-        else compress_kernel<BITS, 0><<<dim3(nchunks), dim3(64), 0, st>>>(v, c, va, ws);        \
-        break;
-            OMC_FOR_EACH_BITS(X)
-#undef X
-            default:
-                return static_cast<int>(hipErrorInvalidValue);
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return static_cast<int>(e);
+    CodecArgs ca{};
+    ca.arena = static_cast<uint8_t *>(codes);
+    ca.single.n = va.n;
+    ca.single.total_dwords = va.total_dwords;
+    ca.single.fp = va.fp;
+    ca.vin = v;
+    ca.ws = ws;
+    ca.nitems = nchunks;
+    if (nchunks > 0) {
+        const int rc = launch_full(va.fp.bits, va.fp.variant, nchunks, ca, st);
+        if (rc != 0) return rc;
     }
     if (has_tail) {
-        if (va.fp.wide) compress_tail_kernel<true><<<dim3(1), dim3(64), 0, st>>>(v, c, va, ws + nchunks);
-        else compress_tail_kernel<false><<<dim3(1), dim3(64), 0, st>>>(v, c, va, ws + nchunks);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return static_cast<int>(e);
+        ca.first_item = nchunks;                       // the tail's partial slot
+        const int rc = launch_tail(va.fp.wide != 0, 1, ca, st);
+        if (rc != 0) return rc;
     }
     // the width of the reduction depends on the size alone, so results do not depend on the run
     if (nchunks <= 256)
@@ -77,6 +65,63 @@ int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes,
     else
         finalize_single_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
     return static_cast<int>(hipGetLastError());
+}
+
+int launch_compress_set(const float *values, const PlanHeader *ph, const void *plan_dev, void *arena,
+                        float *sb_table, Partial *ws, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *ph_bytes = reinterpret_cast<const uint8_t *>(ph);
+    const PlanGroup *groups = reinterpret_cast<const PlanGroup *>(ph_bytes + ph->group_off);
+    CodecArgs ca{};
+    ca.arena = static_cast<uint8_t *>(arena);
+    ca.plan = static_cast<const uint8_t *>(plan_dev);
+    ca.var_off = ph->var_off;
+    ca.item_off = ph->item_off;
+    ca.vin = values;
+    ca.ws = ws;
+    const PlanGroup *fp32_group = nullptr;
+    bool any_full = false;
+    for (uint32_t gi = 0; gi < ph->ngroups; ++gi) {
+        if (groups[gi].kind == kGroupFp32 && groups[gi].nitems > 0) fp32_group = &groups[gi];
+        if (groups[gi].kind == kGroupFull && groups[gi].nitems > 0) any_full = true;
+    }
+    bool fp32_done = (fp32_group == nullptr);
+    for (uint32_t gi = 0; gi < ph->ngroups; ++gi) {
+        const PlanGroup &g = groups[gi];
+        if (g.nitems == 0 || g.kind == kGroupFp32) continue;
+        ca.first_item = g.first_item;
+        ca.nitems = g.nitems;
+        ca.fp32_first = 0;
+        ca.fp32_nitems = 0;
+        int rc;
+        if (g.kind == kGroupFull) {
+            if (!fp32_done) {                          // the fp32 copies ride along with the first full-tile launch
+                ca.fp32_first = fp32_group->first_item;
+                ca.fp32_nitems = fp32_group->nitems;
+                fp32_done = true;
+            }
+            rc = launch_full(g.bits, g.wide, g.nitems + ca.fp32_nitems, ca, st);
+        } else {
+            rc = launch_tail(g.wide != 0, g.nitems, ca, st);
+        }
+        if (rc != 0) return rc;
+    }
+    if (!fp32_done) {                                  // no full-tile launch to ride on: a launch of copies alone
+        (void)any_full;
+        ca.first_item = 0;
+        ca.nitems = 0;
+        ca.fp32_first = fp32_group->first_item;
+        ca.fp32_nitems = fp32_group->nitems;
+        codec_kernel<8, kCompress, 0><<<dim3(fp32_group->nitems), dim3(64), 0, st>>>(ca);
+        const int rc = static_cast<int>(hipGetLastError());
+        if (rc != 0) return rc;
+    }
+    if (ph->nquant > 0) {
+        finalize_plan_kernel<kFinalizeWaves><<<dim3(ph->nvars), dim3(64 * kFinalizeWaves), 0, st>>>(
+            ca.plan, ph->var_off, ws, sb_table);
+        return static_cast<int>(hipGetLastError());
+    }
+    return 0;
 }
 
 }  // namespace omc

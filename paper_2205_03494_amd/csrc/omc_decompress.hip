@@ -1,56 +1,87 @@
-// omc_decompress: packed codes + (s, b) -> fp32.
-#include "omc_stream.h"
+// omc_decompress / omc_decompress_set: packed codes + (s, b) -> fp32.
+#include "omc_codec_impl.h"
 
 namespace omc {
 
-template <int B>
-__global__ __launch_bounds__(64, (Tuning<kDecompress, B>::waves)) void decompress_kernel(
-    const uint32_t *__restrict__ codes, VarArgs va, const float *__restrict__ sb, float *__restrict__ out) {
-    __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
-    TileArgs a{};
-    a.codes = const_cast<uint32_t *>(codes);   // never written in this mode
-    a.total_dwords = va.total_dwords;
-    a.vout = out;
-    a.n = va.n;
-    a.s = sb ? to_scalar_regs(sb[0]) : 1.0f;
-    a.b = sb ? to_scalar_regs(sb[1]) : 0.0f;
-    OptConst oc{};
-    do_chunk<B, kDecompress, 0>(a, va.fp, oc, blockIdx.x, lds, nullptr);
-}
-
-__global__ __launch_bounds__(64) void decompress_tail_kernel(const uint32_t *__restrict__ codes, VarArgs va,
-                                                             const float *__restrict__ sb, float *__restrict__ out) {
-    TileArgs a{};
-    a.codes = const_cast<uint32_t *>(codes);
-    a.total_dwords = va.total_dwords;
-    a.vout = out;
-    a.n = va.n;
-    a.s = sb ? to_scalar_regs(sb[0]) : 1.0f;
-    a.b = sb ? to_scalar_regs(sb[1]) : 0.0f;
-    OptConst oc{};
-    do_tail<kDecompress, false>(a, va.fp, oc, nullptr);
+static int launch_full(uint32_t bits, uint32_t grid, const CodecArgs &ca, hipStream_t st) {
+    switch (bits) {
+#define X(BITS)                                                                       \
+    case BITS:                                                                        \
+        codec_kernel<BITS, kDecompress, 0><<<dim3(grid), dim3(64), 0, st>>>(ca);      \
+        break;
+        OMC_FOR_EACH_BITS(X)
+#undef X
+        default:
+            return static_cast<int>(hipErrorInvalidValue);
+    }
+    return static_cast<int>(hipGetLastError());
 }
 
 int launch_decompress(const void *codes, const VarArgs &va, const float *sb, float *out, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
-    const uint32_t *c = static_cast<const uint32_t *>(codes);
+    CodecArgs ca{};
+    ca.arena = static_cast<uint8_t *>(const_cast<void *>(codes));   // never written in this mode
+    ca.single.n = va.n;
+    ca.single.total_dwords = va.total_dwords;
+    ca.single.fp = va.fp;
+    ca.sb_in = sb;
+    ca.vout = out;
+    ca.nitems = nchunks;
     if (nchunks > 0) {
-        switch (va.fp.bits) {
-#define X(BITS)                                                                        \
-    case BITS:                                                                         \
-        decompress_kernel<BITS><<<dim3(nchunks), dim3(64), 0, st>>>(c, va, sb, out);   \
-        break;
-            OMC_FOR_EACH_BITS(X)
-#undef X
-            default:
-                return static_cast<int>(hipErrorInvalidValue);
-        }
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return static_cast<int>(e);
+        const int rc = launch_full(va.fp.bits, nchunks, ca, st);
+        if (rc != 0) return rc;
     }
     if (va.n % kTileElems) {
-        decompress_tail_kernel<<<dim3(1), dim3(64), 0, st>>>(c, va, sb, out);
+        codec_tail_kernel<kDecompress, false><<<dim3(1), dim3(64), 0, st>>>(ca);
+        return static_cast<int>(hipGetLastError());
+    }
+    return 0;
+}
+
+int launch_decompress_set(const void *arena, const PlanHeader *ph, const void *plan_dev, const float *sb_table,
+                          float *out, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t *ph_bytes = reinterpret_cast<const uint8_t *>(ph);
+    const PlanGroup *groups = reinterpret_cast<const PlanGroup *>(ph_bytes + ph->group_off);
+    CodecArgs ca{};
+    ca.arena = static_cast<uint8_t *>(const_cast<void *>(arena));
+    ca.plan = static_cast<const uint8_t *>(plan_dev);
+    ca.var_off = ph->var_off;
+    ca.item_off = ph->item_off;
+    ca.sb_in = sb_table;
+    ca.vout = out;
+    const PlanGroup *fp32_group = nullptr;
+    for (uint32_t gi = 0; gi < ph->ngroups; ++gi)
+        if (groups[gi].kind == kGroupFp32 && groups[gi].nitems > 0) fp32_group = &groups[gi];
+    bool fp32_done = (fp32_group == nullptr);
+    for (uint32_t gi = 0; gi < ph->ngroups; ++gi) {
+        const PlanGroup &g = groups[gi];
+        if (g.nitems == 0 || g.kind == kGroupFp32) continue;
+        ca.first_item = g.first_item;
+        ca.nitems = g.nitems;
+        ca.fp32_first = 0;
+        ca.fp32_nitems = 0;
+        int rc;
+        if (g.kind == kGroupFull) {
+            if (!fp32_done) {
+                ca.fp32_first = fp32_group->first_item;
+                ca.fp32_nitems = fp32_group->nitems;
+                fp32_done = true;
+            }
+            rc = launch_full(g.bits, g.nitems + ca.fp32_nitems, ca, st);
+        } else {
+            codec_tail_kernel<kDecompress, false><<<dim3(g.nitems), dim3(64), 0, st>>>(ca);
+            rc = static_cast<int>(hipGetLastError());
+        }
+        if (rc != 0) return rc;
+    }
+    if (!fp32_done) {
+        ca.first_item = 0;
+        ca.nitems = 0;
+        ca.fp32_first = fp32_group->first_item;
+        ca.fp32_nitems = fp32_group->nitems;
+        codec_kernel<8, kDecompress, 0><<<dim3(fp32_group->nitems), dim3(64), 0, st>>>(ca);
         return static_cast<int>(hipGetLastError());
     }
     return 0;

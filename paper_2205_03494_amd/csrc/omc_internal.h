@@ -102,6 +102,10 @@ struct VarArgs {
 int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb,
                     Partial *ws, void *stream);
 int launch_decompress(const void *codes, const VarArgs &va, const float *sb, float *out, void *stream);
+int launch_compress_set(const float *values, const PlanHeader *ph, const void *plan_dev, void *arena,
+                        float *sb_table, Partial *ws, void *stream);
+int launch_decompress_set(const void *arena, const PlanHeader *ph, const void *plan_dev, const float *sb_table,
+                          float *out, void *stream);
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table,
                 const float *grads, float *state0, float *state1, const omc_opt &opt, Partial *ws,
                 void *stream, void *const *events);

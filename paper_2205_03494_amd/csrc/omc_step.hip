@@ -37,22 +37,6 @@ static int launch_tail(bool wide, const StepArgs &sa, hipStream_t st) {
     return static_cast<int>(hipGetLastError());
 }
 
-// One wave per variable: new (s, b) of every quantized variable from its chunks' partials.
-constexpr int kFinalizeWaves = 4;
-__global__ __launch_bounds__(64 * kFinalizeWaves) void finalize_plan_kernel(const uint8_t *__restrict__ plan,
-                                                                            uint64_t var_off,
-                                                                            const Partial *__restrict__ ws,
-                                                                            float *__restrict__ sb_table) {
-    __shared__ double red[kFinalizeWaves * 10];
-    const PlanVar *vars = reinterpret_cast<const PlanVar *>(plan + var_off);
-    const PlanVar pv = to_scalar_regs(vars[blockIdx.x]);
-    if (!(pv.flags & OMC_VAR_QUANTIZED)) return;
-    finalize_variable<kFinalizeWaves>(pv.nitems ? ws + pv.first_item : ws, pv.nitems,
-                                      pv.tail_item != kNoItem ? ws + pv.tail_item : nullptr, pv.n,
-                                      !(pv.flags & OMC_VAR_NO_PVT),
-                                      sb_table + 2 * static_cast<uint64_t>(blockIdx.x), red);
-}
-
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table, const float *grads,
                 float *state0, float *state1, const omc_opt &opt, Partial *ws, void *stream,
                 void *const *events) {
@@ -124,7 +108,7 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     if (ph->nquant > 0) {
         int rc = mark(0);
         if (rc != 0) return rc;
-        finalize_plan_kernel<<<dim3(ph->nvars), dim3(64 * kFinalizeWaves), 0, st>>>(sa.plan, ph->var_off, ws, sb_table);
+        finalize_plan_kernel<kFinalizeWaves><<<dim3(ph->nvars), dim3(64 * kFinalizeWaves), 0, st>>>(sa.plan, ph->var_off, ws, sb_table);
         rc = static_cast<int>(hipGetLastError());
         if (rc != 0) return rc;
         return mark(1);

@@ -829,6 +829,21 @@ __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ pa
     sb_out[1] = static_cast<float>(b);
 }
 
+// One workgroup of NW waves per variable: new (s, b) of every quantized variable of a plan.
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void finalize_plan_kernel(const uint8_t *__restrict__ plan, uint64_t var_off,
+                                                                const Partial *__restrict__ ws,
+                                                                float *__restrict__ sb_table) {
+    __shared__ double red[NW * 10];
+    const PlanVar *vars = reinterpret_cast<const PlanVar *>(plan + var_off);
+    const PlanVar pv = to_scalar_regs(vars[blockIdx.x]);
+    if (!(pv.flags & OMC_VAR_QUANTIZED)) return;
+    finalize_variable<NW>(pv.nitems ? ws + pv.first_item : ws, pv.nitems,
+                          pv.tail_item != kNoItem ? ws + pv.tail_item : nullptr, pv.n,
+                          !(pv.flags & OMC_VAR_NO_PVT), sb_table + 2 * static_cast<uint64_t>(blockIdx.x), red);
+}
+constexpr int kFinalizeWaves = 4;
+
 // ---- dispatch over the code width ---------------------------------------------------------------------
 #define OMC_FOR_EACH_BITS(X)                                                                       \
     X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17) X(18)  \

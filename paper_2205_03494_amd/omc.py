@@ -74,6 +74,9 @@ _step = _sig("omc_step_update_recompress", C.c_int, _vp, C.c_size_t, _vp, _vp, _
 _plan_launches = _sig("omc_plan_launches", C.c_uint32, _vp)
 _step_ev = _sig("omc_step_update_recompress_events", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, _vp,
                 _vp, C.c_uint64, C.POINTER(omc_opt), _vp, C.c_size_t, _vp, _vp, C.c_uint32)
+_compress_set = _sig("omc_compress_set", C.c_int, _vp, C.c_uint64, _vp, _vp, _vp, C.c_size_t, _vp, _vp, C.c_size_t, _vp)
+_decompress_set = _sig("omc_decompress_set", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, C.c_uint64, _vp)
+_plan_transport = _sig("omc_plan_transport_bytes", C.c_uint64, _vp)
 _gemm_ws = _sig("omc_dequant_gemm_workspace_bytes", C.c_size_t, C.c_uint32)
 _gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
              C.c_uint32, _vp, C.c_size_t, _vp)
@@ -82,7 +85,8 @@ EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_
             "omc_packed_bytes", "omc_compress_workspace_bytes", "omc_compress", "omc_decompress",
             "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_plan_arena_bytes",
             "omc_plan_aux_elems", "omc_plan_launches", "omc_step_update_recompress",
-            "omc_step_update_recompress_events", "omc_dequant_gemm_workspace_bytes",
+            "omc_step_update_recompress_events", "omc_compress_set", "omc_decompress_set",
+            "omc_plan_transport_bytes", "omc_dequant_gemm_workspace_bytes",
             "omc_dequant_gemm"]
 
 
@@ -171,6 +175,10 @@ class Plan:
         return _plan_ws(self.host.ctypes.data)
 
     @property
+    def transport_bytes(self) -> int:
+        return _plan_transport(self.host.ctypes.data)
+
+    @property
     def launches(self) -> int:
         return _plan_launches(self.host.ctypes.data)
 
@@ -209,6 +217,20 @@ def omc_step_update_recompress(arena: torch.Tensor, plan: Plan, sb_table: torch.
                  _ptr(plan.dev), _ptr(sb_table), _ptr(grads), _ptr(state0), _ptr(state1),
                  grads.numel(), C.byref(o), _ptr(ws), ws.numel() * ws.element_size(),
                  _stream(stream)), "omc_step_update_recompress")
+
+
+def omc_compress_set(values: torch.Tensor, plan: Plan, arena: torch.Tensor, sb_table: torch.Tensor,
+                     ws: torch.Tensor, stream=None) -> None:
+    _check(_compress_set(_ptr(values), values.numel(), plan.host.ctypes.data, _ptr(plan.dev), _ptr(arena),
+                         arena.numel() * arena.element_size(), _ptr(sb_table), _ptr(ws),
+                         ws.numel() * ws.element_size(), _stream(stream)), "omc_compress_set")
+
+
+def omc_decompress_set(arena: torch.Tensor, plan: Plan, sb_table: torch.Tensor, out: torch.Tensor,
+                       stream=None) -> None:
+    _check(_decompress_set(_ptr(arena), arena.numel() * arena.element_size(), plan.host.ctypes.data,
+                           _ptr(plan.dev), _ptr(sb_table), _ptr(out), out.numel(), _stream(stream)),
+           "omc_decompress_set")
 
 
 class HipEvents:

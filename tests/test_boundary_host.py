@@ -155,3 +155,43 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert omc._gemm(A, A, omc.fmt(5, 10), None, A, 256, 256, 64, A, 4096, None) == 2
     assert omc._gemm(A, A, f, None, A, 100, 256, 64, A, 4096, None) == 3
     assert omc._gemm(A, A, f, None, A, 256, 256, 64, A, 16, None) == 5
+
+
+def test_transport_bytes_reproduce_the_papers_memory_ratios():
+    """Packed-size accounting of the library itself against Tables 1 and 2 (90 % of the weight matrices
+    quantized; parameter memory = communication cost)."""
+    specs = synth.conformer_varset(512, 17, 2048, 32)
+    n_total = sum(s.n for s in specs)
+    for E, M, paper_ratio in ((4, 14, 301 / 474), (3, 7, 224 / 548), (2, 3, 147 / 548)):
+        f = omc.fmt(E, M)
+        ratios = []
+        for seed in range(6):
+            mask = synth.ppq_mask(specs, 0.9, seed)
+            lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(f, n))
+            vs = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=f,
+                       quantized=bool(mask[i])) for i, s in enumerate(specs)]
+            size, st, buf = _plan_status(vs)
+            assert st == 0
+            tb = omc._plan_transport(buf.ctypes.data)
+            assert tb == sum(omc.omc_packed_bytes(f, s.n) + 8 if q else 4 * s.n for s, q in zip(specs, mask))
+            ratios.append(tb / (4.0 * n_total))
+        assert abs(np.mean(ratios) - paper_ratio) < 0.015
+
+
+def test_set_entry_points_reject_bad_arguments():
+    f = omc.fmt(4, 3)
+    A = 0x1000
+    vs = [dict(data_offset=0, aux_offset=0, n=5000, fmt=f, quantized=True)]
+    size, st, buf = _plan_status(vs)
+    ph = buf.ctypes.data
+    assert omc._compress_set(None, 5000, ph, A, 0x100000, 1 << 20, A, A, 4096, None) == 1
+    assert omc._compress_set(A, 10, ph, A, 0x100000, 1 << 20, A, A, 4096, None) == 3
+    assert omc._compress_set(A, 5000, ph, A, 0x100000, 16, A, A, 4096, None) == 3
+    assert omc._compress_set(A, 5000, ph, A, 0x100000, 1 << 20, A, A, 8, None) == 5
+    assert omc._compress_set(A, 5000, ph, A, A + 16, 1 << 20, A, A, 4096, None) == 3      # values overlap the arena
+    assert omc._compress_set(A + 4, 5000, ph, A, 0x100000, 1 << 20, A, A, 4096, None) == 4
+    assert omc._decompress_set(A, 1 << 20, ph, A, None, 0x100000, 5000, None) == 1
+    assert omc._decompress_set(A, 1 << 20, ph, A, A, 0x100000, 10, None) == 3
+    bad = buf.copy()
+    bad[0] ^= 1
+    assert omc._decompress_set(A, 1 << 20, bad.ctypes.data, A, A, 0x100000, 5000, None) == 8
