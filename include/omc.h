@@ -242,7 +242,9 @@ size_t omc_dequant_gemm_workspace_bytes(uint32_t M);
  * Uses  A*(s*Vt + b*1) = s*(A*Vt) + b*rowsum(A)*1^T.  Requires man_bits <= 7 (every Vtilde is then
  * exactly a bfloat16), M % 256 == 0, N % 128 == 0, K % 32 == 0 (OMC_ERR_FORMAT / OMC_ERR_SIZE).
  * Values of the format below 2^-126 (possible only with a bias near 127) may be flushed to zero by
- * the matrix cores. */
+ * the matrix cores.  S1E4M3 with bias 7 is converted by the hardware's FP8 instructions unless a
+ * pre-pass over the codes finds the one code (all exponent and mantissa bits set, value 480) that
+ * they read differently; results are the same either way. */
 omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, const float *sb,
                             float *C, uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes,
                             void *stream);

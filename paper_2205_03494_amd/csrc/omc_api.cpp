@@ -419,7 +419,7 @@ uint64_t omc_plan_transport_bytes(const void *plan_host) {
 }
 
 size_t omc_dequant_gemm_workspace_bytes(uint32_t M) {
-    return M == 0 ? 0 : (static_cast<size_t>(M) * sizeof(float) + 15) / 16 * 16;
+    return M == 0 ? 0 : 256 + (static_cast<size_t>(M) * sizeof(float) + 15) / 16 * 16;   // flag words + row sums
 }
 
 omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, const float *sb, float *C,

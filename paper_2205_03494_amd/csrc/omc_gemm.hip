@@ -34,17 +34,46 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 #ifndef OMC_GEMM_WAVES
 #define OMC_GEMM_WAVES 2
 #endif
+// LDS slot of an A row within its k-chunk plane: XOR with the chunk keeps the four planes' stores of
+// one wave apart (measured against no swizzle and a rotation by 4 * chunk: both slower)
+#define OMC_A_SLOT(row, chunk) ((row) ^ (2u * (chunk)))
 
 constexpr int kBN = 128, kBK = 32;
 constexpr int kWChunkBytes = kBN * 16;   // one k-chunk (8 bf16) of all columns
 
-// One wave per activation row: rowsum[m] = sum_k A[m][k] in fp32 (lane-strided, then a butterfly).
-__global__ __launch_bounds__(256) void gemm_rowsum_kernel(const uint16_t *__restrict__ A, float *__restrict__ rowsum,
-                                                          uint32_t M, uint32_t K) {
+constexpr uint32_t kScanBlocks = 64;      // one flag word each; a GEMM wave reads them all with one load
+
+// Pre-pass.  Workgroups [0, rowsum_blocks): one wave per activation row, rowsum[m] = sum_k A[m][k] in
+// fp32 (lane-strided, then a butterfly).  Workgroups after those (S1E4M3 with bias 7 only): scan the
+// codes for the top code, the one code whose value differs from the hardware FP8 conversion's
+// (480 here, NaN there); flags[j] != 0 sends the GEMM to the generic decode.
+__global__ __launch_bounds__(256) void gemm_prep_kernel(const uint16_t *__restrict__ A, float *__restrict__ rowsum,
+                                                        uint32_t M, uint32_t K, uint32_t rowsum_blocks,
+                                                        const uint32_t *__restrict__ codes, uint64_t code_dwords,
+                                                        uint32_t *__restrict__ flags) {
+    if (blockIdx.x >= rowsum_blocks) {
+        __shared__ uint32_t any_top[4];
+        const uint32_t j = blockIdx.x - rowsum_blocks;
+        const uint64_t pieces = code_dwords / 4;                          // 16-byte pieces (streams are padded to 16 bytes)
+        const uint64_t per = (pieces + kScanBlocks - 1) / kScanBlocks;
+        const uint64_t lo = j * per, hi = (lo + per < pieces) ? lo + per : pieces;
+        uint32_t found = 0;
+        for (uint64_t q = lo + threadIdx.x; q < hi; q += 256) {
+            const u32x4 v = reinterpret_cast<const u32x4 *>(codes)[q];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) found |= ((v[i] & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u;
+        }
+        const bool w = __any(found != 0);
+        if ((threadIdx.x & 63) == 0) any_top[threadIdx.x >> 6] = w ? 1u : 0u;
+        __syncthreads();
+        if (threadIdx.x == 0) flags[j] = any_top[0] | any_top[1] | any_top[2] | any_top[3];
+        return;
+    }
     const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
     if (row >= M) return;
@@ -95,17 +124,17 @@ __device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32
     return c << (32 - B);
 }
 
-template <int BM, bool BYTE>
-__global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
-                                                              const uint32_t *__restrict__ codes, uint64_t total_dwords,
-                                                              FmtParams fp, const float *__restrict__ sb,
-                                                              const float *__restrict__ rowsum, float *__restrict__ C,
-                                                              uint32_t M, uint32_t N, uint32_t K) {
+// DEC: 0 = any code width, 1 = byte codes.  HW (byte codes of S1E4M3 / bias 7 only): hardware FP8 conversion.
+template <int BM, int DEC, bool HW>
+__device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A, const uint32_t *__restrict__ codes,
+                                                  uint64_t total_dwords, const FmtParams &fp,
+                                                  const float *__restrict__ sb, const float *__restrict__ rowsum,
+                                                  float *__restrict__ C, uint32_t N, uint32_t K, uint8_t *lds) {
+    constexpr bool BYTE = DEC != 0;
     constexpr int kAChunkBytes = BM * 16;                 // one k-chunk (8 bf16) of all rows
     constexpr int kStageBytes = 4 * kAChunkBytes + 4 * kWChunkBytes;
     constexpr int MI = BM / 128;                          // 32-row MFMA tiles per wave
     constexpr int AP = BM / 64;                           // 16-byte pieces of A per thread and stage
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kStageBytes];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63, wave = tid >> 6;
@@ -126,36 +155,59 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
     };
     StageRegs r0, r1;
 
+    auto load_a_piece = [&](StageRegs &r, uint32_t k0, int p) {
+        const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
+        r.a[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
+    };
+    auto load_w_row = [&](StageRegs &r, uint32_t k0, int rr) {
+        const uint64_t e = static_cast<uint64_t>(k0 + 4 * w_kg + rr) * N + w_col;
+        load_codes4<BYTE>(codes, total_dwords, e, fp.bits, r.w_raw[rr], r.w_off[rr]);
+    };
     auto load_stage = [&](StageRegs &r, uint32_t k0) {
 #pragma unroll
-        for (int p = 0; p < AP; ++p) {
-            const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
-            r.a[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
-        }
+        for (int p = 0; p < AP; ++p) load_a_piece(r, k0, p);
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const uint64_t e = static_cast<uint64_t>(k0 + 4 * w_kg + rr) * N + w_col;
-            load_codes4<BYTE>(codes, total_dwords, e, fp.bits, r.w_raw[rr], r.w_off[rr]);
-        }
+        for (int rr = 0; rr < 4; ++rr) load_w_row(r, k0, rr);
     };
 
-    auto store_stage = [&](const StageRegs &r, uint8_t *ldsA) {
+    auto store_a_piece = [&](const StageRegs &r, uint8_t *ldsA, int p) {
+        const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
+        *reinterpret_cast<u32x4 *>(ldsA + chunk * kAChunkBytes + (OMC_A_SLOT(row, chunk) << 4)) = r.a[p];
+    };
+    auto store_w_column = [&](uint8_t *ldsA, int i, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) {
         uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
+        u32x2 out;
+        out[0] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);   // bf16(v0) | bf16(v1) << 16
+        out[1] = __builtin_amdgcn_perm(v3, v2, 0x07060302u);
+        *reinterpret_cast<u32x2 *>(ldsW + wave * kWChunkBytes + ((32u * i + w_cg) << 4) + 8u * w_h) = out;
+    };
+    // decode and store of the patch in four parts (part i = column 4 cg + i; the hardware conversion
+    // yields two columns at a time, so its parts 1 and 3 are empty)
+    auto store_w_part = [&](const StageRegs &r, uint8_t *ldsA, int part) {
+        if (HW) {
+            if (part & 1) return;
+            f32x2 c[4];
 #pragma unroll
-        for (int p = 0; p < AP; ++p) {
-            const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
-            *reinterpret_cast<u32x4 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4)) = r.a[p];
-        }
+            for (int rr = 0; rr < 4; ++rr)
+                c[rr] = (part == 0) ? __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[rr][0]), false)
+                                    : __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[rr][0]), true);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {                       // column 4 cg + i of the patch
+            for (int j = 0; j < 2; ++j)
+                store_w_column(ldsA, part + j, __float_as_uint(c[0][j]), __float_as_uint(c[1][j]),
+                               __float_as_uint(c[2][j]), __float_as_uint(c[3][j]));
+        } else {
             uint32_t v[4];
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) v[rr] = decode_bits(code_top_of<BYTE>(r.w_raw[rr], r.w_off[rr], fp.bits, i), fp);
-            u32x2 out;
-            out[0] = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);   // bf16(v0) | bf16(v1) << 16
-            out[1] = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
-            *reinterpret_cast<u32x2 *>(ldsW + wave * kWChunkBytes + ((32u * i + w_cg) << 4) + 8u * w_h) = out;
+            for (int rr = 0; rr < 4; ++rr)
+                v[rr] = decode_bits(code_top_of<BYTE>(r.w_raw[rr], r.w_off[rr], fp.bits, part), fp);
+            store_w_column(ldsA, part, v[0], v[1], v[2], v[3]);
         }
+    };
+    auto store_stage = [&](const StageRegs &r, uint8_t *ldsA) {
+#pragma unroll
+        for (int p = 0; p < AP; ++p) store_a_piece(r, ldsA, p);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) store_w_part(r, ldsA, part);
     };
 
     f32x16 acc[MI][4];
@@ -167,26 +219,50 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
     const uint32_t f_row = lane & 31u, f_half = lane >> 5;   // fragment roles
-    auto multiply_stage = [&](const uint8_t *ldsA) {
+    struct Frags {
+        bf16x8 a[MI], b[4];
+    };
+    auto read_frags = [&](const uint8_t *ldsA, int ks, Frags &f) {
         const uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
+        const uint32_t chunk = 2 * ks + f_half;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const uint32_t chunk = 2 * ks + f_half;
-            bf16x8 fa[MI], fb[4];
+        for (int mi = 0; mi < MI; ++mi) {
+            const uint32_t row = 32 * MI * wave + 32 * mi + f_row;
+            f.a[mi] = *reinterpret_cast<const bf16x8 *>(ldsA + chunk * kAChunkBytes + (OMC_A_SLOT(row, chunk) << 4));
+        }
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                const uint32_t row = 32 * MI * wave + 32 * mi + f_row;
-                fa[mi] = *reinterpret_cast<const bf16x8 *>(ldsA + chunk * kAChunkBytes + ((row ^ (2u * chunk)) << 4));
-            }
+        for (int ni = 0; ni < 4; ++ni)
+            f.b[ni] = *reinterpret_cast<const bf16x8 *>(ldsW + chunk * kWChunkBytes + ((32u * ni + f_row) << 4));
+    };
+    auto multiply_frags = [&](const Frags &f) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < 4; ++ni)
-                fb[ni] = *reinterpret_cast<const bf16x8 *>(ldsW + chunk * kWChunkBytes + ((32u * ni + f_row) << 4));
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+    };
+    auto multiply_stage = [&](const uint8_t *ldsA) {
+        if (BYTE) {                                         // all fragments of the K step first
+            Frags f0, f1;
+            read_frags(ldsA, 0, f0);
+            read_frags(ldsA, 1, f1);
+            multiply_frags(f0);
+            multiply_frags(f1);
+        } else {                                            // wider codes need the registers for the raw words
+            Frags f;
+            read_frags(ldsA, 0, f);
+            multiply_frags(f);
+            read_frags(ldsA, 1, f);
+            multiply_frags(f);
         }
+    };
+    // One steady-state round as straight-line code: fragments of both halves, the matrix instructions,
+    // decode + LDS stores of the next K step, barrier, global loads of the step after the next two.
+    auto steady_round = [&](const uint8_t *cur, uint8_t *nxt, StageRegs &r, uint32_t k_load) {
+        multiply_stage(cur);
+        store_stage(r, nxt);
+        __syncthreads();
+        load_stage(r, k_load);
     };
 
     const uint32_t nk = K / kBK;
@@ -197,7 +273,12 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
     if (nk > 1) load_stage(r0, kBK);
     if (nk > 2) load_stage(r1, 2 * kBK);
     // Invariant at the top of an even round `it`: buf0 holds K step it, r0 step it+1, r1 step it+2.
-    for (uint32_t it = 0; it < nk; it += 2) {
+    uint32_t it = 0;
+    for (; it + 4 < nk; it += 2) {                          // both rounds store and load unconditionally
+        steady_round(buf0, buf1, r0, (it + 3) * kBK);
+        steady_round(buf1, buf0, r1, (it + 4) * kBK);
+    }
+    for (; it < nk; it += 2) {
         multiply_stage(buf0);
         if (it + 1 < nk) store_stage(r0, buf1);            // nobody reads buf1 any more (barrier of the round before)
         __syncthreads();
@@ -236,32 +317,58 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
     }
 }
 
-int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb, float *C,
-                        uint32_t M, uint32_t N, uint32_t K, float *rowsum, void *stream) {
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (sb) {
-        gemm_rowsum_kernel<<<dim3((M + 3) / 4), dim3(256), 0, st>>>(A, rowsum, M, K);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return static_cast<int>(e);
+// DEC 2 = byte codes of S1E4M3 / bias 7: hardware conversion unless the pre-pass found a top code.
+template <int BM, int DEC>
+__global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
+                                                              const uint32_t *__restrict__ codes, uint64_t total_dwords,
+                                                              FmtParams fp, const float *__restrict__ sb,
+                                                              const float *__restrict__ rowsum, float *__restrict__ C,
+                                                              uint32_t M, uint32_t N, uint32_t K,
+                                                              const uint32_t *__restrict__ flags) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * (4 * BM * 16 + 4 * kWChunkBytes)];
+    (void)M;
+    if (DEC == 2) {
+        const bool top = __any(flags[threadIdx.x & 63u] != 0);
+        if (!top) {
+            dequant_gemm_body<BM, 1, true>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
+            return;
+        }
     }
+    dequant_gemm_body<BM, (DEC == 0 ? 0 : 1), false>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
+}
+
+int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb, float *C,
+                        uint32_t M, uint32_t N, uint32_t K, float *ws, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
     const uint64_t n = static_cast<uint64_t>(K) * N;
     const uint64_t total_dwords = ((n * fp.bits + 7) / 8 + 15) / 16 * 4;
     const uint32_t *c = static_cast<const uint32_t *>(codes);
+    // workspace: kScanBlocks flag words, then M row sums
+    uint32_t *flags = reinterpret_cast<uint32_t *>(ws);
+    float *rowsum = ws + kScanBlocks;
+    const int dec = (fp.bits != 8) ? 0 : (fp.variant == 2 ? 2 : 1);
+    const uint32_t rowsum_blocks = sb ? (M + 3) / 4 : 0;
+    const uint32_t scan_blocks = (dec == 2) ? kScanBlocks : 0;
+    if (rowsum_blocks + scan_blocks > 0) {
+        gemm_prep_kernel<<<dim3(rowsum_blocks + scan_blocks), dim3(256), 0, st>>>(A, rowsum, M, K, rowsum_blocks, c,
+                                                                                  total_dwords, flags);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return static_cast<int>(e);
+    }
     // 256-row tiles unless they would leave fewer than two workgroups per compute unit
     const bool small = static_cast<uint64_t>(M / 256) * (N / kBN) < 512;
+#define OMC_GEMM_LAUNCH(BM, DEC) \
+    dequant_gemm_kernel<BM, DEC><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K, flags)
     if (!small) {
-        const dim3 grid(M / 256, N / kBN);
-        if (fp.bits == 8)
-            dequant_gemm_kernel<256, true><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
-        else
-            dequant_gemm_kernel<256, false><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+        if (dec == 2) OMC_GEMM_LAUNCH(256, 2);
+        else if (dec == 1) OMC_GEMM_LAUNCH(256, 1);
+        else OMC_GEMM_LAUNCH(256, 0);
     } else {
-        const dim3 grid(M / 128, N / kBN);
-        if (fp.bits == 8)
-            dequant_gemm_kernel<128, true><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
-        else
-            dequant_gemm_kernel<128, false><<<grid, dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K);
+        if (dec == 2) OMC_GEMM_LAUNCH(128, 2);
+        else if (dec == 1) OMC_GEMM_LAUNCH(128, 1);
+        else OMC_GEMM_LAUNCH(128, 0);
     }
+#undef OMC_GEMM_LAUNCH
     return static_cast<int>(hipGetLastError());
 }
 

@@ -71,3 +71,21 @@ def test_config5_shapes_sampled_rows(shape):
         ref = orc.dequant_gemm(A, packed, of, sb, M, N, K, rows=(r0, r0 + 24), threads=8)
         rel = check(C, ref, (r0, r0 + 24))
         assert rel < 1e-5
+
+
+@pytest.mark.parametrize("top_at", [None, 0, -1, 12345])
+def test_every_byte_code_exact_with_and_without_the_top_code(top_at):
+    """S1E4M3 / bias 7 takes the hardware FP8 conversion unless the weights hold a top code (value 480);
+    the pre-pass must find one anywhere in the stream, and both decodes must give the exact code values."""
+    of, gf = pair(4, 3)
+    M, N, K = 256, 128, 256
+    A = np.zeros((M, K), np.float32)
+    A[np.arange(M), np.arange(M) % K] = 1.0
+    codes = ((np.arange(K * N, dtype=np.int64) * 37 + 11) % 254).astype(np.uint32)
+    codes = np.where(codes >= 127, codes + 1, codes)          # 0..126, 128..254: no top code, both signs, subnormals
+    if top_at is not None:
+        codes[top_at] = 0x7F if top_at != -1 else 0xFF
+    W = orc.decode(codes, of)
+    C = run_gemm(synth.to_bf16_bits(A.ravel()), orc.pack(codes, 8), gf, None, M, N, K)
+    want = W.reshape(K, N)[np.arange(M) % K]
+    assert np.array_equal(C, want)
