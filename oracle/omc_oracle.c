@@ -479,3 +479,22 @@ int orc_dequant_gemm(const uint16_t *A, const uint8_t *packed, orc_format f, con
     free(W);
     return 0;
 }
+
+/* ---- server-side aggregation -------------------------------------------------------------------
+ * Sec. 1 (a federated round ends with the clients' models transported back and aggregated) and
+ * Sec. 2.5 (each client quantizes its own subset of the variables, so the server sees a variable
+ * in full precision from some clients and as codes + (s, b) from others).  The paper does not spell
+ * the aggregation out; the reading taken here is the plain federated average with equal weights:
+ *     out[i] = ( ... ((v_0[i] + v_1[i]) + v_2[i]) ... + v_{R-1}[i] ) / R
+ * on the clients' decompressed values, every operation rounded once to fp32, clients in index
+ * order.  The caller decompresses (orc_decompress) whatever arrived compressed. */
+int orc_mean_f32(const float *const *v, int R, uint64_t n, float *out)
+{
+    if (R < 1) return 1;
+    for (uint64_t i = 0; i < n; ++i) {
+        float acc = v[0][i];
+        for (int r = 1; r < R; ++r) acc = acc + v[r][i];
+        out[i] = acc / (float)R;
+    }
+    return 0;
+}

@@ -91,6 +91,8 @@ def lib():
         L.orc_step_varset.restype = C.c_int
         L.orc_step_varset.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.POINTER(_Opt), C.c_int]
+        L.orc_mean_f32.restype = C.c_int
+        L.orc_mean_f32.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_void_p]
         L.orc_dequant_gemm.restype = C.c_int
         L.orc_dequant_gemm.argtypes = [C.c_void_p, C.c_void_p, _Fmt, C.c_void_p, C.c_void_p,
                                        C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
@@ -282,4 +284,19 @@ def dequant_gemm(A_bf16_bits, packed, fmt: Format, sb, M, N, K, rows=None, threa
                                 int(threads))
     if rc:
         raise ValueError(f"orc_dequant_gemm failed ({rc})")
+    return out
+
+
+# --------------------------------------------------------------------------- server aggregation
+def aggregate_mean(replica_values) -> np.ndarray:
+    """Equal-weight federated average of R decompressed copies of one variable (fp32, clients in
+    index order, one rounding per operation).  replica_values: sequence of R float32 arrays."""
+    vs = [_f32(v) for v in replica_values]
+    n = vs[0].size
+    assert all(v.size == n for v in vs)
+    ptrs = (C.c_void_p * len(vs))(*[v.ctypes.data for v in vs])
+    out = np.empty(n, dtype=np.float32)
+    rc = lib().orc_mean_f32(ptrs, len(vs), n, _p(out))
+    if rc:
+        raise ValueError(f"orc_mean_f32 failed ({rc})")
     return out
