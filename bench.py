@@ -161,6 +161,48 @@ def set_conversion_leg(torch, omc, wl, n_q, n_f, iters=20):
     return res
 
 
+def aggregate_leg(torch, omc, synth, blocks, R=8, iters=20):
+    """Server side of a round: mean of R clients' copies of the set, each client with its own 90 %
+    subset of the weight matrices in S1E4M3 and the rest in fp32."""
+    import numpy as np
+    specs = synth.conformer_varset(512, blocks, 2048, 32, frontend=True)
+    gf = omc.fmt(4, 3)
+    arenas, sbs, plans = [], [], []
+    alg = 0.0
+    vals_d = None
+    for r in range(R):
+        mask = synth.ppq_mask(specs, 0.9, 100 + r)
+        lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(gf, n))
+        table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gf,
+                      quantized=bool(mask[i])) for i, s in enumerate(specs)]
+        plan = omc.omc_plan_build(omc.make_var_table(table))
+        if vals_d is None:
+            vals_d = torch.from_numpy(synth.init_values(lay, 0)).cuda()
+        client = vals_d + 1e-3 * torch.randn_like(vals_d)
+        arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
+        sb = torch.zeros((len(specs), 2), device="cuda")
+        ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+        omc.omc_compress_set(client, plan, arena, sb, ws)
+        arenas.append(arena); sbs.append(sb); plans.append(plan)
+        alg += sum((1.0 if q else 4.0) * s.n for s, q in zip(specs, mask))
+    n_total = sum(s.n for s in specs)
+    alg += 4.0 * n_total
+    agg = omc.omc_aggregate_plan_build(plans)
+    out = torch.empty(vals_d.numel(), device="cuda")
+    for _ in range(3):
+        omc.omc_aggregate_mean(agg, arenas, sbs, out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        omc.omc_aggregate_mean(agg, arenas, sbs, out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    return {"clients": R, "params": n_total, "ms": ms, "algorithmic_bytes": alg,
+            "algorithmic_GBps": alg / (ms * 1e-3) / 1e9, "frac_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "fp32_clients_bytes": 4.0 * n_total * (R + 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -171,6 +213,7 @@ def main():
     ap.add_argument("--cpu-iters", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
     ap.add_argument("--gemm-only", action="store_true", help="only the forward GEMM leg (for profiler runs)")
+    ap.add_argument("--aggregate-only", action="store_true", help="only the server aggregation leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device-to-device copy of known size (1 GiB read + 1 GiB written "
                          "per launch) to calibrate profiler byte counters and show the copy ceiling")
@@ -204,6 +247,9 @@ def main():
         return
     if args.gemm_only:
         print(json.dumps({"gemm": gemm_leg(torch, omc, synth)}))
+        return
+    if args.aggregate_only:
+        print(json.dumps({"server_aggregation": aggregate_leg(torch, omc, synth, args.blocks)}))
         return
     wl = build_workload(torch, omc, synth, args.blocks, 512, 2048)
     specs, mask, lay, plan = wl["specs"], wl["mask"], wl["lay"], wl["plan"]
@@ -310,6 +356,9 @@ def main():
     del grads, arena0
     torch.cuda.empty_cache()
     out["set_conversions"] = set_conversion_leg(torch, omc, wl, n_q, n_f)
+    del wl
+    torch.cuda.empty_cache()
+    out["server_aggregation"] = aggregate_leg(torch, omc, synth, args.blocks)
     out["forward_gemm"] = gemm_leg(torch, omc, synth)
     if cpu is not None:
         out["cpu_baseline"] = {

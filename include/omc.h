@@ -11,6 +11,7 @@
  *   omc_step_update_recompress   one training iteration over a whole variable set:
  *                                decompress -> parameter update -> recompress, fused     (Sec. 2.1, backward path)
  *   omc_dequant_gemm             C = A * decompress(W), weights expanded on chip          (Sec. 2.1, forward path)
+ *   omc_aggregate_mean           server: mean of R clients' mixed-precision copies        (Sec. 1, 2.5)
  *
  * Conventions that hold for every entry point
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
@@ -225,6 +226,40 @@ omc_status omc_step_update_recompress_events(void *arena, size_t arena_bytes, co
                                              float *state0, float *state1, uint64_t aux_elems,
                                              const omc_opt *opt, void *ws, size_t ws_bytes, void *stream,
                                              void *const *events, uint32_t nevents);
+
+/* ---- server-side aggregation ------------------------------------------------------------- */
+
+/* The server's end of a federated round (Sec. 1: the clients' trained models are transported back and
+ * aggregated; Sec. 2.5: every client quantizes its own subset of the variables, so one variable
+ * arrives as codes + (s, b) from some clients and in fp32 from others).  The paper leaves the
+ * aggregation itself open; this is the plain federated average with equal weights,
+ *     out[i] = ( ... ((v_0[i] + v_1[i]) + v_2[i]) ... + v_{R-1}[i] ) / R,
+ * over the clients' decompressed values, clients in index order, fp32, each operation rounded once.
+ *
+ * Each client r hands over what omc_compress_set / the training steps produced: its plan, arena and
+ * (s, b) table.  The plans must describe the same variable list (count, sizes, aux offsets) and
+ * agree on the format of every variable among the clients that quantize it; data offsets and the
+ * quantized subsets may differ freely.  At most OMC_MAX_REPLICAS clients per call.
+ *
+ * omc_aggregate_plan_bytes / _build: host only; merge the R host plans into an aggregation plan
+ * (position independent; the caller copies it to the device).  0 / an error status for plans that do
+ * not fit together (OMC_ERR_PLAN, OMC_ERR_SIZE, OMC_ERR_FORMAT).
+ *
+ * omc_aggregate_mean:
+ *   agg_host, agg_dev   the aggregation plan in host memory and its device copy (16-byte aligned)
+ *   arenas, sb_tables   host arrays of R device pointers: client r's arena (arena_bytes[r] bytes, at
+ *                       least what its plan addresses) and (s, b) table (2 floats per variable)
+ *   out                 device, aux_elems floats, variable v at its aux_offset; the server model in
+ *                       full precision (omc_compress_set packs it for the next round)
+ * Inputs are read once, in the form they arrived in; nothing is written but out.  The library
+ * allocates nothing; launches go to `stream`. */
+#define OMC_MAX_REPLICAS 16
+size_t omc_aggregate_plan_bytes(const void *const *plans_host, uint32_t nreplicas);
+omc_status omc_aggregate_plan_build(const void *const *plans_host, uint32_t nreplicas, void *agg_host,
+                                    size_t agg_bytes);
+omc_status omc_aggregate_mean(const void *agg_host, const void *agg_dev, const void *const *arenas,
+                              const size_t *arena_bytes, const float *const *sb_tables, float *out,
+                              uint64_t aux_elems, void *stream);
 
 /* ---- forward path ------------------------------------------------------------------------ */
 

@@ -418,6 +418,194 @@ uint64_t omc_plan_transport_bytes(const void *plan_host) {
     return total;
 }
 
+}  // extern "C"
+
+// ---- server-side aggregation ---------------------------------------------------------------
+namespace omc {
+struct AggLayout {
+    uint64_t var_off, src_off, item_off, group_off, total;
+    uint32_t nitems;
+    std::vector<PlanGroup> groups;
+    std::vector<uint8_t> any_quant;          // per variable
+};
+
+static const AggHeader *agg_check(const void *agg_host) {
+    if (!agg_host) return nullptr;
+    const AggHeader *ah = static_cast<const AggHeader *>(agg_host);
+    if (ah->magic != kAggMagic || ah->version != kAggVersion) return nullptr;
+    if (ah->nreplicas == 0 || ah->nreplicas > kMaxReplicas) return nullptr;
+    if (ah->var_off != sizeof(AggHeader)) return nullptr;
+    if (ah->src_off != ah->var_off + static_cast<uint64_t>(ah->nvars) * sizeof(AggVar)) return nullptr;
+    if (ah->item_off != ah->src_off + static_cast<uint64_t>(ah->nvars) * ah->nreplicas * sizeof(AggSrc)) return nullptr;
+    if (ah->group_off != ah->item_off + static_cast<uint64_t>(ah->nitems) * sizeof(PlanItem)) return nullptr;
+    if (ah->total_bytes != align_up(ah->group_off + static_cast<uint64_t>(ah->ngroups) * sizeof(PlanGroup), 16))
+        return nullptr;
+    return ah;
+}
+
+static bool same_format(const FmtParams &a, const FmtParams &b) {
+    return a.exp_bits == b.exp_bits && a.man_bits == b.man_bits && a.bias == b.bias;
+}
+
+// The clients' plans must describe one variable list: same count, sizes and aux offsets, and one
+// format per variable among the clients that quantize it.
+static omc_status agg_layout(const void *const *plans_host, uint32_t R, AggLayout *al) {
+    if (!plans_host) return OMC_ERR_NULL;
+    if (R == 0 || R > kMaxReplicas) return OMC_ERR_SIZE;
+    const PlanHeader *p0 = plan_check(plans_host[0]);
+    if (!p0) return OMC_ERR_PLAN;
+    const uint32_t nvars = p0->nvars;
+    const PlanVar *v0 = reinterpret_cast<const PlanVar *>(static_cast<const uint8_t *>(plans_host[0]) + p0->var_off);
+    al->any_quant.assign(nvars, 0);
+    std::vector<FmtParams> fmt(nvars);
+    for (uint32_t r = 0; r < R; ++r) {
+        const PlanHeader *ph = plan_check(plans_host[r]);
+        if (!ph) return OMC_ERR_PLAN;
+        if (ph->nvars != nvars) return OMC_ERR_SIZE;
+        const PlanVar *pv = reinterpret_cast<const PlanVar *>(static_cast<const uint8_t *>(plans_host[r]) + ph->var_off);
+        for (uint32_t i = 0; i < nvars; ++i) {
+            if (pv[i].n != v0[i].n || pv[i].aux_offset != v0[i].aux_offset) return OMC_ERR_SIZE;
+            if (pv[i].flags & OMC_VAR_QUANTIZED) {
+                if (al->any_quant[i] && !same_format(fmt[i], pv[i].fp)) return OMC_ERR_FORMAT;
+                al->any_quant[i] = 1;
+                fmt[i] = pv[i].fp;
+            }
+        }
+    }
+    bool present[33] = {false};
+    bool tails = false, flat = false;
+    uint64_t nitems = 0;
+    for (uint32_t i = 0; i < nvars; ++i) {
+        const uint64_t n = v0[i].n;
+        if (al->any_quant[i]) {
+            if (n >= kTileElems) present[fmt[i].bits] = true;
+            if (n % kTileElems) tails = true;
+            nitems += (n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk + (n % kTileElems ? 1 : 0);
+        } else {
+            flat = true;
+            nitems += (n + kChunkElems - 1) / kChunkElems;
+        }
+    }
+    if (nitems > 0x7fffffffull) return OMC_ERR_SIZE;
+    al->groups.clear();
+    for (uint32_t b = 2; b <= 32; ++b)
+        if (present[b]) al->groups.push_back(PlanGroup{kGroupFull, b, 0, 0, 0, 0});
+    if (tails) al->groups.push_back(PlanGroup{kGroupTail, 0, 0, 0, 0, 0});
+    if (flat) al->groups.push_back(PlanGroup{kGroupFp32, 0, 0, 0, 0, 0});
+    al->nitems = static_cast<uint32_t>(nitems);
+    al->var_off = sizeof(AggHeader);
+    al->src_off = al->var_off + static_cast<uint64_t>(nvars) * sizeof(AggVar);
+    al->item_off = al->src_off + static_cast<uint64_t>(nvars) * R * sizeof(AggSrc);
+    al->group_off = al->item_off + nitems * sizeof(PlanItem);
+    al->total = align_up(al->group_off + al->groups.size() * sizeof(PlanGroup), 16);
+    return OMC_OK;
+}
+}  // namespace omc
+
+extern "C" {
+
+size_t omc_aggregate_plan_bytes(const void *const *plans_host, uint32_t nreplicas) {
+    AggLayout al;
+    if (agg_layout(plans_host, nreplicas, &al) != OMC_OK) return 0;
+    return static_cast<size_t>(al.total);
+}
+
+omc_status omc_aggregate_plan_build(const void *const *plans_host, uint32_t nreplicas, void *agg_host,
+                                    size_t agg_bytes) {
+    if (!agg_host) return OMC_ERR_NULL;
+    AggLayout al;
+    const omc_status st = agg_layout(plans_host, nreplicas, &al);
+    if (st != OMC_OK) return st;
+    if (agg_bytes < al.total) return OMC_ERR_SIZE;
+    const uint32_t R = nreplicas;
+    uint8_t *base = static_cast<uint8_t *>(agg_host);
+    std::memset(base, 0, al.total);
+    AggHeader *ah = reinterpret_cast<AggHeader *>(base);
+    AggVar *av = reinterpret_cast<AggVar *>(base + al.var_off);
+    AggSrc *src = reinterpret_cast<AggSrc *>(base + al.src_off);
+    PlanItem *items = reinterpret_cast<PlanItem *>(base + al.item_off);
+    PlanGroup *groups = reinterpret_cast<PlanGroup *>(base + al.group_off);
+    const PlanHeader *p0 = plan_check(plans_host[0]);
+    const uint32_t nvars = p0->nvars;
+    for (uint32_t r = 0; r < R; ++r) {
+        const PlanHeader *ph = plan_check(plans_host[r]);
+        const PlanVar *pv = reinterpret_cast<const PlanVar *>(static_cast<const uint8_t *>(plans_host[r]) + ph->var_off);
+        ah->arena_bytes[r] = ph->arena_bytes;
+        for (uint32_t i = 0; i < nvars; ++i) {
+            AggSrc &s = src[static_cast<uint64_t>(i) * R + r];
+            s.data_offset = pv[i].data_offset;
+            s.quantized = (pv[i].flags & OMC_VAR_QUANTIZED) ? 1u : 0u;
+            if (r == 0) {
+                av[i].aux_offset = pv[i].aux_offset;
+                av[i].n = pv[i].n;
+            }
+            if (s.quantized) {
+                av[i].fp = pv[i].fp;
+                av[i].total_dwords = pv[i].total_dwords;
+            }
+        }
+    }
+    uint32_t next = 0;
+    for (size_t gi = 0; gi < al.groups.size(); ++gi) {
+        PlanGroup g = al.groups[gi];
+        g.first_item = next;
+        for (uint32_t i = 0; i < nvars; ++i) {
+            const uint64_t n = av[i].n;
+            const bool q = al.any_quant[i] != 0;
+            if (g.kind == kGroupFull) {
+                if (!q || av[i].fp.bits != g.bits || n < kTileElems) continue;
+                const uint32_t c_end = static_cast<uint32_t>((n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
+                for (uint32_t c = 0; c < c_end; ++c) items[next++] = PlanItem{i, c};
+            } else if (g.kind == kGroupTail) {
+                if (!q || n % kTileElems == 0) continue;
+                items[next++] = PlanItem{i, 0};
+            } else {
+                if (q) continue;
+                const uint32_t c_end = static_cast<uint32_t>((n + kChunkElems - 1) / kChunkElems);
+                for (uint32_t c = 0; c < c_end; ++c) items[next++] = PlanItem{i, c};
+            }
+        }
+        g.nitems = next - g.first_item;
+        groups[gi] = g;
+    }
+    ah->magic = kAggMagic;
+    ah->version = kAggVersion;
+    ah->nvars = nvars;
+    ah->nitems = al.nitems;
+    ah->ngroups = static_cast<uint32_t>(al.groups.size());
+    ah->nreplicas = R;
+    ah->total_bytes = al.total;
+    ah->var_off = al.var_off;
+    ah->src_off = al.src_off;
+    ah->item_off = al.item_off;
+    ah->group_off = al.group_off;
+    ah->aux_elems = p0->aux_elems;
+    return OMC_OK;
+}
+
+omc_status omc_aggregate_mean(const void *agg_host, const void *agg_dev, const void *const *arenas,
+                              const size_t *arena_bytes, const float *const *sb_tables, float *out,
+                              uint64_t aux_elems, void *stream) {
+    if (!agg_host || !agg_dev || !arenas || !arena_bytes || !sb_tables || !out) return OMC_ERR_NULL;
+    const AggHeader *ah = agg_check(agg_host);
+    if (!ah) return OMC_ERR_PLAN;
+    if (aux_elems < ah->aux_elems) return OMC_ERR_SIZE;
+    if (!aligned16(agg_dev) || !aligned16(out)) return OMC_ERR_ALIGN;
+    AggPointers ptrs{};
+    const uintptr_t o0 = reinterpret_cast<uintptr_t>(out), o1 = o0 + 4 * ah->aux_elems;
+    for (uint32_t r = 0; r < ah->nreplicas; ++r) {
+        if (!arenas[r] || !sb_tables[r]) return OMC_ERR_NULL;
+        if (arena_bytes[r] < ah->arena_bytes[r]) return OMC_ERR_SIZE;
+        if (!aligned16(arenas[r]) || (reinterpret_cast<uintptr_t>(sb_tables[r]) & 3u)) return OMC_ERR_ALIGN;
+        const uintptr_t a0 = reinterpret_cast<uintptr_t>(arenas[r]);
+        if (a0 < o1 && o0 < a0 + ah->arena_bytes[r]) return OMC_ERR_SIZE;     // output overlaps an input
+        ptrs.arena[r] = static_cast<const uint8_t *>(arenas[r]);
+        ptrs.sb[r] = sb_tables[r];
+    }
+    const int rc = launch_aggregate_mean(ah, agg_dev, ptrs, out, stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
 size_t omc_dequant_gemm_workspace_bytes(uint32_t M) {
     return M == 0 ? 0 : 256 + (static_cast<size_t>(M) * sizeof(float) + 15) / 16 * 16;   // flag words + row sums
 }

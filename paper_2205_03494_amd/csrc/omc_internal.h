@@ -87,6 +87,35 @@ struct PlanGroup {
     uint32_t pad;
 };
 
+// ---- aggregation plan blob (server side: R clients' copies of one variable set) ---------------
+constexpr uint32_t kAggMagic = 0x47414d4fu;  // "OMAG"
+constexpr uint32_t kAggVersion = 1;
+constexpr uint32_t kMaxReplicas = 16;
+
+struct AggHeader {
+    uint32_t magic, version;
+    uint32_t nvars, nitems, ngroups, nreplicas;
+    uint64_t total_bytes;
+    uint64_t var_off, src_off, item_off, group_off;
+    uint64_t aux_elems;
+    uint64_t arena_bytes[kMaxReplicas];     // extent each client's arena must have
+};
+
+struct AggVar {
+    uint64_t aux_offset, n;
+    uint64_t total_dwords;   // packed length of the variable where it is quantized; 0: fp32 at every client
+    FmtParams fp;            // the one format every quantizing client uses for this variable
+};
+
+struct AggSrc {              // one per (variable, client), variable-major
+    uint64_t data_offset;    // into that client's arena
+    uint32_t quantized;
+    uint32_t pad;
+};
+
+// groups reuse PlanGroup: kGroupFull (bits) = full tiles of variables quantized somewhere,
+// kGroupTail = their ragged tails, kGroupFp32 = variables that are fp32 at every client
+
 // ---- host helpers (omc_host.cpp) -----------------------------------------------------------
 bool make_fmt_params(omc_format f, FmtParams *out);
 const PlanHeader *plan_check(const void *plan_host);
@@ -109,6 +138,11 @@ int launch_decompress_set(const void *arena, const PlanHeader *ph, const void *p
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table,
                 const float *grads, float *state0, float *state1, const omc_opt &opt, Partial *ws,
                 void *stream, void *const *events);
+struct AggPointers {
+    const uint8_t *arena[kMaxReplicas];
+    const float *sb[kMaxReplicas];
+};
+int launch_aggregate_mean(const AggHeader *ah, const void *agg_dev, const AggPointers &ptrs, float *out, void *stream);
 int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb,
                         float *C, uint32_t M, uint32_t N, uint32_t K, float *rowsum, void *stream);
 

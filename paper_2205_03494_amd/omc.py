@@ -77,6 +77,9 @@ _step_ev = _sig("omc_step_update_recompress_events", C.c_int, _vp, C.c_size_t, _
 _compress_set = _sig("omc_compress_set", C.c_int, _vp, C.c_uint64, _vp, _vp, _vp, C.c_size_t, _vp, _vp, C.c_size_t, _vp)
 _decompress_set = _sig("omc_decompress_set", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, C.c_uint64, _vp)
 _plan_transport = _sig("omc_plan_transport_bytes", C.c_uint64, _vp)
+_agg_bytes = _sig("omc_aggregate_plan_bytes", C.c_size_t, _vp, C.c_uint32)
+_agg_build = _sig("omc_aggregate_plan_build", C.c_int, _vp, C.c_uint32, _vp, C.c_size_t)
+_agg_mean = _sig("omc_aggregate_mean", C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.c_uint64, _vp)
 _gemm_ws = _sig("omc_dequant_gemm_workspace_bytes", C.c_size_t, C.c_uint32)
 _gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
              C.c_uint32, _vp, C.c_size_t, _vp)
@@ -86,7 +89,8 @@ EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_
             "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_plan_arena_bytes",
             "omc_plan_aux_elems", "omc_plan_launches", "omc_step_update_recompress",
             "omc_step_update_recompress_events", "omc_compress_set", "omc_decompress_set",
-            "omc_plan_transport_bytes", "omc_dequant_gemm_workspace_bytes",
+            "omc_plan_transport_bytes", "omc_aggregate_plan_bytes", "omc_aggregate_plan_build",
+            "omc_aggregate_mean", "omc_dequant_gemm_workspace_bytes",
             "omc_dequant_gemm"]
 
 
@@ -278,3 +282,35 @@ def omc_dequant_gemm(A: torch.Tensor, codes: torch.Tensor, f: omc_format, sb: Op
                      Cout: torch.Tensor, M: int, N: int, K: int, ws: torch.Tensor, stream=None) -> None:
     _check(_gemm(_ptr(A), _ptr(codes), f, _ptr(sb), _ptr(Cout), M, N, K, _ptr(ws),
                  ws.numel() * ws.element_size(), _stream(stream)), "omc_dequant_gemm")
+
+
+# --------------------------------------------------------------------------- server aggregation
+OMC_MAX_REPLICAS = 16
+
+
+@dataclass
+class AggregatePlan:
+    host: np.ndarray                 # the blob (uint8)
+    dev: torch.Tensor                # its device copy
+    nreplicas: int
+
+
+def omc_aggregate_plan_build(plans: Sequence["Plan"]) -> AggregatePlan:
+    """Merge the clients' plans (same variable list, own quantized subsets) into an aggregation plan."""
+    R = len(plans)
+    ptrs = (C.c_void_p * R)(*[p.host.ctypes.data for p in plans])
+    size = _agg_bytes(ptrs, R)
+    buf = np.zeros(max(size, 16), dtype=np.uint8)
+    _check(_agg_build(ptrs, R, buf.ctypes.data, buf.size), "omc_aggregate_plan_build")
+    return AggregatePlan(buf, torch.from_numpy(buf).cuda(), R)
+
+
+def omc_aggregate_mean(agg: AggregatePlan, arenas: Sequence[torch.Tensor], sb_tables: Sequence[torch.Tensor],
+                       out: torch.Tensor, stream=None) -> None:
+    R = agg.nreplicas
+    assert len(arenas) == R and len(sb_tables) == R
+    ap = (C.c_void_p * R)(*[_ptr(a) for a in arenas])
+    ab = (C.c_size_t * R)(*[a.numel() * a.element_size() for a in arenas])
+    sp = (C.c_void_p * R)(*[_ptr(s) for s in sb_tables])
+    _check(_agg_mean(agg.host.ctypes.data, _ptr(agg.dev), ap, ab, sp, _ptr(out), out.numel(), _stream(stream)),
+           "omc_aggregate_mean")

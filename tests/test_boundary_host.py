@@ -195,3 +195,45 @@ def test_set_entry_points_reject_bad_arguments():
     bad = buf.copy()
     bad[0] ^= 1
     assert omc._decompress_set(A, 1 << 20, bad.ctypes.data, A, A, 0x100000, 5000, None) == 8
+
+
+def _host_plan(vs):
+    size, st, buf = _plan_status(vs)
+    assert st == 0
+    return buf
+
+
+def test_aggregate_plan_checks_that_the_clients_plans_fit_together():
+    f, g = omc.fmt(4, 3), omc.fmt(3, 7)
+    def table(q0, q1, fmt0=f, n1=5000, aux1=4096):
+        return [dict(data_offset=0, aux_offset=0, n=3000, fmt=fmt0, quantized=q0),
+                dict(data_offset=16384, aux_offset=aux1, n=n1, fmt=f, quantized=q1)]
+    a, b = _host_plan(table(True, False)), _host_plan(table(False, True))
+    def build(plans):
+        ptrs = (omc.C.c_void_p * len(plans))(*[p.ctypes.data for p in plans])
+        size = omc._agg_bytes(ptrs, len(plans))
+        buf = np.zeros(max(size, 16), np.uint8)
+        return size, omc._agg_build(ptrs, len(plans), buf.ctypes.data, buf.size), buf
+    size, st, buf = build([a, b, a])
+    assert st == 0 and size > 0 and size % 16 == 0
+    assert build([a, _host_plan(table(True, False, fmt0=g))])[1] == 2          # formats differ for variable 0
+    assert build([a, _host_plan(table(True, False, n1=5001))])[1] == 3         # sizes differ
+    assert build([a, _host_plan(table(True, False, aux1=8192))])[1] == 3       # aux offsets differ
+    bad = a.copy(); bad[0] ^= 1
+    assert build([a, bad])[1] == 8
+    assert build([a] * 17)[1] == 3
+    assert omc._agg_bytes(None, 2) == 0
+    # the call itself
+    A = 0x10000
+    arenas = (omc.C.c_void_p * 3)(A, A, A)
+    sizes = (omc.C.c_size_t * 3)(1 << 20, 1 << 20, 1 << 20)
+    sbs = (omc.C.c_void_p * 3)(A, A, A)
+    out = 0x4000000
+    assert omc._agg_mean(None, A, arenas, sizes, sbs, out, 1 << 20, None) == 1
+    assert omc._agg_mean(buf.ctypes.data, A, arenas, sizes, sbs, out, 10, None) == 3       # out too small
+    small = (omc.C.c_size_t * 3)(1 << 20, 16, 1 << 20)
+    assert omc._agg_mean(buf.ctypes.data, A, arenas, small, sbs, out, 1 << 20, None) == 3  # an arena too small
+    assert omc._agg_mean(buf.ctypes.data, A, arenas, sizes, sbs, A + 64, 1 << 20, None) == 3   # out overlaps an input
+    assert omc._agg_mean(buf.ctypes.data, A, arenas, sizes, sbs, out + 4, 1 << 20, None) == 4
+    broken = buf.copy(); broken[4] ^= 1
+    assert omc._agg_mean(broken.ctypes.data, A, arenas, sizes, sbs, out, 1 << 20, None) == 8

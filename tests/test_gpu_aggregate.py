@@ -1,0 +1,82 @@
+"""GPU parity of the server-side aggregation against the oracle: every client's copy decompressed
+by the oracle, then its fp32 left-to-right mean, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import omc_oracle as orc
+from paper_2205_03494_amd import omc, synth
+from gpu_util import bits_equal, to_dev
+from test_gpu_sets import build, oracle_arena, ragged_specs
+
+pytestmark = pytest.mark.gpu
+
+
+def client_values(lay, base, r):
+    """Client r's trained copy: the shared starting point plus its own small update."""
+    d = synth.gradients(lay, 2e-3, 500 + r)
+    return (base + d).astype(np.float32)
+
+
+def run_case(specs, fmts, masks, seed=0):
+    R = len(masks)
+    lays, plans, arenas, sbs, ref_src = [], [], [], [], []
+    base = None
+    for r, mask in enumerate(masks):
+        lay, plan = build(specs, mask, fmts)
+        if base is None:
+            base = synth.init_values(lay, seed)
+        vals = client_values(lay, base, r)
+        arena, sb = oracle_arena(specs, mask, fmts, lay, vals)     # what client r transports
+        lays.append(lay); plans.append(plan)
+        arenas.append(to_dev(arena)); sbs.append(to_dev(sb))
+        ref_src.append((lay, arena, sb, vals))
+    agg = omc.omc_aggregate_plan_build(plans)
+    out = torch.full((lays[0].aux_elems,), float("nan"), device="cuda")
+    omc.omc_aggregate_mean(agg, arenas, sbs, out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    for i, s in enumerate(specs):
+        a = int(lays[0].aux_offset[i])
+        copies = []
+        for r in range(R):
+            lay, arena, sb, vals = ref_src[r]
+            d = int(lay.data_offset[i])
+            if masks[r][i]:
+                of = orc.Format(*fmts[i])
+                copies.append(orc.decompress(arena[d:d + orc.packed_bytes(s.n, of.bits)], s.n, of, sb[i]))
+            else:
+                copies.append(arena[d:d + 4 * s.n].view(np.float32))
+        want = orc.aggregate_mean(copies)
+        assert bits_equal(o[a:a + s.n], want), (s.name, s.n)
+        end = int(lays[0].aux_offset[i + 1]) if i + 1 < len(specs) else lays[0].aux_elems
+        assert np.all(np.isnan(o[a + s.n:end]))
+    return o
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 8, 16])
+def test_conformer_shaped_set_with_per_client_subsets(R):
+    specs = synth.conformer_varset(96, 2, 384, 8, frontend=True)
+    fmts = [(4, 3)] * len(specs)
+    masks = [synth.ppq_mask(specs, 0.9, 10 + r) for r in range(R)]
+    run_case(specs, fmts, masks)
+
+
+@pytest.mark.parametrize("EM", [(4, 3), (3, 7), (2, 3), (4, 14), (5, 10), (8, 7), (8, 23)])
+def test_ragged_sizes_and_formats(EM):
+    specs = ragged_specs()
+    fmts = [EM] * len(specs)
+    rng = np.random.default_rng(5)
+    masks = [np.array([s.is_matrix and rng.random() < 0.7 for s in specs]) for _ in range(3)]
+    masks[0][:] = [s.is_matrix for s in specs]              # client 0 quantizes every matrix
+    masks[1][:] = False                                     # client 1 sends everything in fp32
+    run_case(specs, fmts, masks)
+
+
+def test_mixed_formats_across_variables_and_everyone_fp32():
+    specs = ragged_specs()
+    choices = [(4, 3), (3, 7), (5, 10), (2, 3)]
+    fmts = [choices[i % 4] for i in range(len(specs))]
+    masks = [np.array([s.is_matrix for s in specs]), np.array([s.is_matrix and i % 2 == 0 for i, s in enumerate(specs)])]
+    run_case(specs, fmts, masks)
+    run_case(specs, fmts, [np.zeros(len(specs), bool)] * 3)  # no client quantizes anything
