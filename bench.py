@@ -203,6 +203,47 @@ def aggregate_leg(torch, omc, synth, blocks, R=8, iters=20):
             "fp32_clients_bytes": 4.0 * n_total * (R + 1)}
 
 
+def formats_leg(torch, omc, synth, blocks, steps=20):
+    """The fused decompress + SGD + recompress kernel on the same variable set for every storage
+    format of the paper's tables (Tables 1-3: 19-, 13-, 11- and 6-bit), per-variable transformation on
+    and, for the 11-bit format, off (the ablation's switch)."""
+    import numpy as np
+    specs = synth.conformer_varset(512, blocks, 2048, 32, frontend=True)
+    mask = np.array([s.is_matrix for s in specs])
+    n_q = int(sum(s.n for s, q in zip(specs, mask) if q))
+    res = []
+    vals_d = None
+    for (E, M, pvt) in ((4, 14, True), (4, 8, True), (3, 9, True), (2, 10, True), (5, 7, True), (3, 7, True),
+                        (3, 7, False), (2, 3, True)):
+        gf = omc.fmt(E, M)
+        B = 1 + E + M
+        lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(gf, n))
+        table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gf,
+                      quantized=bool(mask[i]), use_pvt=pvt) for i, s in enumerate(specs)]
+        plan = omc.omc_plan_build(omc.make_var_table(table))
+        if vals_d is None:
+            vals_d = torch.from_numpy(synth.init_values(lay, 0)).cuda()
+            grads = [torch.from_numpy(synth.gradients(lay, 1e-3, 1000 + k)).cuda() for k in range(2)]
+        arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
+        sb = torch.zeros((len(specs), 2), device="cuda")
+        ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+        omc.omc_compress_set(vals_d, plan, arena, sb, ws)
+        o = omc.opt(omc.OMC_SGD, 0.01)
+        nl = plan.launches
+        ev = omc.HipEvents(2 * nl * steps)
+        for k in range(3):
+            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], None, None, o, ws)
+        for k in range(steps):
+            omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], None, None, o, ws, ev, first=k * 2 * nl)
+        torch.cuda.synchronize()
+        ms = sum(ev.elapsed_ms(k * 2 * nl, k * 2 * nl + 1) for k in range(steps)) / steps
+        alg = (2.0 * B / 8.0 + 4.0) * n_q
+        res.append({"format": f"S1E{E}M{M}", "bits": B, "pvt": pvt, "kernel_ms": ms,
+                    "algorithmic_GBps": alg / (ms * 1e-3) / 1e9, "frac_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        del arena, sb, ws, plan
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -359,6 +400,8 @@ def main():
     del wl
     torch.cuda.empty_cache()
     out["server_aggregation"] = aggregate_leg(torch, omc, synth, args.blocks)
+    torch.cuda.empty_cache()
+    out["paper_formats_sgd"] = formats_leg(torch, omc, synth, args.blocks)
     out["forward_gemm"] = gemm_leg(torch, omc, synth)
     if cpu is not None:
         out["cpu_baseline"] = {

@@ -43,7 +43,7 @@ bool make_fmt_params(omc_format f, FmtParams *out) {
     p.magic_off = static_cast<uint32_t>(23 - M) << 23;
     const int top_exp = top_field(f) - bias;
     p.wide = (M == 23 || top_exp + 23 - M > 127) ? 1u : 0u;
-    p.variant = (E == 4 && M == 3 && bias == 7) ? 2u : p.wide;
+    p.variant = (E == 4 && M == 3 && bias == 7) ? 2u : (E == 2 && M == 3 && bias == 1) ? 3u : p.wide;
     p.exp_adj = 127 + M;
     p.dec_scale = std::ldexp(1.0f, 127 - bias);
     p.enc_scale = std::ldexp(1.0f, bias - 127);
@@ -87,7 +87,7 @@ struct PlanLayout {
 static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *pl) {
     if (!vars) return OMC_ERR_NULL;
     if (nvars == 0) return OMC_ERR_SIZE;
-    bool present[99] = {false};   // 3 * bits + variant
+    bool present[132] = {false};  // 4 * bits + variant
     bool tails[2] = {false, false};
     bool any_fp32 = false;
     uint64_t nitems = 0;
@@ -105,7 +105,7 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
             const uint32_t bits = 1u + v.fmt.exp_bits + v.fmt.man_bits;
             FmtParams fp;
             make_fmt_params(v.fmt, &fp);
-            if (v.n >= kTileElems) present[3 * bits + fp.variant] = true;
+            if (v.n >= kTileElems) present[4 * bits + fp.variant] = true;
             if (v.n % kTileElems) tails[fp.wide] = true;
             bytes = packed_bytes_u(bits, v.n);
             ++nquant;
@@ -127,8 +127,8 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
     };
     if (overlaps(data) || overlaps(aux)) return OMC_ERR_SIZE;
     pl->groups.clear();
-    for (uint32_t k = 6; k < 99; ++k)
-        if (present[k]) pl->groups.push_back(PlanGroup{kGroupFull, k / 3, k % 3, 0, 0, 0});
+    for (uint32_t k = 8; k < 132; ++k)
+        if (present[k]) pl->groups.push_back(PlanGroup{kGroupFull, k / 4, k % 4, 0, 0, 0});
     for (uint32_t w = 0; w < 2; ++w)
         if (tails[w]) pl->groups.push_back(PlanGroup{kGroupTail, 0, w, 0, 0, 0});
     if (any_fp32) pl->groups.push_back(PlanGroup{kGroupFp32, 0, 0, 0, 0, 0});

@@ -17,6 +17,10 @@ static int launch_full(uint32_t bits, uint32_t variant, uint32_t grid, const Cod
         codec_kernel<8, kCompress, 2><<<dim3(grid), dim3(64), 0, st>>>(ca);
         return static_cast<int>(hipGetLastError());
     }
+    if (bits == 6 && variant == 3) {
+        codec_kernel<6, kCompress, 3><<<dim3(grid), dim3(64), 0, st>>>(ca);
+        return static_cast<int>(hipGetLastError());
+    }
     switch (bits) {
 #define X(BITS)                                                                                  \
     case BITS:                                                                                   \

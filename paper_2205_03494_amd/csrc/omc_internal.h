@@ -29,7 +29,8 @@ struct FmtParams {
     uint32_t magic_off;      // (23 - M) << 23
     uint32_t wide;           // 1: round with ldexp/rint (top binade + 23 - M would overflow fp32, or M == 23)
     uint32_t variant;        // kernel variant: 0 add/subtract rounding, 1 = wide, 2 = the format is OCP FP8 E4M3
-                             // except for its top code (S1E4M3, bias 7): hardware conversions apply
+                             // except for its top code (S1E4M3, bias 7), 3 = the format is the OCP microscaling
+                             // 6-bit E2M3 element (S1E2M3, bias 1): hardware conversions apply
     int32_t exp_adj;         // 127 + M
     float dec_scale;         // 2^(127 - bias)
     float enc_scale;         // 2^(bias - 127)
@@ -46,7 +47,7 @@ static_assert(sizeof(Partial) == 48, "Partial layout");
 
 // ---- plan blob ---------------------------------------------------------------------------
 constexpr uint32_t kPlanMagic = 0x434d4f50u;  // "POMC"
-constexpr uint32_t kPlanVersion = 3;
+constexpr uint32_t kPlanVersion = 4;
 
 struct PlanHeader {
     uint32_t magic, version;

@@ -4,6 +4,13 @@
 
 namespace omc {
 
+#ifndef OMC_TUNE_WAVES_FP6
+#define OMC_TUNE_WAVES_FP6 2
+#endif
+#ifndef OMC_TUNE_FP6_MAXMODE
+#define OMC_TUNE_FP6_MAXMODE 2      // kStepSgd: the hardware 6-bit variant serves plain SGD only
+#endif
+
 struct StepArgs {
     uint8_t *arena;
     const uint8_t *plan;      // device copy of the plan blob
@@ -79,7 +86,7 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
 }
 
 template <int B, int MODE, int VARIANT>
-__global__ __launch_bounds__(64, (Tuning<MODE, B>::waves)) void step_kernel(StepArgs sa) {
+__global__ __launch_bounds__(64, (VARIANT == 3 ? OMC_TUNE_WAVES_FP6 : Tuning<MODE, B>::waves)) void step_kernel(StepArgs sa) {
     __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
     if (blockIdx.x >= sa.nitems) {                       // the workgroups past the end serve fp32 variables
         do_fp32_item<MODE>(sa, sa.fp32_first + (blockIdx.x - sa.nitems));
@@ -108,6 +115,10 @@ inline int launch_step_group_mode(uint32_t bits, uint32_t variant, const StepArg
     // the hardware-conversion variant pays off where the vector ALU is the limit: plain SGD
     if (bits == 8 && variant == 2 && MODE == kStepSgd) {
         step_kernel<8, MODE, 2><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);
+        return static_cast<int>(hipGetLastError());
+    }
+    if (bits == 6 && variant == 3 && MODE <= OMC_TUNE_FP6_MAXMODE) {
+        step_kernel<6, MODE, 3><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);
         return static_cast<int>(hipGetLastError());
     }
     switch (bits) {

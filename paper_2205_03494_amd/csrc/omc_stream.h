@@ -580,6 +580,72 @@ __device__ __forceinline__ bool cycle_ocp_e4m3(const TileArgs &a, const OptConst
     return true;
 }
 
+// The same cycle for S1E2M3 with bias 1.  That format is the 6-bit E2M3 element type of the OCP
+// microscaling formats, code for code (no Inf / NaN codes, gradual underflow, saturating
+// nearest-even conversion), and gfx950 converts 32 such elements per lane in one instruction in
+// each direction, with exactly this library's packing (element k in bits [6k, 6k+6) of six
+// dwords): one instruction decodes the lane's tile, one rounds and packs it (its two 16-float
+// operands interleave: even elements, odd elements), one more decodes the new codes for the fit.
+// Probed against the oracle: identical for every code and position, every tie, subnormal and
+// overflow, and for +-Inf; only a NaN input is not covered (sign handling), and a NaN leaves a NaN in
+// the lane's sums, so such a tile is redone with cycle_generic.  Returns false when a redo is needed.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x32 __attribute__((ext_vector_type(32)));
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
+template <int MODE>
+__device__ __forceinline__ bool cycle_mx_fp6(const TileArgs &a, const OptConst &oc, uint32_t (&w)[6],
+                                             float (&rg)[32], float (&rm)[32], float (&rv)[32],
+                                             uint32_t (&o)[6], FitAcc &acc) {
+    const FitAcc saved = acc;
+    float nm[32], nv[32];
+    f32x16 xe, xo;                                         // new values: even and odd elements
+    if (MODE != kCompress) {
+        const u32x6 cw = {w[0], w[1], w[2], w[3], w[4], w[5]};
+        const f32x32 vt = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(cw, 1.0f);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const float sv = a.s * vt[i];
+            float x = sv + a.b;
+            if (MODE >= kStepSgd) {
+                float m = MODE >= kStepMomentum ? rm[i] : 0.0f, v = MODE == kStepAdam ? rv[i] : 0.0f;
+                x = apply_update<MODE>(x, rg[i], m, v, oc);
+                if (MODE >= kStepMomentum) nm[i] = m;
+                if (MODE == kStepAdam) nv[i] = v;
+            }
+            if (i & 1) xo[i >> 1] = x; else xe[i >> 1] = x;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            if (i & 1) xo[i >> 1] = rg[i]; else xe[i >> 1] = rg[i];
+        }
+    }
+    const u32x6 nw = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(xe, xo, 1.0f);
+    const f32x32 tq = __builtin_amdgcn_cvt_scalef32_pk32_f32_fp6(nw, 1.0f);
+    acc.seed(tq[0]);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        acc.add((i & 1) ? xo[i >> 1] : xe[i >> 1], tq[i]);
+        if (i % 4 == 3) { pin(acc.sV); pin(acc.sT); pin(acc.sVT); pin(acc.sTT); pin(acc.diff); }
+    }
+    const bool bad = (acc.sV != acc.sV);
+    if (__any(bad)) {
+        acc = saved;
+        return false;
+    }
+#pragma unroll
+    for (int j = 0; j < 6; ++j) o[j] = nw[j];
+    if (MODE >= kStepMomentum) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) rm[i] = nm[i];
+    }
+    if (MODE == kStepAdam) {
+#pragma unroll
+        for (int i = 0; i < 32; ++i) rv[i] = nv[i];
+    }
+    return true;
+}
+
 // Everything after the loads of the full tile at e0 have been issued into `st`.  When PREFETCH,
 // the loads of the next tile are issued into the same registers as soon as they are free, so
 // that they are in flight while this tile is computed.
@@ -600,6 +666,9 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
     uint32_t o[B];
     if constexpr (VARIANT == 2 && B == 8 && MODE != kDecompress) {
         if (!cycle_ocp_e4m3<MODE>(a, oc, w, rg, rm, rv, o, acc))
+            cycle_generic<B, MODE, false>(a, fp, oc, w, rg, rm, rv, o, acc);
+    } else if constexpr (VARIANT == 3 && B == 6 && MODE != kDecompress) {
+        if (!cycle_mx_fp6<MODE>(a, oc, w, rg, rm, rv, o, acc))
             cycle_generic<B, MODE, false>(a, fp, oc, w, rg, rm, rv, o, acc);
     } else {
         cycle_generic<B, MODE, VARIANT == 1>(a, fp, oc, w, rg, rm, rv, o, acc);

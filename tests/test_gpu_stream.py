@@ -247,3 +247,48 @@ def test_e4m3_top_code_overflow_and_non_finite_values(kind, lr):
                 assert np.array_equal(ga, oa)
             assert np.isnan(vs.g_sb.cpu().numpy()).all() and np.isnan(vs.o_sb).all()
     assert mism == 0
+
+
+def test_e2m3_hardware_path_saturation_and_non_finite_values():
+    """S1E2M3 (bias 1) runs on the hardware's 6-bit conversions in the SGD and compress kernels; a
+    tile that meets a NaN is redone generically.  Weights at the format's limits, updates that
+    overflow, every tie of the format, then a NaN and an Inf."""
+    n = 4 * 8192 + 2048 * 3
+    of, gf = pair(2, 3)
+    vals = synth.normal_f32(n, 1.0, 31)
+    vals[5] = 7.5; vals[2048 + 77] = -7.5; vals[9000] = 7.4; vals[20000:20064] = 100.0
+    ties = (np.arange(0, 128, dtype=np.float32) + 0.5) * np.float32(0.0625)      # midpoints of neighbouring values
+    vals[4096:4096 + 128] = ties
+    vals[6144:6144 + 128] = -ties
+    # compress alone first (codec kernel, hardware variant)
+    xd = to_dev(vals)
+    codes = torch.zeros(omc.omc_packed_bytes(gf, n), dtype=torch.uint8, device="cuda")
+    sb = torch.zeros(2, device="cuda")
+    ws = torch.empty(omc.omc_compress_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    omc.omc_compress(xd, n, gf, False, codes, sb, ws)
+    torch.cuda.synchronize()
+    want, _ = orc.compress(vals, of, use_pvt=False)
+    assert np.array_equal(codes.cpu().numpy(), want)
+    vs = VarSet(_single(n), [True], (2, 3), seed=0, values=vals)
+    mism = 0
+    for t in range(1, 4):
+        g = synth.normal_f32(n, 0.5, 400 + t)
+        g[12000] = -1e6
+        g[3] = 2000.0
+        if t == 3:
+            g[30000] = np.nan
+            g[31000] = np.inf
+            g[100] = -np.inf
+        vs.step_oracle(g, 0, 0.05, t)
+        vs.step_gpu(to_dev(g), 0, 0.05, t)
+        if t < 3:
+            mism += vs.compare(0, f"t={t}")
+        else:
+            torch.cuda.synchronize()
+            ga = vs.g_arena.cpu().numpy().copy()
+            oa = vs.o_arena.copy()
+            k = 30000 * 6 // 8                    # the NaN element's code bits: sign of a computed NaN is not pinned
+            ga[k:k + 2] = oa[k:k + 2] = 0
+            assert np.array_equal(ga, oa)
+            assert np.isnan(vs.g_sb.cpu().numpy()).all() and np.isnan(vs.o_sb).all()
+    assert mism == 0
