@@ -153,7 +153,7 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
         u32x4 a[AP];
         uint32_t w_raw[4][3], w_off[4];
     };
-    StageRegs r0, r1;
+    StageRegs r0, r1;                                      // r1 only in the two-ahead loop
 
     auto load_a_piece = [&](StageRegs &r, uint32_t k0, int p) {
         const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
@@ -256,7 +256,33 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
             multiply_frags(f);
         }
     };
-    // One steady-state round as straight-line code: fragments of both halves, the matrix instructions,
+    const uint32_t nk = K / kBK;
+    if constexpr (BM == 256) {
+    // One register set: the loads of K step ks+2 are issued right after the barrier that ends round
+    // ks and have all of round ks+1 to arrive before they are decoded and stored.
+    load_stage(r0, 0);
+    store_stage(r0, lds);
+    __syncthreads();
+    if (nk > 1) load_stage(r0, kBK);
+    uint32_t ks = 0;
+    for (; ks + 2 < nk; ++ks) {
+        const uint32_t cur = (ks & 1u) * kStageBytes;
+        multiply_stage(lds + cur);
+        store_stage(r0, lds + (kStageBytes - cur));
+        __syncthreads();
+        load_stage(r0, (ks + 2) * kBK);
+    }
+    for (; ks < nk; ++ks) {
+        const uint32_t cur = (ks & 1u) * kStageBytes;
+        multiply_stage(lds + cur);
+        if (ks + 1 < nk) {
+            store_stage(r0, lds + (kStageBytes - cur));
+            __syncthreads();
+        }
+    }
+    } else {
+    // The 128-row tiling (three workgroups per compute unit) does better with loads two K steps ahead
+    // in two register sets.  One steady-state round as straight-line code: fragments of both halves, the matrix instructions,
     // decode + LDS stores of the next K step, barrier, global loads of the step after the next two.
     auto steady_round = [&](const uint8_t *cur, uint8_t *nxt, StageRegs &r, uint32_t k_load) {
         multiply_stage(cur);
@@ -265,7 +291,6 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
         load_stage(r, k_load);
     };
 
-    const uint32_t nk = K / kBK;
     uint8_t *buf0 = lds, *buf1 = lds + kStageBytes;
     load_stage(r0, 0);
     store_stage(r0, buf0);
@@ -289,6 +314,7 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
             __syncthreads();
             if (it + 4 < nk) load_stage(r1, (it + 4) * kBK);
         }
+    }
     }
 
     // ---- epilogue: C = s * acc + b * rowsum --------------------------------------------------------
