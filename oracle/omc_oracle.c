@@ -498,3 +498,33 @@ int orc_mean_f32(const float *const *v, int R, uint64_t n, float *out)
     }
     return 0;
 }
+
+/* ---- backward path of a linear layer: gradient with respect to the input ------------------------
+ * Sec. 2.1, backward propagation: the layer's parameters are decompressed on the fly here too.
+ * For Y = X * Wbar with Wbar [K x N] the input gradient is dX = dY * Wbar^T:
+ *     dX[i][k] = sum_j dY[i][j] * Wbar[k][j],
+ * evaluated in double on the fp32 values of the decompressed weights and the bfloat16 values of dY. */
+int orc_dequant_gemm_dx(const uint16_t *dY, const uint8_t *packed, orc_format f, const float *sb,
+                        double *dX, uint32_t M, uint32_t N, uint32_t K,
+                        uint32_t row_begin, uint32_t row_end, int threads)
+{
+    uint64_t n = (uint64_t)K * N;
+    float *W = (float *)malloc(n * sizeof(float));
+    if (!W) return 2;
+    int rc = orc_decompress(packed, n, f, sb, W);
+    if (rc) { free(W); return rc; }
+    if (row_end > M) row_end = M;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for schedule(static) num_threads(threads)
+    for (uint32_t i = row_begin; i < row_end; ++i) {
+        double *d = dX + (uint64_t)(i - row_begin) * K;
+        for (uint32_t k = 0; k < K; ++k) {
+            const float *w = W + (uint64_t)k * N;
+            double acc = 0.0;
+            for (uint32_t j = 0; j < N; ++j) acc += bf16_value(dY[(uint64_t)i * N + j]) * (double)w[j];
+            d[k] = acc;
+        }
+    }
+    free(W);
+    return 0;
+}

@@ -91,6 +91,10 @@ def lib():
         L.orc_step_varset.restype = C.c_int
         L.orc_step_varset.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.POINTER(_Opt), C.c_int]
+        L.orc_dequant_gemm_dx.restype = C.c_int
+        L.orc_dequant_gemm_dx.argtypes = [C.c_void_p, C.c_void_p, _Fmt, C.c_void_p, C.c_void_p,
+                                          C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+                                          C.c_int]
         L.orc_mean_f32.restype = C.c_int
         L.orc_mean_f32.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_void_p]
         L.orc_dequant_gemm.restype = C.c_int
@@ -284,6 +288,20 @@ def dequant_gemm(A_bf16_bits, packed, fmt: Format, sb, M, N, K, rows=None, threa
                                 int(threads))
     if rc:
         raise ValueError(f"orc_dequant_gemm failed ({rc})")
+    return out
+
+
+def dequant_gemm_dx(dY_bf16_bits, packed, fmt: Format, sb, M, N, K, rows=None, threads: int = 1):
+    """dX[rows] = dY[rows] @ decompress(packed)^T in double; the weights are [K, N], dY is uint16 bf16 bits [M, N]."""
+    dY = np.ascontiguousarray(dY_bf16_bits, dtype=np.uint16)
+    assert dY.size == M * N
+    r0, r1 = (0, M) if rows is None else rows
+    out = np.empty((r1 - r0, K), dtype=np.float64)
+    sbp = None if sb is None else np.ascontiguousarray(sb, dtype=np.float32)
+    b = np.ascontiguousarray(packed, dtype=np.uint8)
+    rc = lib().orc_dequant_gemm_dx(_p(dY), _p(b), fmt.c(), _p(sbp), _p(out), M, N, K, r0, r1, int(threads))
+    if rc:
+        raise ValueError(f"orc_dequant_gemm_dx failed ({rc})")
     return out
 
 

@@ -319,3 +319,28 @@ def test_gemm_oracle_against_numpy_matmul():
     x = synth.normal_f32(10000, 3.0, 4)
     want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(synth.to_bf16_bits(x), want)
+
+
+def test_gemm_dx_oracle_against_numpy_and_the_adjoint_identity():
+    """dX = dY @ Wbar^T.  Pinned to numpy's matmul on the decompressed weights and, independently of any
+    matmul layout convention, to the adjoint identity <dY, X Wbar> = <dY Wbar^T, X> with the forward oracle."""
+    fmt = Format(3, 7)
+    M, N, K = 24, 40, 56
+    X = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 1))
+    dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 3))
+    W = synth.normal_f32(K * N, 1 / np.sqrt(K), 2)
+    packed, sb = orc.compress(W, fmt)
+    dX = orc.dequant_gemm_dx(dY, packed, fmt, sb, M, N, K)
+    assert dX.shape == (M, K)
+    dYf = (dY.astype(np.uint32) << 16).view(np.float32).astype(np.float64).reshape(M, N)
+    Xf = (X.astype(np.uint32) << 16).view(np.float32).astype(np.float64).reshape(M, K)
+    Wb = orc.decompress(packed, K * N, fmt, sb).astype(np.float64).reshape(K, N)
+    assert np.allclose(dX, dYf @ Wb.T, rtol=1e-12, atol=1e-12)
+    Y = orc.dequant_gemm(X, packed, fmt, sb, M, N, K)
+    lhs, rhs = float(np.sum(dYf * Y)), float(np.sum(dX * Xf))
+    assert abs(lhs - rhs) <= 1e-10 * max(abs(lhs), 1.0)
+    assert np.array_equal(orc.dequant_gemm_dx(dY, packed, fmt, sb, M, N, K, rows=(3, 11)), dX[3:11])
+    # a transposed operand would fail here: non-square weights, one-hot dY picks out rows of Wbar^T
+    e = np.zeros((M, N), np.float32); e[0, 7] = 1.0
+    d1 = orc.dequant_gemm_dx(synth.to_bf16_bits(e.ravel()), packed, fmt, sb, M, N, K)
+    assert np.array_equal(d1[0], Wb[:, 7]) and not d1[1:].any()
