@@ -129,8 +129,23 @@ def gemm_leg(torch, omc, synth, iters=20):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / iters
         tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-        out.append({"M": M, "N": N, "K": K, "ms": ms, "TFLOPs": tf, "frac_of_bf16_mfma_peak": tf / 2500.0,
-                    "hbm_bytes": 2 * M * K + K * N + 4 * M * N})
+        rec = {"M": M, "N": N, "K": K, "ms": ms, "TFLOPs": tf, "frac_of_bf16_mfma_peak": tf / 2500.0,
+               "hbm_bytes": 2 * M * K + K * N + 4 * M * N}
+        # the same layer's input gradient: dX[M, K] = dY[M, N] @ Wbar^T
+        del C
+        dY = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 13)).view(np.int16)).cuda()
+        dX = torch.empty((M, K), dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws)
+        e0.record()
+        for _ in range(iters):
+            omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        rec["dx_ms"] = ms
+        rec["dx_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        out.append(rec)
     return out
 
 

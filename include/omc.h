@@ -11,6 +11,7 @@
  *   omc_step_update_recompress   one training iteration over a whole variable set:
  *                                decompress -> parameter update -> recompress, fused     (Sec. 2.1, backward path)
  *   omc_dequant_gemm             C = A * decompress(W), weights expanded on chip          (Sec. 2.1, forward path)
+ *   omc_dequant_gemm_dx          dX = dY * decompress(W)^T                                (Sec. 2.1, backward path)
  *   omc_aggregate_mean           server: mean of R clients' mixed-precision copies        (Sec. 1, 2.5)
  *
  * Conventions that hold for every entry point
@@ -283,6 +284,22 @@ size_t omc_dequant_gemm_workspace_bytes(uint32_t M);
 omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, const float *sb,
                             float *C, uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes,
                             void *stream);
+
+/* ---- backward path: gradient with respect to the layer's input ----------------------------- */
+
+/* dX[M x K] = dY[M x N] * Wbar^T for the same packed K*N-element variable that omc_dequant_gemm
+ * multiplies by (Sec. 2.1, backward propagation: the parameters a layer needs are decompressed on the
+ * fly there as well; they are expanded inside the kernel here).
+ *   dY       device, M*N bfloat16 bit patterns, row-major
+ *   codes    device, packed variable, element index k*N + j   (unchanged layout; read transposed)
+ *   sb       device, 2 floats, or NULL for (1, 0)
+ *   dX       device, M*K floats, row-major; fp32 accumulation
+ *   ws       device workspace of omc_dequant_gemm_workspace_bytes(M) bytes
+ * Uses dY*(s*Vt + b*1)^T = s*(dY*Vt^T) + b*rowsum(dY)*1^T.  Requires man_bits <= 7, M % 256 == 0,
+ * K % 128 == 0, N % 32 == 0 (OMC_ERR_FORMAT / OMC_ERR_SIZE); otherwise as omc_dequant_gemm. */
+omc_status omc_dequant_gemm_dx(const uint16_t *dY, const void *codes, omc_format f, const float *sb,
+                               float *dX, uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes,
+                               void *stream);
 
 #ifdef __cplusplus
 }

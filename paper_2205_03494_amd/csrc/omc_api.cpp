@@ -621,7 +621,23 @@ omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, 
         return OMC_ERR_ALIGN;
     if (!ws || ws_bytes < omc_dequant_gemm_workspace_bytes(M)) return OMC_ERR_WORKSPACE;
     if (!aligned16(ws)) return OMC_ERR_ALIGN;
-    const int rc = launch_dequant_gemm(A, codes, fp, sb, C, M, N, K, static_cast<float *>(ws), stream);
+    const int rc = launch_dequant_gemm(A, codes, fp, sb, C, M, N, K, static_cast<float *>(ws), 0, stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+omc_status omc_dequant_gemm_dx(const uint16_t *dY, const void *codes, omc_format f, const float *sb, float *dX,
+                               uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes, void *stream) {
+    if (!dY || !codes || !dX) return OMC_ERR_NULL;
+    FmtParams fp;
+    if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
+    if (fp.man_bits > 7) return OMC_ERR_FORMAT;
+    if (M == 0 || N == 0 || K == 0 || M % 256 != 0 || K % 128 != 0 || N % 32 != 0) return OMC_ERR_SIZE;
+    if (!aligned16(dY) || !aligned16(codes) || !aligned16(dX) || (reinterpret_cast<uintptr_t>(sb) & 3u))
+        return OMC_ERR_ALIGN;
+    if (!ws || ws_bytes < omc_dequant_gemm_workspace_bytes(M)) return OMC_ERR_WORKSPACE;
+    if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    // output columns = K (the weights' rows), contraction over N
+    const int rc = launch_dequant_gemm(dY, codes, fp, sb, dX, M, K, N, static_cast<float *>(ws), 1, stream);
     return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
 }
 

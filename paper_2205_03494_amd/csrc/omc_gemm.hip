@@ -125,7 +125,9 @@ __device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32
 }
 
 // DEC: 0 = any code width, 1 = byte codes.  HW (byte codes of S1E4M3 / bias 7 only): hardware FP8 conversion.
-template <int BM, int DEC, bool HW>
+// TRANS: the packed variable is [N x K] (output column major), i.e. C = A * W^T for the weights as
+// stored: the input-gradient GEMM of the layer whose forward pass is the non-transposed one.
+template <int BM, int DEC, bool HW, bool TRANS>
 __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A, const uint32_t *__restrict__ codes,
                                                   uint64_t total_dwords, const FmtParams &fp,
                                                   const float *__restrict__ sb, const float *__restrict__ rowsum,
@@ -147,6 +149,10 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
     const uint32_t w_h = lane & 1u, w_cg = lane >> 1;
     const uint32_t w_kg = 2 * wave + w_h;
     const uint64_t w_col = n0 + 4 * w_cg;
+    // W transposed: thread = (LDS slot, half of the K step); slot 32 i + cg holds column 4 cg + i, and the
+    // thread takes that column's 16 consecutive k-values (contiguous in memory) as four groups of four
+    const uint32_t t_slot = tid & 127u, t_h = tid >> 7;
+    const uint64_t t_row = n0 + 4 * (t_slot & 31u) + (t_slot >> 5);
 
     // two register sets: global loads run two K steps ahead of the matrix cores
     struct StageRegs {
@@ -160,12 +166,22 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
         r.a[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
     };
     auto load_w_row = [&](StageRegs &r, uint32_t k0, int rr) {
-        const uint64_t e = static_cast<uint64_t>(k0 + 4 * w_kg + rr) * N + w_col;
+        const uint64_t e = TRANS ? t_row * K + k0 + 16 * t_h + 4 * rr
+                                 : static_cast<uint64_t>(k0 + 4 * w_kg + rr) * N + w_col;
         load_codes4<BYTE>(codes, total_dwords, e, fp.bits, r.w_raw[rr], r.w_off[rr]);
     };
     auto load_stage = [&](StageRegs &r, uint32_t k0) {
 #pragma unroll
         for (int p = 0; p < AP; ++p) load_a_piece(r, k0, p);
+        if (TRANS && BYTE) {                                // the thread's 16 codes are one aligned 16-byte piece
+            const u32x4 t = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(codes) + t_row * K + k0 + 16 * t_h);
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                r.w_raw[rr][0] = t[rr];
+                r.w_off[rr] = 0;
+            }
+            return;
+        }
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) load_w_row(r, k0, rr);
     };
@@ -184,6 +200,25 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
     // decode and store of the patch in four parts (part i = column 4 cg + i; the hardware conversion
     // yields two columns at a time, so its parts 1 and 3 are empty)
     auto store_w_part = [&](const StageRegs &r, uint8_t *ldsA, int part) {
+        if (TRANS) {                                        // part = group of four consecutive k-values
+            uint32_t v[4];
+            if (HW) {
+                const f32x2 c01 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[part][0]), false);
+                const f32x2 c23 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[part][0]), true);
+                v[0] = __float_as_uint(c01[0]); v[1] = __float_as_uint(c01[1]);
+                v[2] = __float_as_uint(c23[0]); v[3] = __float_as_uint(c23[1]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    v[i] = decode_bits(code_top_of<BYTE>(r.w_raw[part], r.w_off[part], fp.bits, i), fp);
+            }
+            uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
+            u32x2 out;
+            out[0] = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);
+            out[1] = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
+            *reinterpret_cast<u32x2 *>(ldsW + (2u * t_h + (part >> 1)) * kWChunkBytes + (t_slot << 4) + 8u * (part & 1)) = out;
+            return;
+        }
         if (HW) {
             if (part & 1) return;
             f32x2 c[4];
@@ -344,7 +379,7 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
 }
 
 // DEC 2 = byte codes of S1E4M3 / bias 7: hardware conversion unless the pre-pass found a top code.
-template <int BM, int DEC>
+template <int BM, int DEC, bool TRANS>
 __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
                                                               const uint32_t *__restrict__ codes, uint64_t total_dwords,
                                                               FmtParams fp, const float *__restrict__ sb,
@@ -356,15 +391,16 @@ __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_g
     if (DEC == 2) {
         const bool top = __any(flags[threadIdx.x & 63u] != 0);
         if (!top) {
-            dequant_gemm_body<BM, 1, true>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
+            dequant_gemm_body<BM, 1, true, TRANS>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
             return;
         }
     }
-    dequant_gemm_body<BM, (DEC == 0 ? 0 : 1), false>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
+    dequant_gemm_body<BM, (DEC == 0 ? 0 : 1), false, TRANS>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
 }
 
+// C[M x N] = A[M x K] * W (trans == 0, W packed as [K x N]) or A * W^T (trans != 0, W packed as [N x K])
 int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb, float *C,
-                        uint32_t M, uint32_t N, uint32_t K, float *ws, void *stream) {
+                        uint32_t M, uint32_t N, uint32_t K, float *ws, int trans, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint64_t n = static_cast<uint64_t>(K) * N;
     const uint64_t total_dwords = ((n * fp.bits + 7) / 8 + 15) / 16 * 4;
@@ -383,8 +419,15 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
     }
     // 256-row tiles unless they would leave fewer than two workgroups per compute unit
     const bool small = static_cast<uint64_t>(M / 256) * (N / kBN) < 512;
-#define OMC_GEMM_LAUNCH(BM, DEC) \
-    dequant_gemm_kernel<BM, DEC><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, rowsum, C, M, N, K, flags)
+#define OMC_GEMM_LAUNCH(BM, DEC)                                                                                    \
+    do {                                                                                                            \
+        if (trans)                                                                                                  \
+            dequant_gemm_kernel<BM, DEC, true><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, \
+                                                                                            rowsum, C, M, N, K, flags); \
+        else                                                                                                        \
+            dequant_gemm_kernel<BM, DEC, false><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, \
+                                                                                             rowsum, C, M, N, K, flags); \
+    } while (0)
     if (!small) {
         if (dec == 2) OMC_GEMM_LAUNCH(256, 2);
         else if (dec == 1) OMC_GEMM_LAUNCH(256, 1);

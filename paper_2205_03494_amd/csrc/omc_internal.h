@@ -145,6 +145,6 @@ struct AggPointers {
 };
 int launch_aggregate_mean(const AggHeader *ah, const void *agg_dev, const AggPointers &ptrs, float *out, void *stream);
 int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &fp, const float *sb,
-                        float *C, uint32_t M, uint32_t N, uint32_t K, float *rowsum, void *stream);
+                        float *C, uint32_t M, uint32_t N, uint32_t K, float *ws, int trans, void *stream);
 
 }  // namespace omc

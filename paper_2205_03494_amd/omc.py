@@ -83,6 +83,8 @@ _agg_mean = _sig("omc_aggregate_mean", C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.
 _gemm_ws = _sig("omc_dequant_gemm_workspace_bytes", C.c_size_t, C.c_uint32)
 _gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
              C.c_uint32, _vp, C.c_size_t, _vp)
+_gemm_dx = _sig("omc_dequant_gemm_dx", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
+                C.c_uint32, _vp, C.c_size_t, _vp)
 
 EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_format_max",
             "omc_packed_bytes", "omc_compress_workspace_bytes", "omc_compress", "omc_decompress",
@@ -91,7 +93,7 @@ EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_
             "omc_step_update_recompress_events", "omc_compress_set", "omc_decompress_set",
             "omc_plan_transport_bytes", "omc_aggregate_plan_bytes", "omc_aggregate_plan_build",
             "omc_aggregate_mean", "omc_dequant_gemm_workspace_bytes",
-            "omc_dequant_gemm"]
+            "omc_dequant_gemm", "omc_dequant_gemm_dx"]
 
 
 class OmcError(RuntimeError):
@@ -282,6 +284,12 @@ def omc_dequant_gemm(A: torch.Tensor, codes: torch.Tensor, f: omc_format, sb: Op
                      Cout: torch.Tensor, M: int, N: int, K: int, ws: torch.Tensor, stream=None) -> None:
     _check(_gemm(_ptr(A), _ptr(codes), f, _ptr(sb), _ptr(Cout), M, N, K, _ptr(ws),
                  ws.numel() * ws.element_size(), _stream(stream)), "omc_dequant_gemm")
+
+
+def omc_dequant_gemm_dx(dY: torch.Tensor, codes: torch.Tensor, f: omc_format, sb: Optional[torch.Tensor],
+                        dX: torch.Tensor, M: int, N: int, K: int, ws: torch.Tensor, stream=None) -> None:
+    _check(_gemm_dx(_ptr(dY), _ptr(codes), f, _ptr(sb), _ptr(dX), M, N, K, _ptr(ws),
+                    ws.numel() * ws.element_size(), _stream(stream)), "omc_dequant_gemm_dx")
 
 
 # --------------------------------------------------------------------------- server aggregation

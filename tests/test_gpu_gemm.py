@@ -89,3 +89,58 @@ def test_every_byte_code_exact_with_and_without_the_top_code(top_at):
     C = run_gemm(synth.to_bf16_bits(A.ravel()), orc.pack(codes, 8), gf, None, M, N, K)
     want = W.reshape(K, N)[np.arange(M) % K]
     assert np.array_equal(C, want)
+
+
+def run_gemm_dx(dY_bits, packed, gf, sb, M, N, K):
+    dX = torch.full((M, K), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(omc.omc_dequant_gemm_workspace_bytes(M), dtype=torch.uint8, device="cuda")
+    omc.omc_dequant_gemm_dx(to_dev(dY_bits), to_dev(packed), gf, None if sb is None else to_dev(sb), dX, M, N, K, ws)
+    torch.cuda.synchronize()
+    return dX.cpu().numpy()
+
+
+@pytest.mark.parametrize("EM", [(4, 3), (5, 2), (2, 3), (3, 7), (8, 7), (4, 3, 4)])
+@pytest.mark.parametrize("shape", [(256, 32, 128), (256, 96, 256), (512, 160, 128)])
+def test_dx_small_shapes_all_rows(EM, shape):
+    of, gf = pair(*EM)
+    M, N, K = shape
+    dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 5))
+    W = synth.normal_f32(K * N, 1 / np.sqrt(K), 2)
+    packed, sb = orc.compress(W, of)
+    dX = run_gemm_dx(dY, packed, gf, sb, M, N, K)
+    rel = check(dX, orc.dequant_gemm_dx(dY, packed, of, sb, M, N, K, threads=8), (0, M))
+    assert rel < 1e-5
+    dX = run_gemm_dx(dY, packed, gf, None, M, N, K)
+    check(dX, orc.dequant_gemm_dx(dY, packed, of, None, M, N, K, threads=8), (0, M))
+
+
+@pytest.mark.parametrize("top_at", [None, 777])
+def test_dx_identity_pattern_pins_the_transposed_layout(top_at):
+    # dY = one-hot rows: dX must reproduce columns of W exactly, with and without a top code (both decodes)
+    of, gf = pair(4, 3)
+    M, N, K = 256, 64, 128
+    dY = np.zeros((M, N), np.float32)
+    dY[np.arange(M), np.arange(M) % N] = 1.0
+    codes = ((np.arange(K * N, dtype=np.int64) * 37 + 11) % 254).astype(np.uint32)
+    codes = np.where(codes >= 127, codes + 1, codes)
+    if top_at is not None:
+        codes[top_at] = 0x7F
+    W = orc.decode(codes, of).reshape(K, N)
+    dX = run_gemm_dx(synth.to_bf16_bits(dY.ravel()), orc.pack(codes, 8), gf, None, M, N, K)
+    want = W[:, np.arange(M) % N].T
+    assert np.array_equal(dX, want)
+
+
+@pytest.mark.parametrize("shape", [(8192, 4096, 1024), (8192, 1024, 4096)])
+def test_dx_config5_shapes_sampled_rows(shape):
+    M, N, K = shape
+    of, gf = pair(4, 3)
+    dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 13))
+    W = synth.normal_f32(K * N, 1 / np.sqrt(K), 12)
+    packed, sb = orc.compress(W, of)
+    dX = run_gemm_dx(dY, packed, gf, sb, M, N, K)
+    assert np.all(np.isfinite(dX))
+    for r0 in (0, 4000, M - 24):
+        ref = orc.dequant_gemm_dx(dY, packed, of, sb, M, N, K, rows=(r0, r0 + 24), threads=8)
+        rel = check(dX, ref, (r0, r0 + 24))
+        assert rel < 1e-5
