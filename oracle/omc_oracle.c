@@ -528,3 +528,27 @@ int orc_dequant_gemm_dx(const uint16_t *dY, const uint8_t *packed, orc_format f,
     free(W);
     return 0;
 }
+
+/* ---- backward path of a linear layer: gradient with respect to the weights -----------------------
+ * For Y = X * Wbar the weight gradient is dW = X^T * dY:
+ *     dW[k][j] = sum_i X[i][k] * dY[i][j],
+ * in double on the bfloat16 values of X [M x K] and dY [M x N].  The update that consumes it is
+ * orc_step_quantized with this gradient (Sec. 2.1, backward propagation: decompress, apply the
+ * gradient, compress, discard). */
+int orc_gemm_dw(const uint16_t *X, const uint16_t *dY, double *dW, uint32_t M, uint32_t N, uint32_t K,
+                uint32_t row_begin, uint32_t row_end, int threads)
+{
+    if (row_end > K) row_end = K;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for schedule(static) num_threads(threads)
+    for (uint32_t k = row_begin; k < row_end; ++k) {
+        double *d = dW + (uint64_t)(k - row_begin) * N;
+        for (uint32_t j = 0; j < N; ++j) d[j] = 0.0;
+        for (uint32_t i = 0; i < M; ++i) {
+            double x = bf16_value(X[(uint64_t)i * K + k]);
+            const uint16_t *g = dY + (uint64_t)i * N;
+            for (uint32_t j = 0; j < N; ++j) d[j] += x * bf16_value(g[j]);
+        }
+    }
+    return 0;
+}

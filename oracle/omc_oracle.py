@@ -95,6 +95,9 @@ def lib():
         L.orc_dequant_gemm_dx.argtypes = [C.c_void_p, C.c_void_p, _Fmt, C.c_void_p, C.c_void_p,
                                           C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                           C.c_int]
+        L.orc_gemm_dw.restype = C.c_int
+        L.orc_gemm_dw.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
+                                  C.c_uint32, C.c_uint32, C.c_int]
         L.orc_mean_f32.restype = C.c_int
         L.orc_mean_f32.argtypes = [C.c_void_p, C.c_int, C.c_uint64, C.c_void_p]
         L.orc_dequant_gemm.restype = C.c_int
@@ -302,6 +305,19 @@ def dequant_gemm_dx(dY_bf16_bits, packed, fmt: Format, sb, M, N, K, rows=None, t
     rc = lib().orc_dequant_gemm_dx(_p(dY), _p(b), fmt.c(), _p(sbp), _p(out), M, N, K, r0, r1, int(threads))
     if rc:
         raise ValueError(f"orc_dequant_gemm_dx failed ({rc})")
+    return out
+
+
+def gemm_dw(X_bf16_bits, dY_bf16_bits, M, N, K, rows=None, threads: int = 1):
+    """dW[rows] = (X^T @ dY)[rows] in double; X is [M, K], dY is [M, N], both uint16 bf16 bits; rows index k."""
+    X = np.ascontiguousarray(X_bf16_bits, dtype=np.uint16)
+    dY = np.ascontiguousarray(dY_bf16_bits, dtype=np.uint16)
+    assert X.size == M * K and dY.size == M * N
+    r0, r1 = (0, K) if rows is None else rows
+    out = np.empty((r1 - r0, N), dtype=np.float64)
+    rc = lib().orc_gemm_dw(_p(X), _p(dY), _p(out), M, N, K, r0, r1, int(threads))
+    if rc:
+        raise ValueError(f"orc_gemm_dw failed ({rc})")
     return out
 
 

@@ -344,3 +344,28 @@ def test_gemm_dx_oracle_against_numpy_and_the_adjoint_identity():
     e = np.zeros((M, N), np.float32); e[0, 7] = 1.0
     d1 = orc.dequant_gemm_dx(synth.to_bf16_bits(e.ravel()), packed, fmt, sb, M, N, K)
     assert np.array_equal(d1[0], Wb[:, 7]) and not d1[1:].any()
+
+
+def test_gemm_dw_oracle_against_numpy_and_the_adjoint_identity():
+    """dW = X^T @ dY.  Pinned to numpy and to <dW, W> = <dY, X W> with the forward oracle (identity
+    transformation, so that W is exactly what the forward oracle multiplies by)."""
+    fmt = Format(4, 3)
+    M, N, K = 40, 24, 56
+    X = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 1))
+    dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 3))
+    dW = orc.gemm_dw(X, dY, M, N, K)
+    assert dW.shape == (K, N)
+    Xf = (X.astype(np.uint32) << 16).view(np.float32).astype(np.float64).reshape(M, K)
+    dYf = (dY.astype(np.uint32) << 16).view(np.float32).astype(np.float64).reshape(M, N)
+    assert np.allclose(dW, Xf.T @ dYf, rtol=1e-12, atol=1e-12)
+    assert np.array_equal(orc.gemm_dw(X, dY, M, N, K, rows=(7, 19)), dW[7:19])
+    W = synth.normal_f32(K * N, 0.1, 2)
+    packed, _ = orc.compress(W, fmt, use_pvt=False)
+    Wq = orc.decompress(packed, K * N, fmt, None).astype(np.float64).reshape(K, N)
+    Y = orc.dequant_gemm(X, packed, fmt, None, M, N, K)
+    lhs, rhs = float(np.sum(dW * Wq)), float(np.sum(dYf * Y))
+    assert abs(lhs - rhs) <= 1e-10 * max(abs(lhs), 1.0)
+    # one-hot X row picks out a row of dY at the right k (fails for a transposed operand: K != N != M)
+    e = np.zeros((M, K), np.float32); e[5, 9] = 1.0
+    d1 = orc.gemm_dw(synth.to_bf16_bits(e.ravel()), dY, M, N, K)
+    assert np.array_equal(d1[9], dYf[5]) and not np.delete(d1, 9, axis=0).any()
