@@ -145,6 +145,21 @@ def gemm_leg(torch, omc, synth, iters=20):
         ms = e0.elapsed_time(e1) / iters
         rec["dx_ms"] = ms
         rec["dx_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        # and its weight gradient dW[K, N] = X^T @ dY, consumed by the SGD update + recompression in the epilogue
+        del dX
+        wsd = torch.empty(omc.omc_dw_update_workspace_bytes(N, K), dtype=torch.uint8, device="cuda")
+        o = omc.opt(omc.OMC_SGD, 0.01)
+        for _ in range(3):
+            omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd)
+        e0.record()
+        for _ in range(iters):
+            omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        rec["dw_update_ms"] = ms
+        rec["dw_update_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        rec["dw_gradient_bytes_not_materialized"] = 4 * K * N
         out.append(rec)
     return out
 

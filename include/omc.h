@@ -12,6 +12,7 @@
  *                                decompress -> parameter update -> recompress, fused     (Sec. 2.1, backward path)
  *   omc_dequant_gemm             C = A * decompress(W), weights expanded on chip          (Sec. 2.1, forward path)
  *   omc_dequant_gemm_dx          dX = dY * decompress(W)^T                                (Sec. 2.1, backward path)
+ *   omc_dw_update_recompress     dW = X^T dY consumed by the update in the GEMM's epilogue  (Sec. 2.1, backward path)
  *   omc_aggregate_mean           server: mean of R clients' mixed-precision copies        (Sec. 1, 2.5)
  *
  * Conventions that hold for every entry point
@@ -300,6 +301,32 @@ omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, 
 omc_status omc_dequant_gemm_dx(const uint16_t *dY, const void *codes, omc_format f, const float *sb,
                                float *dX, uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes,
                                void *stream);
+
+/* ---- backward path: weight gradient consumed by the update ---------------------------------- */
+
+/* Workspace (device bytes) for omc_dw_update_recompress on a K x N weight matrix; 0 for unsupported sizes. */
+size_t omc_dw_update_workspace_bytes(uint32_t N, uint32_t K);
+
+/* The whole backward step of a linear layer Y = X * Wbar on its compressed weights (Sec. 2.1, backward
+ * propagation: decompress the parameters, apply the gradients, compress, discard): the weight
+ * gradient dW[K x N] = X^T * dY is formed on the matrix cores (fp32 accumulation) and consumed at
+ * once: every weight is decoded and transformed (Sec. 2.2, 2.3), updated with its gradient by the
+ * optimizer of omc_step_update_recompress, rounded to the format and stored back, and new (s, b)
+ * are fitted.  The gradient itself is not written to memory unless dW_out is given.
+ *   X        device, M*K bfloat16 bit patterns, row-major (the layer's input)
+ *   dY       device, M*N bfloat16 bit patterns, row-major (gradient of the layer's output)
+ *   codes    device, packed K*N-element variable, element index k*N + j, updated in place
+ *   sb       device, 2 floats, in: (s, b) of the variable, out: the new pair ((1, 0) when use_pvt == 0)
+ *   state0/1 device, K*N floats each, as for omc_step_update_recompress (momentum / Adam moments)
+ *   dW_out   device, K*N floats, or NULL; receives the gradient exactly as the update consumed it
+ *   ws       device workspace of omc_dw_update_workspace_bytes(N, K) bytes
+ * Requires an 8-bit format (a lane of the accumulator layout then owns whole dwords of codes),
+ * K % 256 == 0, N % 128 == 0, M % 32 == 0 (OMC_ERR_FORMAT / OMC_ERR_SIZE).  Result: identical to
+ * omc_step_update_recompress on this variable with dW_out as its gradient. */
+omc_status omc_dw_update_recompress(const uint16_t *X, const uint16_t *dY, void *codes, omc_format f,
+                                    float *sb, int use_pvt, float *state0, float *state1,
+                                    const omc_opt *opt, float *dW_out, uint32_t M, uint32_t N, uint32_t K,
+                                    void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -625,6 +625,33 @@ omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, 
     return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
 }
 
+size_t omc_dw_update_workspace_bytes(uint32_t N, uint32_t K) {
+    if (N == 0 || K == 0 || K % 256 != 0 || N % 128 != 0) return 0;
+    return static_cast<size_t>(4) * (K / 128) * (N / 128) * sizeof(Partial);   // one partial per wave of the smaller tiling
+}
+
+omc_status omc_dw_update_recompress(const uint16_t *X, const uint16_t *dY, void *codes, omc_format f, float *sb,
+                                    int use_pvt, float *state0, float *state1, const omc_opt *opt, float *dW_out,
+                                    uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes, void *stream) {
+    if (!X || !dY || !codes || !sb || !opt) return OMC_ERR_NULL;
+    FmtParams fp;
+    if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
+    if (fp.bits != 8) return OMC_ERR_FORMAT;
+    if (M == 0 || N == 0 || K == 0 || M % 32 != 0 || K % 256 != 0 || N % 128 != 0) return OMC_ERR_SIZE;
+    if (opt->kind != OMC_SGD && opt->kind != OMC_MOMENTUM && opt->kind != OMC_ADAM) return OMC_ERR_OPT;
+    if (opt->kind >= OMC_MOMENTUM && !state0) return OMC_ERR_OPT;
+    if (opt->kind == OMC_ADAM && !state1) return OMC_ERR_OPT;
+    if (!aligned16(X) || !aligned16(dY) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return OMC_ERR_ALIGN;
+    if ((state0 && !aligned16(state0)) || (state1 && !aligned16(state1)) || (dW_out && !aligned16(dW_out)))
+        return OMC_ERR_ALIGN;
+    const size_t need = omc_dw_update_workspace_bytes(N, K);
+    if (!ws || ws_bytes < need) return OMC_ERR_WORKSPACE;
+    if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    const int rc = launch_dw_update(X, dY, codes, fp, sb, use_pvt, state0, state1, *opt, dW_out, M, N, K,
+                                    static_cast<Partial *>(ws), stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
 omc_status omc_dequant_gemm_dx(const uint16_t *dY, const void *codes, omc_format f, const float *sb, float *dX,
                                uint32_t M, uint32_t N, uint32_t K, void *ws, size_t ws_bytes, void *stream) {
     if (!dY || !codes || !dX) return OMC_ERR_NULL;

@@ -1,0 +1,295 @@
+// omc_dw_update_recompress: the backward pass of a linear layer on a compressed weight matrix
+// (paper Sec. 2.1, backward propagation: decompress the layer's parameters, apply the gradients,
+// compress, discard).  The weight gradient dW = X^T dY is formed on the matrix cores and consumed in
+// the epilogue of the same kernel: the tile's codes are read, decoded and transformed (Sec. 2.2,
+// 2.3), updated with the accumulators as gradient, rounded and written back, and the sums of the fit
+// are taken on the way.  The fp32 gradient never exists in memory (unless the caller asks for a copy).
+//
+// Tiling.  Workgroup = 4 waves, tile of W = 256 rows (k) x 128 columns (n), contraction over the M rows of
+// X and dY in steps of 32.  Both operands are contraction-strided in memory, so threads load 4 x 4
+// patches (four rows of 8 bytes), transpose them in registers and store 8-byte runs of four
+// consecutive m to LDS, laid out as in the forward GEMM: [m-chunk of 8][row or column][16 bytes].
+// Tile row r = 64 i + q stands for weight row 4 q + i, so that the stores of neighbouring threads are
+// neighbours in LDS (the order of the rows of a tile is free); tile column slot 32 i + q stands for
+// column 4 q + i, so that a lane ends up with four adjacent columns of a row: one dword of 8-bit codes.
+#include "omc_stream.h"
+
+namespace omc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kDwCols = 128, kDwStep = 32;
+constexpr int kDwBChunk = kDwCols * 16;
+
+struct DwArgs {
+    const uint16_t *X, *dY;
+    uint32_t *codes;
+    const float *sb;
+    float *st0, *st1;
+    float *dW_out;
+    Partial *ws;
+    FmtParams fp;
+    OptConst oc;
+    uint32_t M, N, K;
+};
+
+__device__ __forceinline__ uint32_t dw_a_slot(uint32_t row, uint32_t chunk) { return row ^ (2u * chunk); }
+
+// ROWS = weight rows per tile (256 or 128); a wave owns ROWS / 4 tile rows = MI 32-row MFMA tiles.
+template <int ROWS, int MODE, bool WIDE>
+__device__ __forceinline__ void dw_epilogue(const DwArgs &a, const f32x16 (&acc)[ROWS / 128][4], uint32_t k0t, uint32_t n0,
+                                            uint32_t lane, uint32_t wave, FitAcc &fit) {
+    constexpr int MI = ROWS / 128;
+    const uint32_t f_row = lane & 31u, f_half = lane >> 5;
+    const float s = a.sb ? to_scalar_regs(a.sb[0]) : 1.0f;
+    const float b = a.sb ? to_scalar_regs(a.sb[1]) : 0.0f;
+    const FmtParams fp = a.fp;
+    bool seeded = false;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            // four weight rows at a time: their code dwords (and state) are fetched together
+            uint32_t cw[4];
+            f32x4 m4[4], v4[4];
+            uint64_t e[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t q = 32 * mi + 8 * g + 4 * f_half + j;      // tile row (ROWS / 4) wave + q  ->  weight row 4 q + wave
+                const uint32_t k = k0t + 4 * q + wave;
+                e[j] = static_cast<uint64_t>(k) * a.N + n0 + 4 * f_row;
+                cw[j] = a.codes[e[j] >> 2];
+                if (MODE >= kStepMomentum) m4[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.st0 + e[j]));
+                if (MODE == kStepAdam) v4[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.st1 + e[j]));
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int v = 4 * g + j;
+                pin(cw[j]);
+                uint32_t out = 0;
+                f32x4 grad;
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni) {
+                    const float gr = acc[mi][ni][v];
+                    grad[ni] = gr;
+                    const float vt = decode_top(cw[j] << (24 - 8 * ni), fp);
+                    const float sv = s * vt;
+                    float x = sv + b;
+                    float mm = MODE >= kStepMomentum ? m4[j][ni] : 0.0f, vv = MODE == kStepAdam ? v4[j][ni] : 0.0f;
+                    x = apply_update<MODE>(x, gr, mm, vv, a.oc);
+                    if (MODE >= kStepMomentum) m4[j][ni] = mm;
+                    if (MODE == kStepAdam) v4[j][ni] = vv;
+                    uint32_t code;
+                    float tq;
+                    encode<WIDE>(x, fp, code, tq);
+                    if (!seeded) { fit.seed(tq); seeded = true; }
+                    fit.add(x, tq);
+                    out |= code << (8 * ni);
+                }
+                // keep the rows in program order: without this the compiler hoists the arithmetic of all
+                // 128 elements above the serial fp64 accumulation and runs out of registers
+                pin(fit.sV); pin(fit.sT); pin(fit.sVT); pin(fit.sTT); pin(fit.diff); pin(out);
+                a.codes[e[j] >> 2] = out;
+                if (MODE >= kStepMomentum) __builtin_nontemporal_store(m4[j], reinterpret_cast<f32x4 *>(a.st0 + e[j]));
+                if (MODE == kStepAdam) __builtin_nontemporal_store(v4[j], reinterpret_cast<f32x4 *>(a.st1 + e[j]));
+                if (a.dW_out) __builtin_nontemporal_store(grad, reinterpret_cast<f32x4 *>(a.dW_out + e[j]));
+            }
+        }
+    }
+}
+
+template <int ROWS, int MODE>
+__global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwArgs a) {
+    constexpr int MI = ROWS / 128;                        // 32-row MFMA tiles per wave
+    constexpr int XP = ROWS / 128;                        // 4 x 4 patches of X per thread and step
+    constexpr int QN = ROWS / 4;                          // groups of four weight rows in a tile
+    constexpr int kDwAChunk = ROWS * 16;
+    constexpr int kDwStageBytes = 4 * kDwAChunk + 4 * kDwBChunk;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kDwStageBytes];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t k0t = blockIdx.x * ROWS, n0 = blockIdx.y * kDwCols;
+    const uint32_t K = a.K, N = a.N;
+
+    // ---- roles in the loads: X patches p = 0, 1 (k group kq of 4 columns, m group mg of 4 rows), one dY patch
+    struct Regs {
+        u32x2 x[XP][4];
+        u32x2 y[4];
+    };
+    Regs r;
+    const uint32_t y_nq = tid & 31u, y_mg = tid >> 5;
+    auto load_stage = [&](uint32_t m0) {
+#pragma unroll
+        for (int p = 0; p < XP; ++p) {
+            const uint32_t idx = tid + 256 * p, kq = idx % QN, mg = idx / QN;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+                r.x[p][rr] = *reinterpret_cast<const u32x2 *>(a.X + static_cast<uint64_t>(m0 + 4 * mg + rr) * K + k0t + 4 * kq);
+        }
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            r.y[rr] = *reinterpret_cast<const u32x2 *>(a.dY + static_cast<uint64_t>(m0 + 4 * y_mg + rr) * N + n0 + 4 * y_nq);
+    };
+    // column i of a 4 x 4 patch of bf16 (rows = consecutive m): the four values as 8 bytes
+    auto patch_column = [&](const u32x2 (&rows)[4], int i) -> u32x2 {
+        const int d = i >> 1;
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        u32x2 out;
+        out[0] = __builtin_amdgcn_perm(rows[1][d], rows[0][d], sel);
+        out[1] = __builtin_amdgcn_perm(rows[3][d], rows[2][d], sel);
+        return out;
+    };
+    auto store_stage = [&](uint8_t *ldsA) {
+        uint8_t *ldsB = ldsA + 4 * kDwAChunk;
+#pragma unroll
+        for (int p = 0; p < XP; ++p) {
+            const uint32_t idx = tid + 256 * p, kq = idx % QN, mg = idx / QN;
+            const uint32_t chunk = mg >> 1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t row = QN * i + kq;
+                *reinterpret_cast<u32x2 *>(ldsA + chunk * kDwAChunk + (dw_a_slot(row, chunk) << 4) + 8u * (mg & 1u)) =
+                    patch_column(r.x[p], i);
+            }
+        }
+        const uint32_t chunk = y_mg >> 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<u32x2 *>(ldsB + chunk * kDwBChunk + ((32u * i + y_nq) << 4) + 8u * (y_mg & 1u)) =
+                patch_column(r.y, i);
+    };
+
+    f32x16 acc[MI][4];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+    const uint32_t f_row = lane & 31u, f_half = lane >> 5;
+    auto multiply_stage = [&](const uint8_t *ldsA) {
+        const uint8_t *ldsB = ldsA + 4 * kDwAChunk;
+        bf16x8 fa[2][MI], fb[2][4];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const uint32_t chunk = 2 * ks + f_half;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const uint32_t row = QN * wave + 32 * mi + f_row;
+                fa[ks][mi] = *reinterpret_cast<const bf16x8 *>(ldsA + chunk * kDwAChunk + (dw_a_slot(row, chunk) << 4));
+            }
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                fb[ks][ni] = *reinterpret_cast<const bf16x8 *>(ldsB + chunk * kDwBChunk + ((32u * ni + f_row) << 4));
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][mi], fb[ks][ni], acc[mi][ni], 0, 0, 0);
+    };
+
+    // the loads of step ms + 2 are issued right after the barrier that ends round ms
+    const uint32_t nm = a.M / kDwStep;
+    load_stage(0);
+    store_stage(lds);
+    __syncthreads();
+    if (nm > 1) load_stage(kDwStep);
+    uint32_t ms = 0;
+    for (; ms + 2 < nm; ++ms) {
+        const uint32_t cur = (ms & 1u) * kDwStageBytes;
+        multiply_stage(lds + cur);
+        store_stage(lds + (kDwStageBytes - cur));
+        __syncthreads();
+        load_stage((ms + 2) * kDwStep);
+    }
+    for (; ms < nm; ++ms) {
+        const uint32_t cur = (ms & 1u) * kDwStageBytes;
+        multiply_stage(lds + cur);
+        if (ms + 1 < nm) {
+            store_stage(lds + (kDwStageBytes - cur));
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: decompress, update, recompress the tile's weights; sums of the fit ----------------
+    FitAcc fit;
+    fit.clear();
+    if (a.fp.wide) dw_epilogue<ROWS, MODE, true>(a, acc, k0t, n0, lane, wave, fit);
+    else dw_epilogue<ROWS, MODE, false>(a, acc, k0t, n0, lane, wave, fit);
+    // one partial per wave (the butterfly leaves the wave's totals in every lane; lane 0 stores them)
+    const uint32_t block = blockIdx.y * gridDim.x + blockIdx.x;
+    Partial *slot = a.ws + 4 * static_cast<uint64_t>(block) + wave;
+    {
+        float tmin, tmax;
+        fit.lane_range(tmin, tmax);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            fit.sV += __shfl_xor(fit.sV, off);
+            fit.sT += __shfl_xor(fit.sT, off);
+            fit.sVT += __shfl_xor(fit.sVT, off);
+            fit.sTT += __shfl_xor(fit.sTT, off);
+            tmin = fminf(tmin, __shfl_xor(tmin, off));
+            tmax = fmaxf(tmax, __shfl_xor(tmax, off));
+        }
+        if (lane == 0) {
+            Partial p;
+            p.sV = fit.sV; p.sT = fit.sT; p.sVT = fit.sVT; p.sTT = fit.sTT;
+            p.tmin = tmin; p.tmax = tmax; p.pad[0] = p.pad[1] = 0;
+            *slot = p;
+        }
+    }
+}
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void dw_finalize_kernel(const Partial *__restrict__ ws, uint32_t nparts, uint64_t n,
+                                                              int use_pvt, float *__restrict__ sb) {
+    __shared__ double red[NW * 10];
+    finalize_variable<NW>(ws, nparts, nullptr, n, use_pvt != 0, sb, red);
+}
+
+int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const FmtParams &fp, float *sb, int use_pvt,
+                     float *state0, float *state1, const omc_opt &opt, float *dW_out, uint32_t M, uint32_t N,
+                     uint32_t K, Partial *ws, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    DwArgs a{};
+    a.X = X;
+    a.dY = dY;
+    a.codes = static_cast<uint32_t *>(codes);
+    a.sb = sb;
+    a.st0 = opt.kind >= OMC_MOMENTUM ? state0 : nullptr;
+    a.st1 = opt.kind == OMC_ADAM ? state1 : nullptr;
+    a.dW_out = dW_out;
+    a.ws = ws;
+    a.fp = fp;
+    a.oc = OptConst{opt.lr, opt.momentum, opt.beta1, opt.beta2, opt.eps, opt.one_minus_beta1,
+                    opt.one_minus_beta2, opt.bias_corr1, opt.bias_corr2};
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    // 256-row tiles unless they would leave fewer than two workgroups per compute unit
+    const bool small = static_cast<uint64_t>(K / 256) * (N / kDwCols) < 512;
+    const dim3 grid(small ? K / 128 : K / 256, N / kDwCols);
+#define OMC_DW_LAUNCH(ROWS)                                                                      \
+    do {                                                                                         \
+        if (opt.kind == OMC_SGD) dw_update_kernel<ROWS, kStepSgd><<<grid, dim3(256), 0, st>>>(a); \
+        else if (opt.kind == OMC_MOMENTUM) dw_update_kernel<ROWS, kStepMomentum><<<grid, dim3(256), 0, st>>>(a); \
+        else dw_update_kernel<ROWS, kStepAdam><<<grid, dim3(256), 0, st>>>(a);                    \
+    } while (0)
+    if (small) OMC_DW_LAUNCH(128);
+    else OMC_DW_LAUNCH(256);
+#undef OMC_DW_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return static_cast<int>(e);
+    const uint32_t nparts = 4u * grid.x * grid.y;
+    const uint64_t n = static_cast<uint64_t>(K) * N;
+    if (nparts <= 256) dw_finalize_kernel<1><<<dim3(1), dim3(64), 0, st>>>(ws, nparts, n, use_pvt, sb);
+    else dw_finalize_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nparts, n, use_pvt, sb);
+    return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace omc

@@ -83,6 +83,9 @@ _agg_mean = _sig("omc_aggregate_mean", C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.
 _gemm_ws = _sig("omc_dequant_gemm_workspace_bytes", C.c_size_t, C.c_uint32)
 _gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
              C.c_uint32, _vp, C.c_size_t, _vp)
+_dw_ws = _sig("omc_dw_update_workspace_bytes", C.c_size_t, C.c_uint32, C.c_uint32)
+_dw = _sig("omc_dw_update_recompress", C.c_int, _vp, _vp, _vp, omc_format, _vp, C.c_int, _vp, _vp, C.POINTER(omc_opt), _vp,
+           C.c_uint32, C.c_uint32, C.c_uint32, _vp, C.c_size_t, _vp)
 _gemm_dx = _sig("omc_dequant_gemm_dx", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
                 C.c_uint32, _vp, C.c_size_t, _vp)
 
@@ -93,7 +96,8 @@ EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_
             "omc_step_update_recompress_events", "omc_compress_set", "omc_decompress_set",
             "omc_plan_transport_bytes", "omc_aggregate_plan_bytes", "omc_aggregate_plan_build",
             "omc_aggregate_mean", "omc_dequant_gemm_workspace_bytes",
-            "omc_dequant_gemm", "omc_dequant_gemm_dx"]
+            "omc_dequant_gemm", "omc_dequant_gemm_dx", "omc_dw_update_workspace_bytes",
+            "omc_dw_update_recompress"]
 
 
 class OmcError(RuntimeError):
@@ -290,6 +294,18 @@ def omc_dequant_gemm_dx(dY: torch.Tensor, codes: torch.Tensor, f: omc_format, sb
                         dX: torch.Tensor, M: int, N: int, K: int, ws: torch.Tensor, stream=None) -> None:
     _check(_gemm_dx(_ptr(dY), _ptr(codes), f, _ptr(sb), _ptr(dX), M, N, K, _ptr(ws),
                     ws.numel() * ws.element_size(), _stream(stream)), "omc_dequant_gemm_dx")
+
+
+def omc_dw_update_workspace_bytes(N: int, K: int) -> int:
+    return _dw_ws(N, K)
+
+
+def omc_dw_update_recompress(X: torch.Tensor, dY: torch.Tensor, codes: torch.Tensor, f: omc_format, sb: torch.Tensor,
+                             use_pvt: bool, state0: Optional[torch.Tensor], state1: Optional[torch.Tensor], o: omc_opt,
+                             dW_out: Optional[torch.Tensor], M: int, N: int, K: int, ws: torch.Tensor, stream=None) -> None:
+    _check(_dw(_ptr(X), _ptr(dY), _ptr(codes), f, _ptr(sb), int(use_pvt), _ptr(state0), _ptr(state1), C.byref(o),
+               _ptr(dW_out), M, N, K, _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+           "omc_dw_update_recompress")
 
 
 # --------------------------------------------------------------------------- server aggregation

@@ -237,3 +237,19 @@ def test_aggregate_plan_checks_that_the_clients_plans_fit_together():
     assert omc._agg_mean(buf.ctypes.data, A, arenas, sizes, sbs, out + 4, 1 << 20, None) == 4
     broken = buf.copy(); broken[4] ^= 1
     assert omc._agg_mean(broken.ctypes.data, A, arenas, sizes, sbs, out, 1 << 20, None) == 8
+
+
+def test_dw_update_rejects_bad_arguments():
+    f = omc.fmt(4, 3)
+    A = 0x100000
+    o = omc.opt(omc.OMC_SGD, 0.1)
+    def call(X=A, dY=A, codes=A, fm=f, sb=A, st0=None, st1=None, opt=o, M=64, N=128, K=256, ws=A, wsb=1 << 20):
+        return omc._dw(X, dY, codes, fm, sb, 1, st0, st1, omc.C.byref(opt), None, M, N, K, ws, wsb, None)
+    assert omc.omc_dw_update_workspace_bytes(128, 256) == 2 * 4 * 48
+    assert omc.omc_dw_update_workspace_bytes(100, 256) == 0
+    assert call(X=None) == 1
+    assert call(fm=omc.fmt(3, 7)) == 2                   # not an 8-bit format
+    assert call(M=48) == 3 and call(N=64) == 3 and call(K=128) == 3
+    assert call(opt=omc.opt(omc.OMC_ADAM, 0.1), st0=A) == 6
+    assert call(codes=A + 4) == 4
+    assert call(wsb=16) == 5

@@ -1,0 +1,71 @@
+"""GPU parity of the fused backward step of a linear layer (weight gradient on the matrix cores,
+consumed by the update in the same kernel).  Two-stage check, because the gradient is a long fp32
+accumulation while the update decides integer codes:
+  1. the gradient the kernel used (dW_out) against the oracle's fp64 X^T dY, to the GEMM tolerance;
+  2. codes, (s, b) and optimizer state against the oracle's step fed with exactly that gradient: bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import omc_oracle as orc
+from paper_2205_03494_amd import omc, synth
+from gpu_util import bits_equal, pair, to_dev
+from test_gpu_gemm import check
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(EM, M, N, K, kind, lr, use_pvt=True, steps=2, grad_scale=1.0, want_dw=True, rows=None):
+    of, gf = pair(*EM)
+    n = K * N
+    W = synth.normal_f32(n, 0.05, 2)
+    packed, sb = orc.compress(W, of, use_pvt=use_pvt)
+    st0 = np.zeros(n, np.float32) if kind >= 1 else None
+    st1 = np.zeros(n, np.float32) if kind == 2 else None
+    codes_d, sb_d = to_dev(packed), to_dev(sb)
+    st0_d = None if st0 is None else to_dev(st0)
+    st1_d = None if st1 is None else to_dev(st1)
+    ws = torch.empty(omc.omc_dw_update_workspace_bytes(N, K), dtype=torch.uint8, device="cuda")
+    dW_d = torch.full((K, N), float("nan"), device="cuda") if want_dw else None
+    for t in range(1, steps + 1):
+        X = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 10 + t))
+        dY = synth.to_bf16_bits(synth.normal_f32(M * N, grad_scale / M, 20 + t))
+        omc.omc_dw_update_recompress(to_dev(X), to_dev(dY), codes_d, gf, sb_d, use_pvt, st0_d, st1_d,
+                                     omc.opt(kind, lr, t=t), dW_d, M, N, K, ws)
+        torch.cuda.synchronize()
+        g = dW_d.cpu().numpy()
+        assert np.all(np.isfinite(g))
+        if rows is None:
+            check(g, orc.gemm_dw(X, dY, M, N, K, threads=8), (0, K))
+        else:
+            for r0 in rows:
+                check(g, orc.gemm_dw(X, dY, M, N, K, rows=(r0, r0 + 16), threads=8), (r0, r0 + 16))
+        orc.step_quantized(packed, n, of, sb, g.ravel(), st0, st1, orc.Opt(kind=kind, lr=lr, t=t), use_pvt=use_pvt)
+        assert np.array_equal(codes_d.cpu().numpy(), packed), f"codes differ at step {t}"
+        assert bits_equal(sb_d.cpu().numpy(), sb), (sb_d.cpu().numpy(), sb)
+        if st0 is not None:
+            assert bits_equal(st0_d.cpu().numpy(), st0)
+        if st1 is not None:
+            assert bits_equal(st1_d.cpu().numpy(), st1)
+
+
+@pytest.mark.parametrize("kind,lr", [(0, 0.05), (1, 0.05), (2, 1e-3)])
+@pytest.mark.parametrize("EM", [(4, 3), (5, 2), (3, 4), (4, 3, 4)])
+def test_small_shapes(EM, kind, lr):
+    run_case(EM, 96, 128, 256, kind, lr)
+
+
+@pytest.mark.parametrize("shape", [(32, 128, 256), (160, 256, 512), (64, 384, 256)])
+def test_tile_grid_and_minimal_contraction(shape):
+    M, N, K = shape
+    run_case((4, 3), M, N, K, 0, 0.05)
+
+
+def test_without_the_transformation_and_with_saturating_updates():
+    run_case((4, 3), 64, 128, 256, 0, 0.05, use_pvt=False)
+    run_case((2, 5), 64, 128, 256, 0, 50.0, grad_scale=100.0)      # most weights end at the format's limits
+
+
+def test_config5_layer_sampled_gradient_rows():
+    # the feed-forward layer of the benchmark shape: X [8192 x 1024], W [1024 x 4096]
+    run_case((4, 3), 8192, 4096, 1024, 0, 0.01, steps=1, rows=(0, 500, 1008))
