@@ -30,6 +30,8 @@ struct DwArgs {
     float *st0, *st1;
     float *dW_out;
     Partial *ws;
+    float *partials;         // split contraction: [tile][split][ROWS * 128] accumulators
+    uint32_t nsplit;         // workgroups per tile along the contraction (gridDim.z)
     FmtParams fp;
     OptConst oc;
     uint32_t M, N, K;
@@ -100,6 +102,35 @@ __device__ __forceinline__ void dw_epilogue(const DwArgs &a, const f32x16 (&acc)
     }
 }
 
+// A wave's share of a finished tile: the epilogue and the wave's partial sums of the fit.
+template <int ROWS, int MODE>
+__device__ __forceinline__ void dw_finish_wave(const DwArgs &a, const f32x16 (&acc)[ROWS / 128][4], uint32_t k0t,
+                                               uint32_t n0, uint32_t lane, uint32_t wave, uint32_t block) {
+    FitAcc fit;
+    fit.clear();
+    if (a.fp.wide) dw_epilogue<ROWS, MODE, true>(a, acc, k0t, n0, lane, wave, fit);
+    else dw_epilogue<ROWS, MODE, false>(a, acc, k0t, n0, lane, wave, fit);
+    // the butterfly leaves the wave's totals in every lane; lane 0 stores them
+    Partial *slot = a.ws + 4 * static_cast<uint64_t>(block) + wave;
+    float tmin, tmax;
+    fit.lane_range(tmin, tmax);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        fit.sV += __shfl_xor(fit.sV, off);
+        fit.sT += __shfl_xor(fit.sT, off);
+        fit.sVT += __shfl_xor(fit.sVT, off);
+        fit.sTT += __shfl_xor(fit.sTT, off);
+        tmin = fminf(tmin, __shfl_xor(tmin, off));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, off));
+    }
+    if (lane == 0) {
+        Partial p;
+        p.sV = fit.sV; p.sT = fit.sT; p.sVT = fit.sVT; p.sTT = fit.sTT;
+        p.tmin = tmin; p.tmax = tmax; p.pad[0] = p.pad[1] = 0;
+        *slot = p;
+    }
+}
+
 template <int ROWS, int MODE>
 __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwArgs a) {
     constexpr int MI = ROWS / 128;                        // 32-row MFMA tiles per wave
@@ -112,7 +143,8 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
     const uint32_t k0t = blockIdx.x * ROWS, n0 = blockIdx.y * kDwCols;
     const uint32_t K = a.K, N = a.N;
 
-    // ---- roles in the loads: X patches p = 0, 1 (k group kq of 4 columns, m group mg of 4 rows), one dY patch
+    // ---- roles in the loads: X patches (k group kq of 4 columns, m group mg of 4 rows; neighbouring threads
+    // take the two halves of an m-chunk, so that their 8-byte LDS stores are adjacent), one dY patch
     struct Regs {
         u32x2 x[XP][4];
         u32x2 y[4];
@@ -122,7 +154,7 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
     auto load_stage = [&](uint32_t m0) {
 #pragma unroll
         for (int p = 0; p < XP; ++p) {
-            const uint32_t idx = tid + 256 * p, kq = idx % QN, mg = idx / QN;
+            const uint32_t idx = tid + 256 * p, kq = (idx >> 1) % QN, mg = 2 * ((idx >> 1) / QN) + (idx & 1u);
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr)
                 r.x[p][rr] = *reinterpret_cast<const u32x2 *>(a.X + static_cast<uint64_t>(m0 + 4 * mg + rr) * K + k0t + 4 * kq);
@@ -144,7 +176,7 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
         uint8_t *ldsB = ldsA + 4 * kDwAChunk;
 #pragma unroll
         for (int p = 0; p < XP; ++p) {
-            const uint32_t idx = tid + 256 * p, kq = idx % QN, mg = idx / QN;
+            const uint32_t idx = tid + 256 * p, kq = (idx >> 1) % QN, mg = 2 * ((idx >> 1) / QN) + (idx & 1u);
             const uint32_t chunk = mg >> 1;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -194,18 +226,20 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
     };
 
     // the loads of step ms + 2 are issued right after the barrier that ends round ms
-    const uint32_t nm = a.M / kDwStep;
-    load_stage(0);
+    // this workgroup's share of the contraction: rows [m_begin, m_begin + nm * 32) of X and dY
+    const uint32_t nm = a.M / kDwStep / a.nsplit;
+    const uint32_t m_begin = blockIdx.z * nm * kDwStep;
+    load_stage(m_begin);
     store_stage(lds);
     __syncthreads();
-    if (nm > 1) load_stage(kDwStep);
+    if (nm > 1) load_stage(m_begin + kDwStep);
     uint32_t ms = 0;
     for (; ms + 2 < nm; ++ms) {
         const uint32_t cur = (ms & 1u) * kDwStageBytes;
         multiply_stage(lds + cur);
         store_stage(lds + (kDwStageBytes - cur));
         __syncthreads();
-        load_stage((ms + 2) * kDwStep);
+        load_stage(m_begin + (ms + 2) * kDwStep);
     }
     for (; ms < nm; ++ms) {
         const uint32_t cur = (ms & 1u) * kDwStageBytes;
@@ -216,33 +250,47 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
         }
     }
 
-    // ---- epilogue: decompress, update, recompress the tile's weights; sums of the fit ----------------
-    FitAcc fit;
-    fit.clear();
-    if (a.fp.wide) dw_epilogue<ROWS, MODE, true>(a, acc, k0t, n0, lane, wave, fit);
-    else dw_epilogue<ROWS, MODE, false>(a, acc, k0t, n0, lane, wave, fit);
-    // one partial per wave (the butterfly leaves the wave's totals in every lane; lane 0 stores them)
-    const uint32_t block = blockIdx.y * gridDim.x + blockIdx.x;
-    Partial *slot = a.ws + 4 * static_cast<uint64_t>(block) + wave;
-    {
-        float tmin, tmax;
-        fit.lane_range(tmin, tmax);
+    const uint32_t block = blockIdx.y * gridDim.x + blockIdx.x;     // tile index
+    // ---- split contraction: park the partial accumulators (accumulator layout, 16 bytes per lane and
+    // row); dw_reduce_update_kernel adds them up in split order and does the rest
+    if (a.nsplit > 1) {
+        constexpr uint32_t kTileFloats = ROWS * kDwCols;
+        float *mine = a.partials + (static_cast<uint64_t>(block) * a.nsplit + blockIdx.z) * kTileFloats;
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            fit.sV += __shfl_xor(fit.sV, off);
-            fit.sT += __shfl_xor(fit.sT, off);
-            fit.sVT += __shfl_xor(fit.sVT, off);
-            fit.sTT += __shfl_xor(fit.sTT, off);
-            tmin = fminf(tmin, __shfl_xor(tmin, off));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, off));
-        }
-        if (lane == 0) {
-            Partial p;
-            p.sV = fit.sV; p.sT = fit.sT; p.sVT = fit.sVT; p.sTT = fit.sTT;
-            p.tmin = tmin; p.tmax = tmax; p.pad[0] = p.pad[1] = 0;
-            *slot = p;
-        }
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                __builtin_nontemporal_store(f32x4{acc[mi][0][v], acc[mi][1][v], acc[mi][2][v], acc[mi][3][v]},
+                                            reinterpret_cast<f32x4 *>(mine) + ((mi * 16 + v) * 256 + tid));
+        return;
     }
+
+    dw_finish_wave<ROWS, MODE>(a, acc, k0t, n0, lane, wave, block);
+}
+
+// Second kernel of the split contraction: one wave per (tile, wave of the first kernel).  Sums the
+// tile's partial accumulators in split order, so the gradient does not depend on scheduling, then
+// the same epilogue.
+template <int ROWS, int MODE>
+__global__ __launch_bounds__(64, 2) void dw_reduce_update_kernel(DwArgs a, uint32_t tiles_x) {
+    constexpr int MI = ROWS / 128;
+    constexpr uint32_t kTileFloats = ROWS * kDwCols;
+    const uint32_t lane = threadIdx.x, wave = blockIdx.x & 3u, block = blockIdx.x >> 2;
+    const uint32_t k0t = (block % tiles_x) * ROWS, n0 = (block / tiles_x) * kDwCols;
+    const float *all = a.partials + static_cast<uint64_t>(block) * a.nsplit * kTileFloats;
+    f32x16 acc[MI][4];
+    for (uint32_t sp = 0; sp < a.nsplit; ++sp) {
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(all + static_cast<uint64_t>(sp) * kTileFloats);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const f32x4 t = __builtin_nontemporal_load(src + ((mi * 16 + v) * 256 + wave * 64 + lane));
+#pragma unroll
+                for (int ni = 0; ni < 4; ++ni) acc[mi][ni][v] = (sp == 0) ? t[ni] : acc[mi][ni][v] + t[ni];
+            }
+    }
+    dw_finish_wave<ROWS, MODE>(a, acc, k0t, n0, lane, wave, block);
 }
 
 template <int NW>
@@ -252,10 +300,34 @@ __global__ __launch_bounds__(64 * NW) void dw_finalize_kernel(const Partial *__r
     finalize_variable<NW>(ws, nparts, nullptr, n, use_pvt != 0, sb, red);
 }
 
+// Tile height and number of contraction splits for a problem size: 256-row tiles and no split when
+// that already gives two workgroups per compute unit; otherwise split the M rows (each split at least
+// 512 rows, at most 8 splits) and, if that is still not enough, take 128-row tiles.
+DwConfig dw_config(uint32_t M, uint32_t N, uint32_t K) {
+    DwConfig c{256, 1};
+    const uint64_t tiles256 = static_cast<uint64_t>(K / 256) * (N / kDwCols);
+    auto splits_for = [&](uint64_t tiles) {
+        uint32_t sp = 1;
+        while (tiles * sp < 512 && sp < 8 && M % (2 * sp * kDwStep) == 0 && M / (2 * sp) >= 512) sp *= 2;
+        return sp;
+    };
+    c.nsplit = splits_for(tiles256);
+    if (tiles256 * c.nsplit < 512) {
+        c.rows = 128;
+        c.nsplit = splits_for(2 * tiles256);
+    }
+    return c;
+}
+
 int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const FmtParams &fp, float *sb, int use_pvt,
                      float *state0, float *state1, const omc_opt &opt, float *dW_out, uint32_t M, uint32_t N,
-                     uint32_t K, Partial *ws, void *stream) {
+                     uint32_t K, void *ws, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const DwConfig cfg = dw_config(M, N, K);
+    const uint32_t tiles = (K / cfg.rows) * (N / kDwCols);
+    // workspace: one fit partial per wave and tile | partial accumulators
+    uint8_t *w8 = static_cast<uint8_t *>(ws);
+    const size_t fit_bytes = (static_cast<size_t>(4) * (K / 128) * (N / kDwCols) * sizeof(Partial) + 255) / 256 * 256;
     DwArgs a{};
     a.X = X;
     a.dY = dY;
@@ -264,32 +336,54 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
     a.st0 = opt.kind >= OMC_MOMENTUM ? state0 : nullptr;
     a.st1 = opt.kind == OMC_ADAM ? state1 : nullptr;
     a.dW_out = dW_out;
-    a.ws = ws;
+    a.ws = reinterpret_cast<Partial *>(w8);
+    a.partials = reinterpret_cast<float *>(w8 + fit_bytes);
+    a.nsplit = cfg.nsplit;
     a.fp = fp;
     a.oc = OptConst{opt.lr, opt.momentum, opt.beta1, opt.beta2, opt.eps, opt.one_minus_beta1,
                     opt.one_minus_beta2, opt.bias_corr1, opt.bias_corr2};
     a.M = M;
     a.N = N;
     a.K = K;
-    // 256-row tiles unless they would leave fewer than two workgroups per compute unit
-    const bool small = static_cast<uint64_t>(K / 256) * (N / kDwCols) < 512;
-    const dim3 grid(small ? K / 128 : K / 256, N / kDwCols);
+    const dim3 grid(K / cfg.rows, N / kDwCols, cfg.nsplit);
 #define OMC_DW_LAUNCH(ROWS)                                                                      \
     do {                                                                                         \
         if (opt.kind == OMC_SGD) dw_update_kernel<ROWS, kStepSgd><<<grid, dim3(256), 0, st>>>(a); \
         else if (opt.kind == OMC_MOMENTUM) dw_update_kernel<ROWS, kStepMomentum><<<grid, dim3(256), 0, st>>>(a); \
         else dw_update_kernel<ROWS, kStepAdam><<<grid, dim3(256), 0, st>>>(a);                    \
     } while (0)
-    if (small) OMC_DW_LAUNCH(128);
+    if (cfg.rows == 128) OMC_DW_LAUNCH(128);
     else OMC_DW_LAUNCH(256);
 #undef OMC_DW_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return static_cast<int>(e);
-    const uint32_t nparts = 4u * grid.x * grid.y;
+    if (cfg.nsplit > 1) {
+        const dim3 grid2(4 * tiles);
+        const uint32_t tx = K / cfg.rows;
+#define OMC_DW_LAUNCH2(ROWS)                                                                                  \
+    do {                                                                                                      \
+        if (opt.kind == OMC_SGD) dw_reduce_update_kernel<ROWS, kStepSgd><<<grid2, dim3(64), 0, st>>>(a, tx);  \
+        else if (opt.kind == OMC_MOMENTUM) dw_reduce_update_kernel<ROWS, kStepMomentum><<<grid2, dim3(64), 0, st>>>(a, tx); \
+        else dw_reduce_update_kernel<ROWS, kStepAdam><<<grid2, dim3(64), 0, st>>>(a, tx);                     \
+    } while (0)
+        if (cfg.rows == 128) OMC_DW_LAUNCH2(128);
+        else OMC_DW_LAUNCH2(256);
+#undef OMC_DW_LAUNCH2
+        e = hipGetLastError();
+        if (e != hipSuccess) return static_cast<int>(e);
+    }
+    const uint32_t nparts = 4u * tiles;
     const uint64_t n = static_cast<uint64_t>(K) * N;
-    if (nparts <= 256) dw_finalize_kernel<1><<<dim3(1), dim3(64), 0, st>>>(ws, nparts, n, use_pvt, sb);
-    else dw_finalize_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nparts, n, use_pvt, sb);
+    if (nparts <= 256) dw_finalize_kernel<1><<<dim3(1), dim3(64), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
+    else dw_finalize_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
     return static_cast<int>(hipGetLastError());
+}
+
+size_t dw_workspace_bytes(uint32_t M, uint32_t N, uint32_t K) {
+    const DwConfig cfg = dw_config(M, N, K);
+    const size_t fit_bytes = (static_cast<size_t>(4) * (K / 128) * (N / kDwCols) * sizeof(Partial) + 255) / 256 * 256;
+    const size_t partial_bytes = cfg.nsplit > 1 ? static_cast<size_t>(cfg.nsplit) * K * N * sizeof(float) : 0;
+    return fit_bytes + partial_bytes;
 }
 
 }  // namespace omc

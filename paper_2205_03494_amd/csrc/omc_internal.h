@@ -139,9 +139,15 @@ int launch_decompress_set(const void *arena, const PlanHeader *ph, const void *p
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table,
                 const float *grads, float *state0, float *state1, const omc_opt &opt, Partial *ws,
                 void *stream, void *const *events);
+struct DwConfig {
+    uint32_t rows;     // weight rows per tile: 256 or 128
+    uint32_t nsplit;   // workgroups per tile along the contraction
+};
+DwConfig dw_config(uint32_t M, uint32_t N, uint32_t K);
+size_t dw_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
 int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const FmtParams &fp, float *sb, int use_pvt,
                      float *state0, float *state1, const omc_opt &opt, float *dW_out, uint32_t M, uint32_t N,
-                     uint32_t K, Partial *ws, void *stream);
+                     uint32_t K, void *ws, void *stream);
 struct AggPointers {
     const uint8_t *arena[kMaxReplicas];
     const float *sb[kMaxReplicas];

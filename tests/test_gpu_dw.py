@@ -25,7 +25,7 @@ def run_case(EM, M, N, K, kind, lr, use_pvt=True, steps=2, grad_scale=1.0, want_
     codes_d, sb_d = to_dev(packed), to_dev(sb)
     st0_d = None if st0 is None else to_dev(st0)
     st1_d = None if st1 is None else to_dev(st1)
-    ws = torch.empty(omc.omc_dw_update_workspace_bytes(N, K), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(omc.omc_dw_update_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
     dW_d = torch.full((K, N), float("nan"), device="cuda") if want_dw else None
     for t in range(1, steps + 1):
         X = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 10 + t))
@@ -59,6 +59,15 @@ def test_small_shapes(EM, kind, lr):
 def test_tile_grid_and_minimal_contraction(shape):
     M, N, K = shape
     run_case((4, 3), M, N, K, 0, 0.05)
+
+
+@pytest.mark.parametrize("M,kind,lr", [(1024, 0, 0.05), (4096, 1, 0.05), (2048, 2, 1e-3)])
+def test_contraction_split_between_workgroups(M, kind, lr):
+    """Few tiles and many rows: the M rows are shared out between workgroups and the last one to arrive at a
+    tile sums the partial accumulators in a fixed order; two runs must agree bit for bit with each other
+    (run_case compares the second step too) and with the oracle's step on the gradient that was used."""
+    run_case((4, 3), M, 128, 256, kind, lr, steps=2)
+    run_case((4, 3), M, 256, 512, kind, lr, steps=1)
 
 
 def test_without_the_transformation_and_with_saturating_updates():
