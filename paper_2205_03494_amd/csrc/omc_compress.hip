@@ -66,6 +66,8 @@ int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes,
     // the width of the reduction depends on the size alone, so results do not depend on the run
     if (nchunks <= 256)
         finalize_single_kernel<1><<<dim3(1), dim3(64), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
+    else if (nchunks <= 2048)
+        finalize_single_kernel<4><<<dim3(1), dim3(256), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
     else
         finalize_single_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
     return static_cast<int>(hipGetLastError());

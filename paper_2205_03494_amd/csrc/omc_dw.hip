@@ -374,7 +374,9 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
     }
     const uint32_t nparts = 4u * tiles;
     const uint64_t n = static_cast<uint64_t>(K) * N;
+    // the width of the reduction depends on the sizes alone, so results do not depend on the run
     if (nparts <= 256) dw_finalize_kernel<1><<<dim3(1), dim3(64), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
+    else if (nparts <= 2048) dw_finalize_kernel<4><<<dim3(1), dim3(256), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
     else dw_finalize_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
     return static_cast<int>(hipGetLastError());
 }

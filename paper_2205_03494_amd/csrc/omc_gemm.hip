@@ -30,6 +30,7 @@
 namespace omc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -48,48 +49,36 @@ constexpr int kWChunkBytes = kBN * 16;   // one k-chunk (8 bf16) of all columns
 
 constexpr uint32_t kScanBlocks = 64;      // one flag word each; a GEMM wave reads them all with one load
 
-// Pre-pass.  Workgroups [0, rowsum_blocks): one wave per activation row, rowsum[m] = sum_k A[m][k] in
-// fp32 (lane-strided, then a butterfly).  Workgroups after those (S1E4M3 with bias 7 only): scan the
-// codes for the top code, the one code whose value differs from the hardware FP8 conversion's
-// (480 here, NaN there); flags[j] != 0 sends the GEMM to the generic decode.
-__global__ __launch_bounds__(256) void gemm_prep_kernel(const uint16_t *__restrict__ A, float *__restrict__ rowsum,
-                                                        uint32_t M, uint32_t K, uint32_t rowsum_blocks,
-                                                        const uint32_t *__restrict__ codes, uint64_t code_dwords,
+// Pre-pass (S1E4M3 with bias 7 only): scan the codes for the top code, the one code whose value
+// differs from the hardware FP8 conversion's (480 here, NaN there); flags[j] != 0 sends the GEMM to the
+// generic decode.
+__global__ __launch_bounds__(256) void gemm_scan_kernel(const uint32_t *__restrict__ codes, uint64_t code_dwords,
                                                         uint32_t *__restrict__ flags) {
-    if (blockIdx.x >= rowsum_blocks) {
-        __shared__ uint32_t any_top[4];
-        const uint32_t j = blockIdx.x - rowsum_blocks;
-        const uint64_t pieces = code_dwords / 4;                          // 16-byte pieces (streams are padded to 16 bytes)
-        const uint64_t per = (pieces + kScanBlocks - 1) / kScanBlocks;
-        const uint64_t lo = j * per, hi = (lo + per < pieces) ? lo + per : pieces;
-        uint32_t found = 0;
-        for (uint64_t q = lo + threadIdx.x; q < hi; q += 256) {
-            const u32x4 v = reinterpret_cast<const u32x4 *>(codes)[q];
+    __shared__ uint32_t any_top[4];
+    const uint32_t j = blockIdx.x;
+    const uint64_t pieces = code_dwords / 4;                          // 16-byte pieces (streams are padded to 16 bytes)
+    const uint64_t per = (pieces + kScanBlocks - 1) / kScanBlocks;
+    const uint64_t lo = j * per, hi = (lo + per < pieces) ? lo + per : pieces;
+    uint32_t found = 0;
+    uint64_t q = lo + threadIdx.x;
+    for (; q + 7 * 256 < hi; q += 8 * 256) {                // eight loads in flight per thread
+        u32x4 v[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) found |= ((v[i] & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u;
-        }
-        const bool w = __any(found != 0);
-        if ((threadIdx.x & 63) == 0) any_top[threadIdx.x >> 6] = w ? 1u : 0u;
-        __syncthreads();
-        if (threadIdx.x == 0) flags[j] = any_top[0] | any_top[1] | any_top[2] | any_top[3];
-        return;
+        for (int u = 0; u < 8; ++u) v[u] = reinterpret_cast<const u32x4 *>(codes)[q + u * 256];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) found |= ((v[u][i] & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u;
     }
-    const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const uint32_t lane = threadIdx.x & 63;
-    if (row >= M) return;
-    const uint16_t *a = A + static_cast<uint64_t>(row) * K;
-    float s = 0.0f;
-    for (uint32_t k = lane * 8; k < K; k += 512) {
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(a + k);
+    for (; q < hi; q += 256) {
+        const u32x4 v = reinterpret_cast<const u32x4 *>(codes)[q];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            s += __uint_as_float(v[i] << 16);
-            s += __uint_as_float(v[i] & 0xffff0000u);
-        }
+        for (int i = 0; i < 4; ++i) found |= ((v[i] & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u;
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-    if (lane == 0) rowsum[row] = s;
+    const bool w = __any(found != 0);
+    if ((threadIdx.x & 63) == 0) any_top[threadIdx.x >> 6] = w ? 1u : 0u;
+    __syncthreads();
+    if (threadIdx.x == 0) flags[j] = any_top[0] | any_top[1] | any_top[2] | any_top[3];
 }
 
 // fp32 value of a code given with its sign bit at bit 31 (see the streaming kernels)
@@ -130,8 +119,8 @@ __device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32
 template <int BM, int DEC, bool HW, bool TRANS>
 __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A, const uint32_t *__restrict__ codes,
                                                   uint64_t total_dwords, const FmtParams &fp,
-                                                  const float *__restrict__ sb, const float *__restrict__ rowsum,
-                                                  float *__restrict__ C, uint32_t N, uint32_t K, uint8_t *lds) {
+                                                  const float *__restrict__ sb, float *__restrict__ C, uint32_t N,
+                                                  uint32_t K, uint8_t *lds) {
     constexpr bool BYTE = DEC != 0;
     constexpr int kAChunkBytes = BM * 16;                 // one k-chunk (8 bf16) of all rows
     constexpr int kStageBytes = 4 * kAChunkBytes + 4 * kWChunkBytes;
@@ -186,9 +175,22 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
         for (int rr = 0; rr < 4; ++rr) load_w_row(r, k0, rr);
     };
 
+    // Row sums of A for the b * rowsum(A) term, taken on the way: every piece of A passes through
+    // store_a_piece exactly once, and a thread's piece p always belongs to the same row.
+    float rsum[AP];
+#pragma unroll
+    for (int p = 0; p < AP; ++p) rsum[p] = 0.0f;
+    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
     auto store_a_piece = [&](const StageRegs &r, uint8_t *ldsA, int p) {
         const uint32_t q = tid + 256 * p, row = q >> 2, chunk = q & 3u;
         *reinterpret_cast<u32x4 *>(ldsA + chunk * kAChunkBytes + (OMC_A_SLOT(row, chunk) << 4)) = r.a[p];
+        if (sb) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t w = r.a[p][i];               // (a bit_cast straight from the vector element reads element 0)
+                rsum[p] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, rsum[p], false);
+            }
+        }
     };
     auto store_w_column = [&](uint8_t *ldsA, int i, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) {
         uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
@@ -355,14 +357,28 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
     // ---- epilogue: C = s * acc + b * rowsum --------------------------------------------------------
     const float s = sb ? sb[0] : 1.0f;
     const float b = sb ? sb[1] : 0.0f;
+    // the four threads that hold the pieces of a row add up their parts and publish the row sum in LDS
+    // (the stage buffers are free once everybody is past the last matrix instruction's fragment reads)
+    float *rowsum_lds = reinterpret_cast<float *>(lds);
+    if (sb) {
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < AP; ++p) {
+            float t = rsum[p];
+            t += __shfl_xor(t, 1);
+            t += __shfl_xor(t, 2);
+            if ((tid & 3u) == 0) rowsum_lds[(tid >> 2) + 64 * p] = t;
+        }
+        __syncthreads();
+    }
     // a lane's accumulators cover rows in runs of four: fetch all row sums it needs in one batch
     f32x4 rs[MI][4];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const uint32_t row = m0 + 32 * MI * wave + 32 * mi + 8 * g + 4 * f_half;
-            rs[mi][g] = sb ? *reinterpret_cast<const f32x4 *>(rowsum + row) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            const uint32_t row = 32 * MI * wave + 32 * mi + 8 * g + 4 * f_half;
+            rs[mi][g] = sb ? *reinterpret_cast<const f32x4 *>(rowsum_lds + row) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         }
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
@@ -383,19 +399,18 @@ template <int BM, int DEC, bool TRANS>
 __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
                                                               const uint32_t *__restrict__ codes, uint64_t total_dwords,
                                                               FmtParams fp, const float *__restrict__ sb,
-                                                              const float *__restrict__ rowsum, float *__restrict__ C,
-                                                              uint32_t M, uint32_t N, uint32_t K,
+                                                              float *__restrict__ C, uint32_t M, uint32_t N, uint32_t K,
                                                               const uint32_t *__restrict__ flags) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[2 * (4 * BM * 16 + 4 * kWChunkBytes)];
     (void)M;
     if (DEC == 2) {
         const bool top = __any(flags[threadIdx.x & 63u] != 0);
         if (!top) {
-            dequant_gemm_body<BM, 1, true, TRANS>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
+            dequant_gemm_body<BM, 1, true, TRANS>(A, codes, total_dwords, fp, sb, C, N, K, lds);
             return;
         }
     }
-    dequant_gemm_body<BM, (DEC == 0 ? 0 : 1), false, TRANS>(A, codes, total_dwords, fp, sb, rowsum, C, N, K, lds);
+    dequant_gemm_body<BM, (DEC == 0 ? 0 : 1), false, TRANS>(A, codes, total_dwords, fp, sb, C, N, K, lds);
 }
 
 // C[M x N] = A[M x K] * W (trans == 0, W packed as [K x N]) or A * W^T (trans != 0, W packed as [N x K])
@@ -405,15 +420,11 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
     const uint64_t n = static_cast<uint64_t>(K) * N;
     const uint64_t total_dwords = ((n * fp.bits + 7) / 8 + 15) / 16 * 4;
     const uint32_t *c = static_cast<const uint32_t *>(codes);
-    // workspace: kScanBlocks flag words, then M row sums
+    // workspace: kScanBlocks flag words
     uint32_t *flags = reinterpret_cast<uint32_t *>(ws);
-    float *rowsum = ws + kScanBlocks;
     const int dec = (fp.bits != 8) ? 0 : (fp.variant == 2 ? 2 : 1);
-    const uint32_t rowsum_blocks = sb ? (M + 3) / 4 : 0;
-    const uint32_t scan_blocks = (dec == 2) ? kScanBlocks : 0;
-    if (rowsum_blocks + scan_blocks > 0) {
-        gemm_prep_kernel<<<dim3(rowsum_blocks + scan_blocks), dim3(256), 0, st>>>(A, rowsum, M, K, rowsum_blocks, c,
-                                                                                  total_dwords, flags);
+    if (dec == 2) {
+        gemm_scan_kernel<<<dim3(kScanBlocks), dim3(256), 0, st>>>(c, total_dwords, flags);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return static_cast<int>(e);
     }
@@ -423,10 +434,10 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
     do {                                                                                                            \
         if (trans)                                                                                                  \
             dequant_gemm_kernel<BM, DEC, true><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, \
-                                                                                            rowsum, C, M, N, K, flags); \
+                                                                                            C, M, N, K, flags);     \
         else                                                                                                        \
             dequant_gemm_kernel<BM, DEC, false><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, \
-                                                                                             rowsum, C, M, N, K, flags); \
+                                                                                             C, M, N, K, flags);    \
     } while (0)
     if (!small) {
         if (dec == 2) OMC_GEMM_LAUNCH(256, 2);

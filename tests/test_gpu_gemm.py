@@ -144,3 +144,21 @@ def test_dx_config5_shapes_sampled_rows(shape):
         ref = orc.dequant_gemm_dx(dY, packed, of, sb, M, N, K, rows=(r0, r0 + 24), threads=8)
         rel = check(dX, ref, (r0, r0 + 24))
         assert rel < 1e-5
+
+
+@pytest.mark.parametrize("shape", [(256, 128, 32), (512, 256, 160), (256, 128, 4096)])
+def test_large_offset_makes_the_row_sum_term_count(shape):
+    """With the fitted (s, b) of zero-mean weights b is tiny and the b * rowsum(A) term hides inside the tolerance;
+    a hand-made pair with a large offset makes both GEMMs depend on their row sums."""
+    of, gf = pair(4, 3)
+    M, N, K = shape
+    A = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 1) + np.float32(0.5))
+    W = synth.normal_f32(K * N, 1 / np.sqrt(K), 2)
+    packed, _ = orc.compress(W, of)
+    sb = np.array([0.75, 0.125], np.float32)
+    C = run_gemm(A, packed, gf, sb, M, N, K)
+    check(C, orc.dequant_gemm(A, packed, of, sb, M, N, K, threads=8), (0, M))
+    dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 5) + np.float32(0.5))
+    dX = run_gemm_dx(dY, packed, gf, sb, M, N, K) if K % 128 == 0 else None
+    if dX is not None:
+        check(dX, orc.dequant_gemm_dx(dY, packed, of, sb, M, N, K, threads=8), (0, M))
