@@ -265,7 +265,8 @@ omc_status omc_aggregate_mean(const void *agg_host, const void *agg_dev, const v
 
 /* ---- forward path ------------------------------------------------------------------------ */
 
-/* Workspace (device bytes) for omc_dequant_gemm with M activation rows. */
+/* Workspace (device bytes) for omc_dequant_gemm / omc_dequant_gemm_dx with M activation rows (a few
+ * flag words of a pre-pass over the codes; 0 for M == 0). */
 size_t omc_dequant_gemm_workspace_bytes(uint32_t M);
 
 /* C[M x N] = A[M x K] * Wbar[K x N], Wbar = decompress(codes, sb)  (Sec. 2.1 forward path: the

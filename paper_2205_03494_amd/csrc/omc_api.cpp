@@ -607,7 +607,7 @@ omc_status omc_aggregate_mean(const void *agg_host, const void *agg_dev, const v
 }
 
 size_t omc_dequant_gemm_workspace_bytes(uint32_t M) {
-    return M == 0 ? 0 : 256 + (static_cast<size_t>(M) * sizeof(float) + 15) / 16 * 16;   // flag words + row sums
+    return M == 0 ? 0 : 256;   // the flag words of the top-code scan (independent of M)
 }
 
 omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, const float *sb, float *C,
