@@ -121,6 +121,96 @@ __global__ __launch_bounds__(64, OMC_AGG_WAVES) void aggregate_kernel(AggArgs aa
     }
 }
 
+// Byte codes need no transposition: a lane takes dwords of four codes at the same element offsets as
+// its 16-byte pieces of the fp32 copies and of the output (slab of 1024 elements: piece j of lane l =
+// elements 256 j + 4 l ..).  Everything stays coalesced and LDS is not used.  S1E4M3 / bias 7 is
+// decoded by the hardware's FP8 conversion; its one deviating code (the top code reads as NaN) leaves a
+// NaN in the sum, and such a slab is redone with the generic decode.
+template <bool HW>
+__device__ __forceinline__ void aggregate_byte_slab(const AggArgs &aa, const AggSrc *src, uint32_t var, const FmtParams &fp,
+                                                    uint64_t e0, uint32_t lane, f32x4 (&acc)[4]) {
+    // (fetching the code dwords of all copies before the first decode, to have more loads in flight,
+    // was measured: 499 us instead of 334 us on the benchmark set; one copy at a time it is)
+    for (uint32_t r = 0; r < aa.nreplicas; ++r) {
+        const AggSrc s = to_scalar_regs(src[r]);
+        f32x4 val[4];
+        if (s.quantized) {
+            const uint32_t *c = reinterpret_cast<const uint32_t *>(aa.p.arena[r] + s.data_offset) + (e0 >> 2);
+            const float sc = to_scalar_regs(aa.p.sb[r][2 * static_cast<uint64_t>(var)]);
+            const float of = to_scalar_regs(aa.p.sb[r][2 * static_cast<uint64_t>(var) + 1]);
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = c[64 * j + lane];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float vt[4];
+                if (HW) {
+                    const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w[j]), false);
+                    const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w[j]), true);
+                    vt[0] = lo[0]; vt[1] = lo[1]; vt[2] = hi[0]; vt[3] = hi[1];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) vt[i] = decode_top(w[j] << (24 - 8 * i), fp);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float sv = sc * vt[i];
+                    val[j][i] = sv + of;
+                }
+            }
+        } else {
+            const f32x4 *v = reinterpret_cast<const f32x4 *>(reinterpret_cast<const float *>(aa.p.arena[r] + s.data_offset) + e0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) val[j] = __builtin_nontemporal_load(v + (64 * j + lane));
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[j][i] = (r == 0) ? val[j][i] : acc[j][i] + val[j][i];
+    }
+}
+
+__global__ __launch_bounds__(64, 8) void aggregate_byte_kernel(AggArgs aa) {
+    if (blockIdx.x >= aa.nitems) {
+        aggregate_flat_item(aa, aa.flat_first + (blockIdx.x - aa.nitems));
+        return;
+    }
+    const uint32_t lane = threadIdx.x;
+    const uint32_t item = aa.first_item + blockIdx.x;
+    const PlanItem it = to_scalar_regs(reinterpret_cast<const PlanItem *>(aa.plan + aa.item_off)[item]);
+    const AggVar av = to_scalar_regs(reinterpret_cast<const AggVar *>(aa.plan + aa.var_off)[it.var]);
+    const AggSrc *src = reinterpret_cast<const AggSrc *>(aa.plan + aa.src_off) + static_cast<uint64_t>(it.var) * aa.nreplicas;
+    const FmtParams fp = av.fp;
+    const uint64_t first_tile = static_cast<uint64_t>(it.chunk) * kTilesPerChunk;
+    const uint64_t full_tiles = av.n / kTileElems;
+    const uint32_t ntiles = static_cast<uint32_t>(
+        (full_tiles - first_tile < kTilesPerChunk) ? full_tiles - first_tile : kTilesPerChunk);
+    const bool hw = fp.variant == 2;
+    for (uint32_t sl = 0; sl < 2 * ntiles; ++sl) {
+        const uint64_t e0 = first_tile * kTileElems + static_cast<uint64_t>(sl) * 1024;
+        f32x4 acc[4];
+        bool done = false;
+        if (hw) {
+            aggregate_byte_slab<true>(aa, src, it.var, fp, e0, lane, acc);
+            bool bad = false;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) bad = bad || (acc[j][i] != acc[j][i]);
+            done = !__any(bad);
+        }
+        if (!done) aggregate_byte_slab<false>(aa, src, it.var, fp, e0, lane, acc);
+        f32x4 *dst = reinterpret_cast<f32x4 *>(aa.out + av.aux_offset + e0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = acc[j][i] / aa.count;
+            __builtin_nontemporal_store(o, dst + (64 * j + lane));
+        }
+    }
+}
+
 // Ragged tails of those variables: one wave each, run-time code width, every access checked.
 __global__ __launch_bounds__(64) void aggregate_tail_kernel(AggArgs aa) {
     const uint32_t lane = threadIdx.x;
@@ -199,6 +289,12 @@ int launch_aggregate_mean(const AggHeader *ah, const void *agg_dev, const AggPoi
                 flat_done = true;
             }
             const dim3 grid(g.nitems + aa.flat_nitems);
+            if (g.bits == 8) {
+                aggregate_byte_kernel<<<grid, dim3(64), 0, st>>>(aa);
+                const hipError_t e8 = hipGetLastError();
+                if (e8 != hipSuccess) return static_cast<int>(e8);
+                continue;
+            }
             switch (g.bits) {
 #define X(BITS) case BITS: aggregate_kernel<BITS><<<grid, dim3(64), 0, st>>>(aa); break;
                 OMC_FOR_EACH_BITS(X)

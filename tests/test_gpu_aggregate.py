@@ -80,3 +80,44 @@ def test_mixed_formats_across_variables_and_everyone_fp32():
     masks = [np.array([s.is_matrix for s in specs]), np.array([s.is_matrix and i % 2 == 0 for i, s in enumerate(specs)])]
     run_case(specs, fmts, masks)
     run_case(specs, fmts, [np.zeros(len(specs), bool)] * 3)  # no client quantizes anything
+
+
+def test_top_codes_and_non_finite_copies_in_the_byte_path():
+    """S1E4M3 copies are decoded by the hardware conversion, which reads the top code as NaN; slabs that
+    meet one are redone generically.  A NaN / Inf in an fp32 copy must come out as the oracle's NaN / Inf."""
+    specs = [synth.VarSpec("w", (8192 * 2 + 2048 * 3,), 8192 * 2 + 2048 * 3, True),
+             synth.VarSpec("u", (4096,), 4096, True)]
+    fmts = [(4, 3), (4, 3)]
+    masks = [np.array([True, True]), np.array([False, True]), np.array([True, False])]
+    R = len(masks)
+    lays, plans, arenas, sbs, copies = [], [], [], [], [[None] * R for _ in specs]
+    for r, mask in enumerate(masks):
+        lay, plan = build(specs, mask, fmts)
+        vals = synth.init_values(lay, 40 + r)
+        a0, a1 = int(lay.aux_offset[0]), int(lay.aux_offset[1])
+        vals[a0 + 5] = 480.0; vals[a0 + 3000] = -480.0; vals[a0 + 9000:a0 + 9040] = 1e4     # top codes where quantized
+        vals[a1 + 7] = 500.0
+        if r == 1:
+            vals[a0 + 12345] = np.nan; vals[a0 + 12346] = np.inf; vals[a0 + 20000] = -np.inf  # fp32 copy of variable 0
+        arena, sb = oracle_arena(specs, mask, fmts, lay, vals)
+        lays.append(lay); plans.append(plan); arenas.append(to_dev(arena)); sbs.append(to_dev(sb))
+        for i, s in enumerate(specs):
+            d = int(lay.data_offset[i])
+            if mask[i]:
+                of = orc.Format(4, 3)
+                copies[i][r] = orc.decompress(arena[d:d + orc.packed_bytes(s.n, 8)], s.n, of, sb[i])
+            else:
+                copies[i][r] = arena[d:d + 4 * s.n].view(np.float32)
+    agg = omc.omc_aggregate_plan_build(plans)
+    out = torch.zeros(lays[0].aux_elems, device="cuda")
+    omc.omc_aggregate_mean(agg, arenas, sbs, out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    for i, s in enumerate(specs):
+        a = int(lays[0].aux_offset[i])
+        want = orc.aggregate_mean(copies[i])
+        got = o[a:a + s.n]
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(got), nan)
+        assert bits_equal(got[~nan], want[~nan])
+    assert np.isnan(o[int(lays[0].aux_offset[0]) + 12345])
