@@ -7,6 +7,9 @@ namespace omc {
 #ifndef OMC_TUNE_WAVES_FP6
 #define OMC_TUNE_WAVES_FP6 2
 #endif
+#ifndef OMC_TUNE_OCP_MAXMODE
+#define OMC_TUNE_OCP_MAXMODE 2      // kStepSgd: the hardware FP8 variant serves plain SGD only
+#endif
 #ifndef OMC_TUNE_FP6_MAXMODE
 #define OMC_TUNE_FP6_MAXMODE 2      // kStepSgd: the hardware 6-bit variant serves plain SGD only
 #endif
@@ -113,7 +116,7 @@ __global__ __launch_bounds__(64, (VARIANT == 3 ? OMC_TUNE_WAVES_FP6 : Tuning<MOD
 template <int MODE>
 inline int launch_step_group_mode(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st) {
     // the hardware-conversion variant pays off where the vector ALU is the limit: plain SGD
-    if (bits == 8 && variant == 2 && MODE == kStepSgd) {
+    if (bits == 8 && variant == 2 && MODE <= OMC_TUNE_OCP_MAXMODE) {
         step_kernel<8, MODE, 2><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);
         return static_cast<int>(hipGetLastError());
     }
