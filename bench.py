@@ -147,7 +147,7 @@ def gemm_leg(torch, omc, synth, iters=20):
         rec["dx_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
         # and its weight gradient dW[K, N] = X^T @ dY, consumed by the SGD update + recompression in the epilogue
         del dX
-        wsd = torch.empty(omc.omc_dw_update_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+        wsd = torch.empty(omc.omc_dw_update_workspace_bytes(gf, M, N, K), dtype=torch.uint8, device="cuda")
         o = omc.opt(omc.OMC_SGD, 0.01)
         for _ in range(3):
             omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd)

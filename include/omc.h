@@ -305,10 +305,11 @@ omc_status omc_dequant_gemm_dx(const uint16_t *dY, const void *codes, omc_format
 
 /* ---- backward path: weight gradient consumed by the update ---------------------------------- */
 
-/* Workspace (device bytes) for omc_dw_update_recompress with M rows of X / dY on a K x N weight matrix;
- * 0 for unsupported sizes.  When the matrix alone gives too few tiles to fill the chip, the M rows are
- * split between workgroups and the workspace holds their partial accumulators (up to 8 * 4*K*N bytes). */
-size_t omc_dw_update_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
+/* Workspace (device bytes) for omc_dw_update_recompress with M rows of X / dY on a K x N weight matrix
+ * stored in format f; 0 for unsupported formats or sizes.  When the matrix alone gives too few tiles
+ * to fill the chip, the M rows are split between workgroups and the workspace holds their partial
+ * accumulators (up to 8 * 4*K*N bytes); for code widths other than 8 it always holds one such copy. */
+size_t omc_dw_update_workspace_bytes(omc_format f, uint32_t M, uint32_t N, uint32_t K);
 
 /* The whole backward step of a linear layer Y = X * Wbar on its compressed weights (Sec. 2.1, backward
  * propagation: decompress the parameters, apply the gradients, compress, discard): the weight
@@ -322,9 +323,11 @@ size_t omc_dw_update_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
  *   sb       device, 2 floats, in: (s, b) of the variable, out: the new pair ((1, 0) when use_pvt == 0)
  *   state0/1 device, K*N floats each, as for omc_step_update_recompress (momentum / Adam moments)
  *   dW_out   device, K*N floats, or NULL; receives the gradient exactly as the update consumed it
- *   ws       device workspace of omc_dw_update_workspace_bytes(M, N, K) bytes
- * Requires an 8-bit format (a lane of the accumulator layout then owns whole dwords of codes),
- * K % 256 == 0, N % 128 == 0, M % 32 == 0 (OMC_ERR_FORMAT / OMC_ERR_SIZE).  Result: identical to
+ *   ws       device workspace of omc_dw_update_workspace_bytes(f, M, N, K) bytes
+ * Requires K % 256 == 0, N % 128 == 0, M % 32 == 0 (OMC_ERR_SIZE).  With an 8-bit format and enough
+ * tiles the update runs in the GEMM kernel's epilogue (a lane of the accumulator layout owns whole
+ * dwords of codes) and the gradient never reaches memory; otherwise the accumulators pass through
+ * the workspace once and a second kernel does the update.  Result: identical to
  * omc_step_update_recompress on this variable with dW_out as its gradient; the gradient's summation
  * order is fixed by the sizes alone, so repeated calls give identical bits. */
 omc_status omc_dw_update_recompress(const uint16_t *X, const uint16_t *dY, void *codes, omc_format f,

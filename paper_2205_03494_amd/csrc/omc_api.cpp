@@ -625,9 +625,10 @@ omc_status omc_dequant_gemm(const uint16_t *A, const void *codes, omc_format f, 
     return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
 }
 
-size_t omc_dw_update_workspace_bytes(uint32_t M, uint32_t N, uint32_t K) {
+size_t omc_dw_update_workspace_bytes(omc_format f, uint32_t M, uint32_t N, uint32_t K) {
+    if (!format_ok(f)) return 0;
     if (M == 0 || N == 0 || K == 0 || M % 32 != 0 || K % 256 != 0 || N % 128 != 0) return 0;
-    return dw_workspace_bytes(M, N, K);
+    return dw_workspace_bytes(1u + f.exp_bits + f.man_bits, M, N, K);
 }
 
 omc_status omc_dw_update_recompress(const uint16_t *X, const uint16_t *dY, void *codes, omc_format f, float *sb,
@@ -636,7 +637,6 @@ omc_status omc_dw_update_recompress(const uint16_t *X, const uint16_t *dY, void 
     if (!X || !dY || !codes || !sb || !opt) return OMC_ERR_NULL;
     FmtParams fp;
     if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
-    if (fp.bits != 8) return OMC_ERR_FORMAT;
     if (M == 0 || N == 0 || K == 0 || M % 32 != 0 || K % 256 != 0 || N % 128 != 0) return OMC_ERR_SIZE;
     if (opt->kind != OMC_SGD && opt->kind != OMC_MOMENTUM && opt->kind != OMC_ADAM) return OMC_ERR_OPT;
     if (opt->kind >= OMC_MOMENTUM && !state0) return OMC_ERR_OPT;
@@ -644,7 +644,7 @@ omc_status omc_dw_update_recompress(const uint16_t *X, const uint16_t *dY, void 
     if (!aligned16(X) || !aligned16(dY) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return OMC_ERR_ALIGN;
     if ((state0 && !aligned16(state0)) || (state1 && !aligned16(state1)) || (dW_out && !aligned16(dW_out)))
         return OMC_ERR_ALIGN;
-    const size_t need = omc_dw_update_workspace_bytes(M, N, K);
+    const size_t need = omc_dw_update_workspace_bytes(f, M, N, K);
     if (!ws || ws_bytes < need) return OMC_ERR_WORKSPACE;
     if (!aligned16(ws)) return OMC_ERR_ALIGN;
     const int rc = launch_dw_update(X, dY, codes, fp, sb, use_pvt, state0, state1, *opt, dW_out, M, N, K,

@@ -12,7 +12,7 @@
 // Tile row r = 64 i + q stands for weight row 4 q + i, so that the stores of neighbouring threads are
 // neighbours in LDS (the order of the rows of a tile is free); tile column slot 32 i + q stands for
 // column 4 q + i, so that a lane ends up with four adjacent columns of a row: one dword of 8-bit codes.
-#include "omc_stream.h"
+#include "omc_dw_args.h"
 
 namespace omc {
 
@@ -20,22 +20,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kDwCols = 128, kDwStep = 32;
 constexpr int kDwBChunk = kDwCols * 16;
-
-struct DwArgs {
-    const uint16_t *X, *dY;
-    uint32_t *codes;
-    const float *sb;
-    float *st0, *st1;
-    float *dW_out;
-    Partial *ws;
-    float *partials;         // split contraction: [tile][split][ROWS * 128] accumulators
-    uint32_t nsplit;         // workgroups per tile along the contraction (gridDim.z)
-    FmtParams fp;
-    OptConst oc;
-    uint32_t M, N, K;
-};
 
 __device__ __forceinline__ uint32_t dw_a_slot(uint32_t row, uint32_t chunk) { return row ^ (2u * chunk); }
 
@@ -251,9 +236,9 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
     }
 
     const uint32_t block = blockIdx.y * gridDim.x + blockIdx.x;     // tile index
-    // ---- split contraction: park the partial accumulators (accumulator layout, 16 bytes per lane and
-    // row); dw_reduce_update_kernel adds them up in split order and does the rest
-    if (a.nsplit > 1) {
+    // ---- park the accumulators (accumulator layout, 16 bytes per lane and row): several splits of the
+    // contraction, or a code width other than 8; the slab kernels add them up in split order and do the rest
+    if (a.park) {
         constexpr uint32_t kTileFloats = ROWS * kDwCols;
         float *mine = a.partials + (static_cast<uint64_t>(block) * a.nsplit + blockIdx.z) * kTileFloats;
 #pragma unroll
@@ -268,36 +253,16 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
     dw_finish_wave<ROWS, MODE>(a, acc, k0t, n0, lane, wave, block);
 }
 
-// Second kernel of the split contraction: one wave per (tile, wave of the first kernel).  Sums the
-// tile's partial accumulators in split order, so the gradient does not depend on scheduling, then
-// the same epilogue.
-template <int ROWS, int MODE>
-__global__ __launch_bounds__(64, 2) void dw_reduce_update_kernel(DwArgs a, uint32_t tiles_x) {
-    constexpr int MI = ROWS / 128;
-    constexpr uint32_t kTileFloats = ROWS * kDwCols;
-    const uint32_t lane = threadIdx.x, wave = blockIdx.x & 3u, block = blockIdx.x >> 2;
-    const uint32_t k0t = (block % tiles_x) * ROWS, n0 = (block / tiles_x) * kDwCols;
-    const float *all = a.partials + static_cast<uint64_t>(block) * a.nsplit * kTileFloats;
-    f32x16 acc[MI][4];
-    for (uint32_t sp = 0; sp < a.nsplit; ++sp) {
-        const f32x4 *src = reinterpret_cast<const f32x4 *>(all + static_cast<uint64_t>(sp) * kTileFloats);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const f32x4 t = __builtin_nontemporal_load(src + ((mi * 16 + v) * 256 + wave * 64 + lane));
-#pragma unroll
-                for (int ni = 0; ni < 4; ++ni) acc[mi][ni][v] = (sp == 0) ? t[ni] : acc[mi][ni][v] + t[ni];
-            }
-    }
-    dw_finish_wave<ROWS, MODE>(a, acc, k0t, n0, lane, wave, block);
-}
-
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void dw_finalize_kernel(const Partial *__restrict__ ws, uint32_t nparts, uint64_t n,
                                                               int use_pvt, float *__restrict__ sb) {
     __shared__ double red[NW * 10];
     finalize_variable<NW>(ws, nparts, nullptr, n, use_pvt != 0, sb, red);
+}
+
+// one Partial per 16-row x 128-column slab (the finest grain any of the update kernels uses)
+static size_t dw_fit_bytes(uint32_t N, uint32_t K) {
+    return (static_cast<size_t>(K) * N / kTileElems * sizeof(Partial) + 255) / 256 * 256;
 }
 
 // Tile height and number of contraction splits for a problem size: 256-row tiles and no split when
@@ -325,9 +290,10 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
     hipStream_t st = static_cast<hipStream_t>(stream);
     const DwConfig cfg = dw_config(M, N, K);
     const uint32_t tiles = (K / cfg.rows) * (N / kDwCols);
-    // workspace: one fit partial per wave and tile | partial accumulators
+    // workspace: the fit's partials (one per 16-row slab at most) | parked accumulators
     uint8_t *w8 = static_cast<uint8_t *>(ws);
-    const size_t fit_bytes = (static_cast<size_t>(4) * (K / 128) * (N / kDwCols) * sizeof(Partial) + 255) / 256 * 256;
+    const size_t fit_bytes = dw_fit_bytes(N, K);
+    const bool byte_codes = fp.bits == 8;
     DwArgs a{};
     a.X = X;
     a.dY = dY;
@@ -338,6 +304,7 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
     a.dW_out = dW_out;
     a.ws = reinterpret_cast<Partial *>(w8);
     a.partials = reinterpret_cast<float *>(w8 + fit_bytes);
+    a.park = (cfg.nsplit > 1 || !byte_codes) ? 1u : 0u;
     a.nsplit = cfg.nsplit;
     a.fp = fp;
     a.oc = OptConst{opt.lr, opt.momentum, opt.beta1, opt.beta2, opt.eps, opt.one_minus_beta1,
@@ -357,22 +324,16 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
 #undef OMC_DW_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return static_cast<int>(e);
-    if (cfg.nsplit > 1) {
-        const dim3 grid2(4 * tiles);
+    uint32_t nparts = 4u * tiles;
+    if (a.park) {                                          // the slab kernels do the update, whatever the code width
         const uint32_t tx = K / cfg.rows;
-#define OMC_DW_LAUNCH2(ROWS)                                                                                  \
-    do {                                                                                                      \
-        if (opt.kind == OMC_SGD) dw_reduce_update_kernel<ROWS, kStepSgd><<<grid2, dim3(64), 0, st>>>(a, tx);  \
-        else if (opt.kind == OMC_MOMENTUM) dw_reduce_update_kernel<ROWS, kStepMomentum><<<grid2, dim3(64), 0, st>>>(a, tx); \
-        else dw_reduce_update_kernel<ROWS, kStepAdam><<<grid2, dim3(64), 0, st>>>(a, tx);                     \
-    } while (0)
-        if (cfg.rows == 128) OMC_DW_LAUNCH2(128);
-        else OMC_DW_LAUNCH2(256);
-#undef OMC_DW_LAUNCH2
-        e = hipGetLastError();
-        if (e != hipSuccess) return static_cast<int>(e);
+        int rc;
+        if (opt.kind == OMC_SGD) rc = launch_dw_generic_sgd(fp.bits, fp.wide, cfg.rows, a, tiles, tx, st);
+        else if (opt.kind == OMC_MOMENTUM) rc = launch_dw_generic_momentum(fp.bits, fp.wide, cfg.rows, a, tiles, tx, st);
+        else rc = launch_dw_generic_adam(fp.bits, fp.wide, cfg.rows, a, tiles, tx, st);
+        if (rc != 0) return rc;
+        nparts = static_cast<uint32_t>(static_cast<uint64_t>(K) * N / kTileElems);
     }
-    const uint32_t nparts = 4u * tiles;
     const uint64_t n = static_cast<uint64_t>(K) * N;
     // the width of the reduction depends on the sizes alone, so results do not depend on the run
     if (nparts <= 256) dw_finalize_kernel<1><<<dim3(1), dim3(64), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
@@ -381,11 +342,11 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
     return static_cast<int>(hipGetLastError());
 }
 
-size_t dw_workspace_bytes(uint32_t M, uint32_t N, uint32_t K) {
+size_t dw_workspace_bytes(uint32_t bits, uint32_t M, uint32_t N, uint32_t K) {
     const DwConfig cfg = dw_config(M, N, K);
-    const size_t fit_bytes = (static_cast<size_t>(4) * (K / 128) * (N / kDwCols) * sizeof(Partial) + 255) / 256 * 256;
-    const size_t partial_bytes = cfg.nsplit > 1 ? static_cast<size_t>(cfg.nsplit) * K * N * sizeof(float) : 0;
-    return fit_bytes + partial_bytes;
+    const bool park = cfg.nsplit > 1 || bits != 8;
+    const size_t partial_bytes = park ? static_cast<size_t>(cfg.nsplit) * K * N * sizeof(float) : 0;
+    return dw_fit_bytes(N, K) + partial_bytes;
 }
 
 }  // namespace omc

@@ -144,7 +144,7 @@ struct DwConfig {
     uint32_t nsplit;   // workgroups per tile along the contraction
 };
 DwConfig dw_config(uint32_t M, uint32_t N, uint32_t K);
-size_t dw_workspace_bytes(uint32_t M, uint32_t N, uint32_t K);
+size_t dw_workspace_bytes(uint32_t bits, uint32_t M, uint32_t N, uint32_t K);
 int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const FmtParams &fp, float *sb, int use_pvt,
                      float *state0, float *state1, const omc_opt &opt, float *dW_out, uint32_t M, uint32_t N,
                      uint32_t K, void *ws, void *stream);

@@ -83,7 +83,7 @@ _agg_mean = _sig("omc_aggregate_mean", C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.
 _gemm_ws = _sig("omc_dequant_gemm_workspace_bytes", C.c_size_t, C.c_uint32)
 _gemm = _sig("omc_dequant_gemm", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
              C.c_uint32, _vp, C.c_size_t, _vp)
-_dw_ws = _sig("omc_dw_update_workspace_bytes", C.c_size_t, C.c_uint32, C.c_uint32, C.c_uint32)
+_dw_ws = _sig("omc_dw_update_workspace_bytes", C.c_size_t, omc_format, C.c_uint32, C.c_uint32, C.c_uint32)
 _dw = _sig("omc_dw_update_recompress", C.c_int, _vp, _vp, _vp, omc_format, _vp, C.c_int, _vp, _vp, C.POINTER(omc_opt), _vp,
            C.c_uint32, C.c_uint32, C.c_uint32, _vp, C.c_size_t, _vp)
 _gemm_dx = _sig("omc_dequant_gemm_dx", C.c_int, _vp, _vp, omc_format, _vp, _vp, C.c_uint32, C.c_uint32,
@@ -296,8 +296,8 @@ def omc_dequant_gemm_dx(dY: torch.Tensor, codes: torch.Tensor, f: omc_format, sb
                     ws.numel() * ws.element_size(), _stream(stream)), "omc_dequant_gemm_dx")
 
 
-def omc_dw_update_workspace_bytes(M: int, N: int, K: int) -> int:
-    return _dw_ws(M, N, K)
+def omc_dw_update_workspace_bytes(f: omc_format, M: int, N: int, K: int) -> int:
+    return _dw_ws(f, M, N, K)
 
 
 def omc_dw_update_recompress(X: torch.Tensor, dY: torch.Tensor, codes: torch.Tensor, f: omc_format, sb: torch.Tensor,

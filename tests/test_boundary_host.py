@@ -245,11 +245,12 @@ def test_dw_update_rejects_bad_arguments():
     o = omc.opt(omc.OMC_SGD, 0.1)
     def call(X=A, dY=A, codes=A, fm=f, sb=A, st0=None, st1=None, opt=o, M=64, N=128, K=256, ws=A, wsb=1 << 20):
         return omc._dw(X, dY, codes, fm, sb, 1, st0, st1, omc.C.byref(opt), None, M, N, K, ws, wsb, None)
-    assert omc.omc_dw_update_workspace_bytes(64, 128, 256) == 512                           # no split: the fit's partials only
-    assert omc.omc_dw_update_workspace_bytes(8192, 128, 256) == 512 + 8 * 4 * 128 * 256     # 8 splits of 1024 rows
-    assert omc.omc_dw_update_workspace_bytes(64, 100, 256) == 0
+    assert omc.omc_dw_update_workspace_bytes(f, 64, 128, 256) == 768                        # no split: the fit's partials only
+    assert omc.omc_dw_update_workspace_bytes(f, 8192, 128, 256) == 768 + 8 * 4 * 128 * 256  # 8 splits of 1024 rows
+    assert omc.omc_dw_update_workspace_bytes(omc.fmt(3, 7), 64, 128, 256) == 768 + 4 * 128 * 256   # other widths park once
+    assert omc.omc_dw_update_workspace_bytes(f, 64, 100, 256) == 0
     assert call(X=None) == 1
-    assert call(fm=omc.fmt(3, 7)) == 2                   # not an 8-bit format
+    assert call(fm=omc.fmt(9, 7)) == 2                   # not a format
     assert call(M=48) == 3 and call(N=64) == 3 and call(K=128) == 3
     assert call(opt=omc.opt(omc.OMC_ADAM, 0.1), st0=A) == 6
     assert call(codes=A + 4) == 4

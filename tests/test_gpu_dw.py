@@ -25,7 +25,7 @@ def run_case(EM, M, N, K, kind, lr, use_pvt=True, steps=2, grad_scale=1.0, want_
     codes_d, sb_d = to_dev(packed), to_dev(sb)
     st0_d = None if st0 is None else to_dev(st0)
     st1_d = None if st1 is None else to_dev(st1)
-    ws = torch.empty(omc.omc_dw_update_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(omc.omc_dw_update_workspace_bytes(gf, M, N, K), dtype=torch.uint8, device="cuda")
     dW_d = torch.full((K, N), float("nan"), device="cuda") if want_dw else None
     for t in range(1, steps + 1):
         X = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 10 + t))
@@ -78,3 +78,36 @@ def test_without_the_transformation_and_with_saturating_updates():
 def test_config5_layer_sampled_gradient_rows():
     # the feed-forward layer of the benchmark shape: X [8192 x 1024], W [1024 x 4096]
     run_case((4, 3), 8192, 4096, 1024, 0, 0.01, steps=1, rows=(0, 500, 1008))
+
+
+@pytest.mark.parametrize("kind,lr", [(0, 0.05), (1, 0.05), (2, 1e-3)])
+@pytest.mark.parametrize("EM", [(3, 7), (2, 3), (5, 7), (4, 14), (8, 7), (5, 10)])
+def test_other_code_widths_take_the_two_kernel_path(EM, kind, lr):
+    """6-, 11-, 13-, 16- and 19-bit formats: the accumulators pass through the workspace and the slab kernel
+    updates the rows; same two-stage check."""
+    run_case(EM, 96, 128, 256, kind, lr)
+
+
+def test_other_code_widths_with_split_contraction_and_several_tiles():
+    run_case((3, 7), 2048, 256, 512, 1, 0.05, steps=2)
+    run_case((2, 3), 1024, 128, 256, 0, 0.05, steps=2, grad_scale=20.0)
+
+
+def test_fp32_as_a_format_is_plain_sgd():
+    """S1E8M23 stores fp32 itself; without the transformation the fused step must equal w - lr * dW in fp32."""
+    M, N, K = 64, 128, 256
+    gf = omc.fmt(8, 23)
+    W = synth.normal_f32(K * N, 0.05, 2)
+    codes = to_dev(W.view(np.uint8).copy())
+    sb = torch.tensor([1.0, 0.0], device="cuda")
+    X = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 11))
+    dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0 / M, 21))
+    ws = torch.empty(omc.omc_dw_update_workspace_bytes(gf, M, N, K), dtype=torch.uint8, device="cuda")
+    dW = torch.zeros((K, N), device="cuda")
+    omc.omc_dw_update_recompress(to_dev(X), to_dev(dY), codes, gf, sb, False, None, None, omc.opt(0, 0.05), dW, M, N, K, ws)
+    torch.cuda.synchronize()
+    g = dW.cpu().numpy().ravel()
+    step = (np.float32(0.05) * g).astype(np.float32)
+    want = (W - step).astype(np.float32)
+    assert bits_equal(codes.cpu().numpy().view(np.float32), want)
+    assert sb.cpu().numpy().tolist() == [1.0, 0.0]
