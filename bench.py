@@ -159,7 +159,7 @@ def gemm_leg(torch, omc, synth, iters=20):
         ms = e0.elapsed_time(e1) / iters
         rec["dw_update_ms"] = ms
         rec["dw_update_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-        rec["dw_gradient_bytes_not_materialized"] = 4 * K * N
+        rec["dw_workspace_bytes"] = wsd.numel()   # fit partials + parked accumulators of the contraction splits
         out.append(rec)
     return out
 
