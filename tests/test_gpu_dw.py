@@ -111,3 +111,8 @@ def test_fp32_as_a_format_is_plain_sgd():
     want = (W - step).astype(np.float32)
     assert bits_equal(codes.cpu().numpy().view(np.float32), want)
     assert sb.cpu().numpy().tolist() == [1.0, 0.0]
+
+
+def test_large_matrix_takes_the_in_kernel_epilogue_on_256_row_tiles():
+    # 4096 x 4096 weights = 512 tiles of 256 x 128: no split, the update runs in the GEMM kernel's epilogue
+    run_case((4, 3), 64, 4096, 4096, 1, 0.05, steps=1, rows=(0, 2000, 4080))
