@@ -18,10 +18,15 @@
 //      that MFMA tile i covers the columns == i (mod 4): the stores of 16 neighbouring lanes then
 //      fill 128 contiguous bytes, and in the epilogue a lane holds four adjacent columns of C,
 //      one 16-byte store per row.
+//      (S1E4M3 with bias 7: the hardware FP8 conversion decodes, after a pre-pass has excluded the one
+//      code it reads differently.)
 // The K loop is double-buffered in LDS: while the matrix cores work on one K step, the codes of the
-// next one are decoded and stored into the other buffer, and the global loads of the two steps
-// after that are in flight into two register sets; one workgroup barrier per K step.  When the 256-row tiling
-// would leave compute units idle, a 128-row variant (wave = 32 rows) doubles the number of workgroups.
+// next one are decoded and stored into the other buffer; the global loads of the step after that are
+// issued right after the barrier that ends a round (the 128-row variant, used when 256-row tiles
+// would leave compute units idle, keeps two register sets and loads two steps ahead); one workgroup
+// barrier per K step.  The row sums of A are taken inside the kernel from the staged pieces.
+// omc_dequant_gemm_dx (dX = dY * Wbar^T) is the same kernel with the codes read along the other
+// direction (TRANS): 16 consecutive codes of a weight row per thread, decoded into two k-chunks.
 #include <hip/hip_runtime.h>
 #include "omc_internal.h"
 
