@@ -130,3 +130,78 @@ def test_config4_full_size_momentum_11bit():
     fmts = [(3, 7)] * len(specs)
     ns, total = run_fullsize(specs, mask, fmts, kind=1, lr=0.01, steps=2, seed=4, max_sample_elems=12_000_000)
     assert ns >= 6
+
+
+def _device_values(specs, lay, seed, delta_seed=None):
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    vals = torch.empty(lay.aux_elems, device="cuda")
+    for i, s in enumerate(specs):
+        a = int(lay.aux_offset[i])
+        std = 1.0 / np.sqrt(s.fan_in) if s.is_matrix else 0.02
+        vals[a:a + s.n].normal_(0.0, std, generator=gen)
+    if delta_seed is not None:                          # a client's own small update on top of the shared values
+        g2 = torch.Generator(device="cuda").manual_seed(delta_seed)
+        vals += torch.empty_like(vals).normal_(0.0, 2e-3, generator=g2)
+    return vals
+
+
+def test_benchmark_set_whole_set_conversions_and_server_aggregation():
+    """Config-2 sized set (115 M parameters): omc_compress_set, omc_decompress_set and omc_aggregate_mean over
+    four clients with their own 90 % subsets, in the launch configuration bench.py times; the oracle
+    recomputes sampled variables one by one."""
+    specs = synth.conformer_varset(512, 17, 2048, 32, frontend=True)
+    fmt = (4, 3)
+    of, gf = orc.Format(*fmt), omc.fmt(*fmt)
+    R = 4
+    clients = []
+    for r in range(R):
+        mask = synth.ppq_mask(specs, 0.9, 300 + r)
+        lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(gf, n))
+        table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gf,
+                      quantized=bool(mask[i])) for i, s in enumerate(specs)]
+        plan = omc.omc_plan_build(omc.make_var_table(table))
+        vals = _device_values(specs, lay, 7, delta_seed=900 + r)
+        arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
+        sb = torch.zeros((len(specs), 2), device="cuda")
+        ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+        omc.omc_compress_set(vals, plan, arena, sb, ws)
+        clients.append(dict(mask=mask, lay=lay, plan=plan, vals=vals, arena=arena, sb=sb))
+    torch.cuda.synchronize()
+    lay0 = clients[0]["lay"]
+    # sample: union of the per-client picks, bounded
+    samples, total = [], 0
+    for i in pick_samples(specs, clients[0]["mask"]):
+        if total + specs[i].n <= 9_000_000 or not samples:
+            samples.append(i)
+            total += specs[i].n
+    # 1. compress_set: each client's transported form of the sampled variables
+    copies = {i: [] for i in samples}
+    for c in clients:
+        for i in samples:
+            s = specs[i]
+            a, d = int(c["lay"].aux_offset[i]), int(c["lay"].data_offset[i])
+            x = c["vals"][a:a + s.n].cpu().numpy()
+            if c["mask"][i]:
+                p, osb = orc.compress(x, of)
+                nb = omc.omc_packed_bytes(gf, s.n)
+                assert np.array_equal(c["arena"][d:d + nb].cpu().numpy(), p), f"compress_set: {s.name}"
+                assert bits_equal(c["sb"][i].cpu().numpy(), osb)
+                copies[i].append(orc.decompress(p, s.n, of, osb))
+            else:
+                assert bits_equal(c["arena"][d:d + 4 * s.n].cpu().numpy().view(np.float32), x), f"compress_set fp32: {s.name}"
+                copies[i].append(x)
+    # 2. decompress_set of client 0
+    out = torch.empty(lay0.aux_elems, device="cuda")
+    omc.omc_decompress_set(clients[0]["arena"], clients[0]["plan"], clients[0]["sb"], out)
+    torch.cuda.synchronize()
+    for i in samples:
+        a = int(lay0.aux_offset[i])
+        assert bits_equal(out[a:a + specs[i].n].cpu().numpy(), copies[i][0]), f"decompress_set: {specs[i].name}"
+    # 3. the server's mean over the four clients
+    agg = omc.omc_aggregate_plan_build([c["plan"] for c in clients])
+    omc.omc_aggregate_mean(agg, [c["arena"] for c in clients], [c["sb"] for c in clients], out)
+    torch.cuda.synchronize()
+    for i in samples:
+        a = int(lay0.aux_offset[i])
+        assert bits_equal(out[a:a + specs[i].n].cpu().numpy(), orc.aggregate_mean(copies[i])), f"aggregate: {specs[i].name}"
+    assert torch.isfinite(out).all()
