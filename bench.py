@@ -274,6 +274,68 @@ def formats_leg(torch, omc, synth, blocks, steps=20):
     return res
 
 
+def other_configs_leg(torch, omc, synth, steps=10):
+    """The other step configurations of the baseline at full size (they are parity-test cases first; timed here
+    for reference): config 3 = the benchmark set with half of the matrices quantized in three formats (8, 11,
+    16 bit) and Adam; config 4 = a 604 M-parameter set (24 blocks, d_model 1024, ffn 4096) in S1E3M7 with momentum."""
+    import numpy as np
+    res = []
+    for name, dims, frac, choices, kind, lr in (
+            ("config3: 17 blocks d=512, 50% of matrices quantized (S1E4M3 / S1E3M7 / S1E5M10), Adam",
+             (512, 17, 2048, 32, True), 0.5, [(4, 3), (3, 7), (5, 10)], omc.OMC_ADAM, 1e-3),
+            ("config4: 24 blocks d=1024 ffn=4096, all matrices S1E3M7, momentum 0.9",
+             (1024, 24, 4096, 32, False), None, [(3, 7)], omc.OMC_MOMENTUM, 0.01)):
+        specs = synth.conformer_varset(dims[0], dims[1], dims[2], dims[3], frontend=dims[4])
+        mask = synth.ppq_mask(specs, frac, 3) if frac is not None else np.array([s.is_matrix for s in specs])
+        fm = [choices[i % len(choices)] for i in range(len(specs))]
+        gfs = [omc.fmt(*fm[i]) if mask[i] else None for i in range(len(specs))]
+        sizes = iter([omc.omc_packed_bytes(gfs[i], specs[i].n) for i in range(len(specs)) if mask[i]])
+        lay = synth.make_layout(specs, mask, lambda n: next(sizes))
+        table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gfs[i],
+                      quantized=bool(mask[i])) for i, s in enumerate(specs)]
+        plan = omc.omc_plan_build(omc.make_var_table(table))
+        gen = torch.Generator(device="cuda").manual_seed(5)
+        vals = torch.empty(lay.aux_elems, device="cuda")
+        for i, s in enumerate(specs):
+            a = int(lay.aux_offset[i])
+            vals[a:a + s.n].normal_(0.0, 1.0 / np.sqrt(s.fan_in) if s.is_matrix else 0.02, generator=gen)
+        grads = [torch.empty(lay.aux_elems, device="cuda").normal_(0.0, 1e-3, generator=gen) for _ in range(2)]
+        arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
+        sb = torch.zeros((len(specs), 2), device="cuda")
+        ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+        omc.omc_compress_set(vals, plan, arena, sb, ws)
+        del vals
+        m = torch.zeros(lay.aux_elems, device="cuda")
+        v = torch.zeros(lay.aux_elems, device="cuda") if kind == omc.OMC_ADAM else None
+        state = 8.0 if kind == omc.OMC_MOMENTUM else 16.0
+        alg = sum((2.0 * (1 + sum(fm[i])) / 8.0 + 4.0 + state) * s.n if mask[i] else (12.0 + state) * s.n
+                  for i, s in enumerate(specs))
+        packed = sum(omc.omc_packed_bytes(gfs[i], s.n) for i, s in enumerate(specs) if mask[i])
+        for k in range(3):
+            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 1), ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(steps):
+            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 4), ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        nl = plan.launches
+        ev = omc.HipEvents(2 * nl * steps)
+        for k in range(steps):
+            omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 20), ws, ev,
+                                                  first=k * 2 * nl)
+        torch.cuda.synchronize()
+        kms = [sum(ev.elapsed_ms(k * 2 * nl + 2 * j, k * 2 * nl + 2 * j + 1) for k in range(steps)) / steps for j in range(nl)]
+        res.append({"workload": name, "params": int(sum(s.n for s in specs)), "launches_per_step": plan.launches,
+                    "ms_per_step": ms, "kernel_ms": kms, "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
+                    "frac_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "compressed_param_GBps": packed / (ms * 1e-3) / 1e9})
+        del arena, sb, ws, m, v, grads, plan
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -291,6 +353,7 @@ def main():
                          "measured: no faster than eager launches on this machine")
     ap.add_argument("--gemm-only", action="store_true", help="only the forward GEMM leg (for profiler runs)")
     ap.add_argument("--aggregate-only", action="store_true", help="only the server aggregation leg")
+    ap.add_argument("--configs-only", action="store_true", help="only the leg over the baseline's other step configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device-to-device copy of known size (1 GiB read + 1 GiB written "
                          "per launch) to calibrate profiler byte counters and show the copy ceiling")
@@ -324,6 +387,9 @@ def main():
         return
     if args.gemm_only:
         print(json.dumps({"gemm": gemm_leg(torch, omc, synth)}))
+        return
+    if args.configs_only:
+        print(json.dumps({"other_step_configs": other_configs_leg(torch, omc, synth)}))
         return
     if args.aggregate_only:
         print(json.dumps({"server_aggregation": aggregate_leg(torch, omc, synth, args.blocks)}))
@@ -497,6 +563,8 @@ def main():
     out["server_aggregation"] = aggregate_leg(torch, omc, synth, args.blocks)
     torch.cuda.empty_cache()
     out["paper_formats_sgd"] = formats_leg(torch, omc, synth, args.blocks)
+    torch.cuda.empty_cache()
+    out["other_step_configs"] = other_configs_leg(torch, omc, synth)
     out["forward_gemm"] = gemm_leg(torch, omc, synth)
     if cpu is not None:
         out["cpu_baseline"] = {
