@@ -434,7 +434,10 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
         if (e != hipSuccess) return static_cast<int>(e);
     }
     // 256-row tiles unless they would leave fewer than two workgroups per compute unit
-    const bool small = static_cast<uint64_t>(M / 256) * (N / kBN) < 512;
+#ifndef OMC_GEMM_SMALL_LIMIT
+#define OMC_GEMM_SMALL_LIMIT 512
+#endif
+    const bool small = static_cast<uint64_t>(M / 256) * (N / kBN) < OMC_GEMM_SMALL_LIMIT;
 #define OMC_GEMM_LAUNCH(BM, DEC)                                                                                    \
     do {                                                                                                            \
         if (trans)                                                                                                  \
