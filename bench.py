@@ -345,6 +345,8 @@ def main():
     ap.add_argument("--cpu-sample-blocks", type=int, default=4)
     ap.add_argument("--cpu-iters", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
+    ap.add_argument("--step-only", action="store_true", help="skip the extra legs (set conversions, aggregation, formats, "
+                                                             "other configurations, matrix-core kernels); for profiler runs")
     ap.add_argument("--eager", action="store_true", help="(default) one library call per step")
     ap.add_argument("--clock-warmup-s", type=float, default=0.5,
                     help="seconds of untimed steps before any measurement, so that the GPU clocks have ramped up")
@@ -557,15 +559,16 @@ def main():
     }
     del grads, arena0
     torch.cuda.empty_cache()
-    out["set_conversions"] = set_conversion_leg(torch, omc, wl, n_q, n_f)
-    del wl
-    torch.cuda.empty_cache()
-    out["server_aggregation"] = aggregate_leg(torch, omc, synth, args.blocks)
-    torch.cuda.empty_cache()
-    out["paper_formats_sgd"] = formats_leg(torch, omc, synth, args.blocks)
-    torch.cuda.empty_cache()
-    out["other_step_configs"] = other_configs_leg(torch, omc, synth)
-    out["forward_gemm"] = gemm_leg(torch, omc, synth)
+    if not args.step_only:
+        out["set_conversions"] = set_conversion_leg(torch, omc, wl, n_q, n_f)
+        del wl
+        torch.cuda.empty_cache()
+        out["server_aggregation"] = aggregate_leg(torch, omc, synth, args.blocks)
+        torch.cuda.empty_cache()
+        out["paper_formats_sgd"] = formats_leg(torch, omc, synth, args.blocks)
+        torch.cuda.empty_cache()
+        out["other_step_configs"] = other_configs_leg(torch, omc, synth)
+        out["forward_gemm"] = gemm_leg(torch, omc, synth)
     if cpu is not None:
         out["cpu_baseline"] = {
             "value": cpu["packed_bytes"] / cpu["sec_per_iter"] / 1e9, "unit": "GB/s",
