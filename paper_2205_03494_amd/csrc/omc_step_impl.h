@@ -28,8 +28,20 @@ struct StepArgs {
 };
 
 // Variables kept in fp32 (paper Sec. 2.4, 2.5): the update alone, 16-byte pieces, coalesced.
+// Every stream is touched once per step, so all loads and stores are non-temporal; a batch of
+// kFp32Batch pieces per lane is loaded before any of them is updated (memory-level parallelism is
+// all this loop needs).
+#ifndef OMC_TUNE_FP32_NT
+#define OMC_TUNE_FP32_NT 1
+#endif
+#ifndef OMC_TUNE_FP32_BATCH
+#define OMC_TUNE_FP32_BATCH 4
+#endif
 template <int MODE>
 __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr bool NT = OMC_TUNE_FP32_NT != 0;
+    constexpr int kFp32Batch = OMC_TUNE_FP32_BATCH;
     const PlanItem *items = reinterpret_cast<const PlanItem *>(sa.plan + sa.item_off);
     const PlanVar *vars = reinterpret_cast<const PlanVar *>(sa.plan + sa.var_off);
     const PlanItem it = to_scalar_regs(items[item]);
@@ -42,47 +54,51 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
     const uint64_t n = pv.n;
     const uint64_t begin = static_cast<uint64_t>(it.chunk) * kChunkElems;
     constexpr int kIters = kChunkElems / 256;
-#pragma unroll 4
-    for (int j = 0; j < kIters; ++j) {
-        const uint64_t e = begin + (static_cast<uint64_t>(j) * 64 + lane) * 4;
-        if (e >= n) continue;
-        float xw[4], xg[4], xm[4] = {0, 0, 0, 0}, xv[4] = {0, 0, 0, 0};
-        const bool full = e + 4 <= n;
-        if (full) {
-            const float4 tw = *reinterpret_cast<const float4 *>(w + e);
-            const float4 tg = *reinterpret_cast<const float4 *>(g + e);
-            xw[0] = tw.x; xw[1] = tw.y; xw[2] = tw.z; xw[3] = tw.w;
-            xg[0] = tg.x; xg[1] = tg.y; xg[2] = tg.z; xg[3] = tg.w;
-            if (MODE >= kStepMomentum) {
-                const float4 tm = *reinterpret_cast<const float4 *>(m + e);
-                xm[0] = tm.x; xm[1] = tm.y; xm[2] = tm.z; xm[3] = tm.w;
-            }
-            if (MODE == kStepAdam) {
-                const float4 tv = *reinterpret_cast<const float4 *>(v + e);
-                xv[0] = tv.x; xv[1] = tv.y; xv[2] = tv.z; xv[3] = tv.w;
-            }
-        } else {
-            for (int c = 0; c < 4; ++c) {
-                const bool ok = e + c < n;
-                xw[c] = ok ? w[e + c] : 0.0f;
-                xg[c] = ok ? g[e + c] : 0.0f;
-                if (MODE >= kStepMomentum) xm[c] = ok ? m[e + c] : 0.0f;
-                if (MODE == kStepAdam) xv[c] = ok ? v[e + c] : 0.0f;
-            }
-        }
+    static_assert(kIters % kFp32Batch == 0, "batches tile the chunk");
+    auto ld = [&](const float *p) {
+        const f32x4 *q = reinterpret_cast<const f32x4 *>(p);
+        return NT ? __builtin_nontemporal_load(q) : *q;
+    };
+    auto st = [&](float *p, const f32x4 &x) {
+        f32x4 *q = reinterpret_cast<f32x4 *>(p);
+        if (NT) __builtin_nontemporal_store(x, q); else *q = x;
+    };
+    for (int j0 = 0; j0 < kIters; j0 += kFp32Batch) {
+        const uint64_t e0 = begin + (static_cast<uint64_t>(j0) * 64 + lane) * 4;
+        if (begin + static_cast<uint64_t>(j0 + kFp32Batch) * 256 <= n) {          // the whole batch is inside: wave-uniform
+            f32x4 xw[kFp32Batch], xg[kFp32Batch], xm[kFp32Batch], xv[kFp32Batch];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) xw[c] = apply_update<MODE>(xw[c], xg[c], xm[c], xv[c], sa.oc);
-        if (full) {
-            *reinterpret_cast<float4 *>(w + e) = make_float4(xw[0], xw[1], xw[2], xw[3]);
-            if (MODE >= kStepMomentum) *reinterpret_cast<float4 *>(m + e) = make_float4(xm[0], xm[1], xm[2], xm[3]);
-            if (MODE == kStepAdam) *reinterpret_cast<float4 *>(v + e) = make_float4(xv[0], xv[1], xv[2], xv[3]);
-        } else {
-            for (int c = 0; c < 4; ++c) {
-                if (e + c < n) {
-                    w[e + c] = xw[c];
-                    if (MODE >= kStepMomentum) m[e + c] = xm[c];
-                    if (MODE == kStepAdam) v[e + c] = xv[c];
+            for (int u = 0; u < kFp32Batch; ++u) {
+                const uint64_t e = e0 + static_cast<uint64_t>(u) * 256;
+                xw[u] = ld(w + e);
+                xg[u] = ld(g + e);
+                xm[u] = (MODE >= kStepMomentum) ? ld(m + e) : f32x4{0, 0, 0, 0};
+                xv[u] = (MODE == kStepAdam) ? ld(v + e) : f32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < kFp32Batch; ++u) {
+                const uint64_t e = e0 + static_cast<uint64_t>(u) * 256;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float tm = xm[u][c], tv = xv[u][c];
+                    xw[u][c] = apply_update<MODE>(xw[u][c], xg[u][c], tm, tv, sa.oc);
+                    xm[u][c] = tm;
+                    xv[u][c] = tv;
                 }
+                st(w + e, xw[u]);
+                if (MODE >= kStepMomentum) st(m + e, xm[u]);
+                if (MODE == kStepAdam) st(v + e, xv[u]);
+            }
+            continue;
+        }
+        for (int u = 0; u < kFp32Batch; ++u) {                                     // the variable ends in this batch
+            const uint64_t e = e0 + static_cast<uint64_t>(u) * 256;
+            for (int c = 0; c < 4; ++c) {
+                if (e + c >= n) break;
+                float tm = (MODE >= kStepMomentum) ? m[e + c] : 0.0f, tv = (MODE == kStepAdam) ? v[e + c] : 0.0f;
+                w[e + c] = apply_update<MODE>(w[e + c], g[e + c], tm, tv, sa.oc);
+                if (MODE >= kStepMomentum) m[e + c] = tm;
+                if (MODE == kStepAdam) v[e + c] = tv;
             }
         }
     }
