@@ -31,12 +31,21 @@ __device__ __forceinline__ void copy_fp32_item(const CodecArgs &ca, uint32_t ite
     const float *src = (MODE == kCompress) ? ca.vin + pv.aux_offset : in_arena;
     float *dst = (MODE == kCompress) ? in_arena : ca.vout + pv.aux_offset;
     const uint64_t begin = static_cast<uint64_t>(it.chunk) * kChunkElems;
-    for (int j = 0; j < kChunkElems / 256; ++j) {
-        const uint64_t e = begin + (static_cast<uint64_t>(j) * 64 + lane) * 4;
-        if (e >= pv.n) break;
-        if (e + 4 <= pv.n) {
-            *reinterpret_cast<f32x4 *>(dst + e) = *reinterpret_cast<const f32x4 *>(src + e);
-        } else {
+    constexpr int kBatch = 8;                              // pieces per lane in flight; both streams are touched once
+    for (int j0 = 0; j0 < kChunkElems / 256; j0 += kBatch) {
+        const uint64_t e0 = begin + (static_cast<uint64_t>(j0) * 64 + lane) * 4;
+        if (begin + static_cast<uint64_t>(j0 + kBatch) * 256 <= pv.n) {   // the whole batch is inside: wave-uniform
+            f32x4 x[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+                x[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src + e0 + static_cast<uint64_t>(u) * 256));
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+                __builtin_nontemporal_store(x[u], reinterpret_cast<f32x4 *>(dst + e0 + static_cast<uint64_t>(u) * 256));
+            continue;
+        }
+        for (int u = 0; u < kBatch; ++u) {                   // the variable ends in this batch
+            const uint64_t e = e0 + static_cast<uint64_t>(u) * 256;
             for (int c = 0; c < 4; ++c)
                 if (e + c < pv.n) dst[e + c] = src[e + c];
         }

@@ -39,7 +39,6 @@ struct StepArgs {
 #endif
 template <int MODE>
 __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) {
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
     constexpr bool NT = OMC_TUNE_FP32_NT != 0;
     constexpr int kFp32Batch = OMC_TUNE_FP32_BATCH;
     const PlanItem *items = reinterpret_cast<const PlanItem *>(sa.plan + sa.item_off);
