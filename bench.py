@@ -104,6 +104,24 @@ def cpu_baseline(wl, synth, sample_blocks, iters, threads, gpu_after=None):
                 n_elems=n_elems, packed_bytes=packed_bytes)
 
 
+LEG_WARMUP_S = 0.15
+
+
+def warm(torch, fn, seconds=None):
+    """Untimed calls for `seconds` of wall time: after host-side set-up the GPU runs at reduced clocks for
+    the first tens of milliseconds, and a handful of warm-up calls measures that ramp instead of the kernel."""
+    seconds = LEG_WARMUP_S if seconds is None else seconds
+    t0 = time.perf_counter()
+    k = 0
+    while True:
+        for _ in range(10):
+            fn(k)
+            k += 1
+        torch.cuda.synchronize()
+        if time.perf_counter() - t0 >= seconds:
+            return k
+
+
 def gemm_leg(torch, omc, synth, iters=20):
     """Forward-path dequant-fused GEMM (BASELINE config 5): bf16 activations [8192 x 1024] times S1E4M3
     weights [1024 x 4096], and [8192 x 4096] times [4096 x 1024]; fp32 accumulate and output."""
@@ -119,8 +137,7 @@ def gemm_leg(torch, omc, synth, iters=20):
         omc.omc_compress(W, K * N, gf, True, codes, sb, wsc)
         C = torch.empty((M, N), dtype=torch.float32, device="cuda")
         ws = torch.empty(omc.omc_dequant_gemm_workspace_bytes(M), dtype=torch.uint8, device="cuda")
-        for _ in range(3):
-            omc.omc_dequant_gemm(A, codes, gf, sb, C, M, N, K, ws)
+        warm(torch, lambda k: omc.omc_dequant_gemm(A, codes, gf, sb, C, M, N, K, ws))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(iters):
@@ -135,8 +152,7 @@ def gemm_leg(torch, omc, synth, iters=20):
         del C
         dY = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 13)).view(np.int16)).cuda()
         dX = torch.empty((M, K), dtype=torch.float32, device="cuda")
-        for _ in range(3):
-            omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws)
+        warm(torch, lambda k: omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws))
         e0.record()
         for _ in range(iters):
             omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws)
@@ -149,8 +165,7 @@ def gemm_leg(torch, omc, synth, iters=20):
         del dX
         wsd = torch.empty(omc.omc_dw_update_workspace_bytes(gf, M, N, K), dtype=torch.uint8, device="cuda")
         o = omc.opt(omc.OMC_SGD, 0.01)
-        for _ in range(3):
-            omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd)
+        warm(torch, lambda k: omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd))
         e0.record()
         for _ in range(iters):
             omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd)
@@ -175,8 +190,7 @@ def set_conversion_leg(torch, omc, wl, n_q, n_f, iters=20):
     for name, fn, nbytes in (
             ("compress_set", lambda: omc.omc_compress_set(wl["vals_d"], plan, arena, sb, ws), 5.0 * n_q + 8.0 * n_f),
             ("decompress_set", lambda: omc.omc_decompress_set(arena, plan, sb, out), 5.0 * n_q + 8.0 * n_f)):
-        for _ in range(3):
-            fn()
+        warm(torch, lambda k: fn())
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(iters):
@@ -219,8 +233,7 @@ def aggregate_leg(torch, omc, synth, blocks, R=8, iters=20):
     alg += 4.0 * n_total
     agg = omc.omc_aggregate_plan_build(plans)
     out = torch.empty(vals_d.numel(), device="cuda")
-    for _ in range(3):
-        omc.omc_aggregate_mean(agg, arenas, sbs, out)
+    warm(torch, lambda k: omc.omc_aggregate_mean(agg, arenas, sbs, out))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(iters):
@@ -261,8 +274,7 @@ def formats_leg(torch, omc, synth, blocks, steps=20):
         o = omc.opt(omc.OMC_SGD, 0.01)
         nl = plan.launches
         ev = omc.HipEvents(2 * nl * steps)
-        for k in range(3):
-            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], None, None, o, ws)
+        warm(torch, lambda k: omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], None, None, o, ws))
         for k in range(steps):
             omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], None, None, o, ws, ev, first=k * 2 * nl)
         torch.cuda.synchronize()
@@ -311,19 +323,18 @@ def other_configs_leg(torch, omc, synth, steps=10):
         alg = sum((2.0 * (1 + sum(fm[i])) / 8.0 + 4.0 + state) * s.n if mask[i] else (12.0 + state) * s.n
                   for i, s in enumerate(specs))
         packed = sum(omc.omc_packed_bytes(gfs[i], s.n) for i, s in enumerate(specs) if mask[i])
-        for k in range(3):
-            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 1), ws)
+        t = warm(torch, lambda k: omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 1), ws))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for k in range(steps):
-            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 4), ws)
+            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=t + k + 1), ws)
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
         nl = plan.launches
         ev = omc.HipEvents(2 * nl * steps)
         for k in range(steps):
-            omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 20), ws, ev,
+            omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=t + steps + k + 1), ws, ev,
                                                   first=k * 2 * nl)
         torch.cuda.synchronize()
         kms = [sum(ev.elapsed_ms(k * 2 * nl + 2 * j, k * 2 * nl + 2 * j + 1) for k in range(steps)) / steps for j in range(nl)]
@@ -337,6 +348,7 @@ def other_configs_leg(torch, omc, synth, steps=10):
 
 
 def main():
+    global LEG_WARMUP_S
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
@@ -345,6 +357,7 @@ def main():
     ap.add_argument("--cpu-sample-blocks", type=int, default=4)
     ap.add_argument("--cpu-iters", type=int, default=3)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
+    ap.add_argument("--leg-warmup-s", type=float, default=LEG_WARMUP_S, help="untimed wall time before each extra leg's measurement (profiler runs shorten it)")
     ap.add_argument("--step-only", action="store_true", help="skip the extra legs (set conversions, aggregation, formats, "
                                                              "other configurations, matrix-core kernels); for profiler runs")
     ap.add_argument("--eager", action="store_true", help="(default) one library call per step")
@@ -360,6 +373,7 @@ def main():
                     help="only run a plain device-to-device copy of known size (1 GiB read + 1 GiB written "
                          "per launch) to calibrate profiler byte counters and show the copy ceiling")
     args = ap.parse_args()
+    LEG_WARMUP_S = args.leg_warmup_s
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
                  "(no collectives or sharding exist in this library)")
