@@ -27,6 +27,8 @@
 // barrier per K step.  The row sums of A are taken inside the kernel from the staged pieces.
 // omc_dequant_gemm_dx (dX = dY * Wbar^T) is the same kernel with the codes read along the other
 // direction (TRANS): 16 consecutive codes of a weight row per thread, decoded into two k-chunks.
+// A second kernel serves grids of at most one tile per compute unit with a long contraction: 16 waves per
+// workgroup, eight that only multiply, four that only stage A and four that only stage W (see there).
 #include <hip/hip_runtime.h>
 #include "omc_internal.h"
 
@@ -399,6 +401,289 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
     }
 }
 
+// ---- wave-specialised variant --------------------------------------------------------------------
+// One workgroup of 16 waves per compute unit and 256 x 128 tile.  Waves 0-7 only multiply (64 x 64 each:
+// 2 x 2 MFMA tiles, 64 accumulator registers), waves 8-11 only stage A (global -> LDS, row sums on the
+// way), waves 12-15 only stage W (global -> decode -> LDS).  No wave carries both instruction streams,
+// so the staging work of a K step runs beside the matrix instructions of another instead of after
+// them.  Three LDS stages: stage j is complete at barrier j, its fragments are read during round j+1
+// (under the matrix instructions of stage j-1) and multiplied during round j+2; the stagers load three
+// K steps ahead in three register sets.  One workgroup barrier per K step, reached by all 16 waves.
+// Columns of the tile are kept in LDS so that a multiplying wave's 64 columns are 64 consecutive slots:
+// column c = 64 h + 2 cg + i sits at slot 64 h + 32 i + cg, and a lane ends up with two adjacent
+// columns of C (8-byte stores, 256 contiguous bytes per row and wave).
+constexpr int kWsStages = 3;
+constexpr int kWsBM = 256;
+constexpr int kWsStageBytes = 4 * kWsBM * 16 + 4 * kWChunkBytes;
+
+__device__ __forceinline__ uint32_t ws_slot_of_column(uint32_t c) {          // c in [0, 128)
+    return (c & 64u) + 32u * (c & 1u) + ((c & 63u) >> 1);
+}
+
+template <int DEC, bool HW, bool TRANS>
+__device__ __forceinline__ void dequant_gemm_ws_body(const uint16_t *__restrict__ A, const uint32_t *__restrict__ codes,
+                                                     uint64_t total_dwords, const FmtParams &fp,
+                                                     const float *__restrict__ sb, float *__restrict__ C, uint32_t N,
+                                                     uint32_t K, uint8_t *lds) {
+    constexpr bool BYTE = DEC != 0;
+    constexpr int kAChunkBytes = kWsBM * 16;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);        // the role is the same for the whole wave
+    const uint32_t m0 = blockIdx.x * kWsBM, n0 = blockIdx.y * kBN;
+    const uint32_t nk = K / kBK;
+    float *rowsum_lds = reinterpret_cast<float *>(lds);                      // reused once the K loop is over
+
+    if (wave < 8) {
+        // ---- multiplying waves ----------------------------------------------------------------------
+        const uint32_t wm = wave >> 1, wh = wave & 1u;
+        const uint32_t f_row = lane & 31u, f_half = lane >> 5;
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+        struct Frags {
+            bf16x8 a[2], b[2];
+        };
+        auto read_frags = [&](const uint8_t *st, int ks, Frags &f) {
+            const uint32_t chunk = 2 * ks + f_half;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const uint32_t row = 64 * wm + 32 * mi + f_row;
+                f.a[mi] = *reinterpret_cast<const bf16x8 *>(st + chunk * kAChunkBytes + (OMC_A_SLOT(row, chunk) << 4));
+            }
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                f.b[ni] = *reinterpret_cast<const bf16x8 *>(st + 4 * kAChunkBytes + chunk * kWChunkBytes +
+                                                            ((64u * wh + 32u * ni + f_row) << 4));
+        };
+        auto multiply_frags = [&](const Frags &f) {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+        };
+        Frags f0, f1;
+        __syncthreads();                                    // barrier 0: stage 0 is complete
+        read_frags(lds, 0, f0);
+        read_frags(lds, 1, f1);
+        __syncthreads();                                    // barrier 1
+        uint32_t nxt = kWsStageBytes;                       // LDS offset of stage j - 1
+        for (uint32_t j = 2; j < nk + 2; ++j) {
+            const bool more = j - 1 < nk;
+            multiply_frags(f0);
+            if (more) read_frags(lds + nxt, 0, f0);
+            multiply_frags(f1);
+            if (more) read_frags(lds + nxt, 1, f1);
+            nxt = (nxt == (kWsStages - 1) * kWsStageBytes) ? 0u : nxt + kWsStageBytes;
+            __syncthreads();                                // barrier j
+        }
+        __syncthreads();                                    // row sums published
+        const float s = sb ? sb[0] : 1.0f;
+        const float b = sb ? sb[1] : 0.0f;
+        f32x4 rs[2][4];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t row = 64 * wm + 32 * mi + 8 * g + 4 * f_half;
+                rs[mi][g] = sb ? *reinterpret_cast<const f32x4 *>(rowsum_lds + row) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            }
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t row = m0 + 64 * wm + 32 * mi + 8 * (v >> 2) + 4 * f_half + (v & 3);
+                const float add = sb ? b * rs[mi][v >> 2][v & 3] : 0.0f;
+                f32x2 out;
+                out[0] = s * acc[mi][0][v] + add;
+                out[1] = s * acc[mi][1][v] + add;
+                __builtin_nontemporal_store(out, reinterpret_cast<f32x2 *>(C + static_cast<uint64_t>(row) * N + n0 + 64 * wh + 2 * f_row));
+            }
+        }
+        return;
+    }
+
+    const uint32_t pt = tid & 255u;                         // thread within its group of four staging waves
+    if (wave < 12) {
+        // ---- waves that stage A ---------------------------------------------------------------------
+        u32x4 ra[kWsStages][4];
+        float rsum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+        auto load_a = [&](u32x4 (&r)[4], uint32_t k0) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t q = pt + 256 * p, row = q >> 2, chunk = q & 3u;
+                r[p] = *reinterpret_cast<const u32x4 *>(A + static_cast<uint64_t>(m0 + row) * K + k0 + 8 * chunk);
+            }
+        };
+        auto store_a = [&](const u32x4 (&r)[4], uint8_t *st) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t q = pt + 256 * p, row = q >> 2, chunk = q & 3u;
+                *reinterpret_cast<u32x4 *>(st + chunk * kAChunkBytes + (OMC_A_SLOT(row, chunk) << 4)) = r[p];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = r[p][i];             // (a bit_cast straight from the vector element reads element 0)
+                    rsum[p] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), ones, rsum[p], false);
+                }
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < kWsStages; ++u)
+            if (static_cast<uint32_t>(u) < nk) load_a(ra[u], u * kBK);
+        uint32_t j = 0;
+        for (; j + kWsStages <= nk; j += kWsStages) {
+#pragma unroll
+            for (int u = 0; u < kWsStages; ++u) {
+                store_a(ra[u], lds + u * kWsStageBytes);
+                if (j + u + kWsStages < nk) load_a(ra[u], (j + u + kWsStages) * kBK);
+                __syncthreads();                            // barrier j + u
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kWsStages - 1; ++u)
+            if (j + u < nk) {
+                store_a(ra[u], lds + u * kWsStageBytes);
+                __syncthreads();
+            }
+        __syncthreads();                                    // barriers nk and nk + 1: the multiplying waves drain
+        __syncthreads();
+        if (sb) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                float t = rsum[p];
+                t += __shfl_xor(t, 1);
+                t += __shfl_xor(t, 2);
+                if ((pt & 3u) == 0) rowsum_lds[(pt >> 2) + 64 * p] = t;
+            }
+        }
+        __syncthreads();                                    // row sums published
+        return;
+    }
+
+    // ---- waves that stage W -----------------------------------------------------------------------------
+    {
+        const uint32_t pw = wave - 12u;
+        const uint32_t w_h = lane & 1u, w_cg = lane >> 1;
+        const uint32_t w_kg = 2 * pw + w_h;
+        const uint64_t w_col = n0 + 4 * w_cg;
+        const uint32_t t_slot = pt & 127u, t_h = pt >> 7;
+        const uint64_t t_row = n0 + (t_slot & 64u) + 2 * (t_slot & 31u) + ((t_slot >> 5) & 1u);
+        struct WRegs {
+            uint32_t raw[4][3], off[4];
+        };
+        WRegs rw[kWsStages];
+        auto load_w = [&](WRegs &r, uint32_t k0) {
+            if (TRANS && BYTE) {                            // the thread's 16 codes are one aligned 16-byte piece
+                const u32x4 t = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(codes) + t_row * K + k0 + 16 * t_h);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    r.raw[rr][0] = t[rr];
+                    r.off[rr] = 0;
+                }
+                return;
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const uint64_t e = TRANS ? t_row * K + k0 + 16 * t_h + 4 * rr
+                                         : static_cast<uint64_t>(k0 + 4 * w_kg + rr) * N + w_col;
+                load_codes4<BYTE>(codes, total_dwords, e, fp.bits, r.raw[rr], r.off[rr]);
+            }
+        };
+        auto store_column = [&](uint8_t *st, int i, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) {
+            uint8_t *ldsW = st + 4 * kAChunkBytes;
+            u32x2 out;
+            out[0] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);   // bf16(v0) | bf16(v1) << 16
+            out[1] = __builtin_amdgcn_perm(v3, v2, 0x07060302u);
+            const uint32_t slot = ws_slot_of_column(4 * w_cg + i);
+            *reinterpret_cast<u32x2 *>(ldsW + pw * kWChunkBytes + (slot << 4) + 8u * w_h) = out;
+        };
+        auto store_w = [&](const WRegs &r, uint8_t *st) {
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {
+                if (TRANS) {                                // part = group of four consecutive k-values
+                    uint32_t v[4];
+                    if (HW) {
+                        const f32x2 c01 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[part][0]), false);
+                        const f32x2 c23 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[part][0]), true);
+                        v[0] = __float_as_uint(c01[0]); v[1] = __float_as_uint(c01[1]);
+                        v[2] = __float_as_uint(c23[0]); v[3] = __float_as_uint(c23[1]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            v[i] = decode_bits(code_top_of<BYTE>(r.raw[part], r.off[part], fp.bits, i), fp);
+                    }
+                    uint8_t *ldsW = st + 4 * kAChunkBytes;
+                    u32x2 out;
+                    out[0] = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);
+                    out[1] = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
+                    *reinterpret_cast<u32x2 *>(ldsW + (2u * t_h + (part >> 1)) * kWChunkBytes + (t_slot << 4) + 8u * (part & 1)) = out;
+                } else if (HW) {
+                    if (part & 1) continue;                 // the hardware conversion yields two columns at a time
+                    f32x2 c[4];
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        c[rr] = (part == 0) ? __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[rr][0]), false)
+                                            : __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[rr][0]), true);
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj)
+                        store_column(st, part + jj, __float_as_uint(c[0][jj]), __float_as_uint(c[1][jj]),
+                                     __float_as_uint(c[2][jj]), __float_as_uint(c[3][jj]));
+                } else {
+                    uint32_t v[4];
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        v[rr] = decode_bits(code_top_of<BYTE>(r.raw[rr], r.off[rr], fp.bits, part), fp);
+                    store_column(st, part, v[0], v[1], v[2], v[3]);
+                }
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < kWsStages; ++u)
+            if (static_cast<uint32_t>(u) < nk) load_w(rw[u], u * kBK);
+        uint32_t j = 0;
+        for (; j + kWsStages <= nk; j += kWsStages) {
+#pragma unroll
+            for (int u = 0; u < kWsStages; ++u) {
+                store_w(rw[u], lds + u * kWsStageBytes);
+                if (j + u + kWsStages < nk) load_w(rw[u], (j + u + kWsStages) * kBK);
+                __syncthreads();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kWsStages - 1; ++u)
+            if (j + u < nk) {
+                store_w(rw[u], lds + u * kWsStageBytes);
+                __syncthreads();
+            }
+        __syncthreads();
+        __syncthreads();
+        __syncthreads();
+    }
+}
+
+template <int DEC, bool TRANS>
+__global__ __launch_bounds__(1024, 1) void dequant_gemm_ws_kernel(const uint16_t *__restrict__ A, const uint32_t *__restrict__ codes,
+                                                                  uint64_t total_dwords, FmtParams fp,
+                                                                  const float *__restrict__ sb, float *__restrict__ C,
+                                                                  uint32_t M, uint32_t N, uint32_t K,
+                                                                  const uint32_t *__restrict__ flags) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kWsStages * kWsStageBytes];
+    (void)M;
+    if (DEC == 2) {
+        const bool top = __any(flags[threadIdx.x & 63u] != 0);
+        if (!top) {
+            dequant_gemm_ws_body<1, true, TRANS>(A, codes, total_dwords, fp, sb, C, N, K, lds);
+            return;
+        }
+    }
+    dequant_gemm_ws_body<(DEC == 0 ? 0 : 1), false, TRANS>(A, codes, total_dwords, fp, sb, C, N, K, lds);
+}
+
 // DEC 2 = byte codes of S1E4M3 / bias 7: hardware conversion unless the pre-pass found a top code.
 template <int BM, int DEC, bool TRANS>
 __global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
@@ -447,7 +732,29 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
             dequant_gemm_kernel<BM, DEC, false><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, \
                                                                                              C, M, N, K, flags);    \
     } while (0)
-    if (!small) {
+    // At most one 256-row tile per compute unit and a long contraction: the wave-specialised kernel (its
+    // prologue and C stores are not covered by another workgroup, so it needs the long K loop to pay off).
+#ifndef OMC_GEMM_WS_MIN_K
+#define OMC_GEMM_WS_MIN_K 2048
+#endif
+#ifndef OMC_GEMM_WS_MAX_TILES
+#define OMC_GEMM_WS_MAX_TILES 256
+#endif
+    if (K >= OMC_GEMM_WS_MIN_K && static_cast<uint64_t>(M / 256) * (N / kBN) <= OMC_GEMM_WS_MAX_TILES) {
+#define OMC_GEMM_WS_LAUNCH(DEC)                                                                                      \
+    do {                                                                                                            \
+        if (trans)                                                                                                  \
+            dequant_gemm_ws_kernel<DEC, true><<<dim3(M / 256, N / kBN), dim3(1024), 0, st>>>(A, c, total_dwords, fp, sb, \
+                                                                                             C, M, N, K, flags);    \
+        else                                                                                                        \
+            dequant_gemm_ws_kernel<DEC, false><<<dim3(M / 256, N / kBN), dim3(1024), 0, st>>>(A, c, total_dwords, fp, sb, \
+                                                                                              C, M, N, K, flags);   \
+    } while (0)
+        if (dec == 2) OMC_GEMM_WS_LAUNCH(2);
+        else if (dec == 1) OMC_GEMM_WS_LAUNCH(1);
+        else OMC_GEMM_WS_LAUNCH(0);
+#undef OMC_GEMM_WS_LAUNCH
+    } else if (!small) {
         if (dec == 2) OMC_GEMM_LAUNCH(256, 2);
         else if (dec == 1) OMC_GEMM_LAUNCH(256, 1);
         else OMC_GEMM_LAUNCH(256, 0);

@@ -29,7 +29,7 @@ def check(C, ref, rows):
 
 
 @pytest.mark.parametrize("EM", [(4, 3), (5, 2), (3, 4), (2, 3), (3, 7), (8, 7), (4, 3, 4)])
-@pytest.mark.parametrize("shape", [(256, 128, 32), (256, 256, 96), (512, 128, 160)])
+@pytest.mark.parametrize("shape", [(256, 128, 32), (256, 256, 96), (512, 128, 160), (256, 128, 2048), (512, 256, 2112)])
 def test_small_shapes_all_rows(EM, shape):
     of, gf = pair(*EM)
     M, N, K = shape
@@ -73,21 +73,23 @@ def test_config5_shapes_sampled_rows(shape):
         assert rel < 1e-5
 
 
+@pytest.mark.parametrize("K", [256, 2048])                  # 2048: the kernel for long contractions on small grids
 @pytest.mark.parametrize("top_at", [None, 0, -1, 12345])
-def test_every_byte_code_exact_with_and_without_the_top_code(top_at):
+def test_every_byte_code_exact_with_and_without_the_top_code(top_at, K):
     """S1E4M3 / bias 7 takes the hardware FP8 conversion unless the weights hold a top code (value 480);
     the pre-pass must find one anywhere in the stream, and both decodes must give the exact code values."""
     of, gf = pair(4, 3)
-    M, N, K = 256, 128, 256
+    M, N = 256, 128
     A = np.zeros((M, K), np.float32)
-    A[np.arange(M), np.arange(M) % K] = 1.0
+    pick = (np.arange(M) * 7 + 3) % K
+    A[np.arange(M), pick] = 1.0
     codes = ((np.arange(K * N, dtype=np.int64) * 37 + 11) % 254).astype(np.uint32)
     codes = np.where(codes >= 127, codes + 1, codes)          # 0..126, 128..254: no top code, both signs, subnormals
     if top_at is not None:
         codes[top_at] = 0x7F if top_at != -1 else 0xFF
     W = orc.decode(codes, of)
     C = run_gemm(synth.to_bf16_bits(A.ravel()), orc.pack(codes, 8), gf, None, M, N, K)
-    want = W.reshape(K, N)[np.arange(M) % K]
+    want = W.reshape(K, N)[pick]
     assert np.array_equal(C, want)
 
 
@@ -100,7 +102,7 @@ def run_gemm_dx(dY_bits, packed, gf, sb, M, N, K):
 
 
 @pytest.mark.parametrize("EM", [(4, 3), (5, 2), (2, 3), (3, 7), (8, 7), (4, 3, 4)])
-@pytest.mark.parametrize("shape", [(256, 32, 128), (256, 96, 256), (512, 160, 128)])
+@pytest.mark.parametrize("shape", [(256, 32, 128), (256, 96, 256), (512, 160, 128), (256, 2048, 128), (512, 2112, 256)])
 def test_dx_small_shapes_all_rows(EM, shape):
     of, gf = pair(*EM)
     M, N, K = shape
@@ -114,20 +116,22 @@ def test_dx_small_shapes_all_rows(EM, shape):
     check(dX, orc.dequant_gemm_dx(dY, packed, of, None, M, N, K, threads=8), (0, M))
 
 
+@pytest.mark.parametrize("N", [64, 2048])                   # 2048: the kernel for long contractions on small grids
 @pytest.mark.parametrize("top_at", [None, 777])
-def test_dx_identity_pattern_pins_the_transposed_layout(top_at):
+def test_dx_identity_pattern_pins_the_transposed_layout(top_at, N):
     # dY = one-hot rows: dX must reproduce columns of W exactly, with and without a top code (both decodes)
     of, gf = pair(4, 3)
-    M, N, K = 256, 64, 128
+    M, K = 256, 128
     dY = np.zeros((M, N), np.float32)
-    dY[np.arange(M), np.arange(M) % N] = 1.0
+    pick = (np.arange(M) * 5 + 1) % N
+    dY[np.arange(M), pick] = 1.0
     codes = ((np.arange(K * N, dtype=np.int64) * 37 + 11) % 254).astype(np.uint32)
     codes = np.where(codes >= 127, codes + 1, codes)
     if top_at is not None:
         codes[top_at] = 0x7F
     W = orc.decode(codes, of).reshape(K, N)
     dX = run_gemm_dx(synth.to_bf16_bits(dY.ravel()), orc.pack(codes, 8), gf, None, M, N, K)
-    want = W[:, np.arange(M) % N].T
+    want = W[:, pick].T
     assert np.array_equal(dX, want)
 
 
@@ -146,7 +150,7 @@ def test_dx_config5_shapes_sampled_rows(shape):
         assert rel < 1e-5
 
 
-@pytest.mark.parametrize("shape", [(256, 128, 32), (512, 256, 160), (256, 128, 4096)])
+@pytest.mark.parametrize("shape", [(256, 128, 32), (512, 256, 160), (256, 128, 4096), (256, 2048, 128)])
 def test_large_offset_makes_the_row_sum_term_count(shape):
     """With the fitted (s, b) of zero-mean weights b is tiny and the b * rowsum(A) term hides inside the tolerance;
     a hand-made pair with a large offset makes both GEMMs depend on their row sums."""
