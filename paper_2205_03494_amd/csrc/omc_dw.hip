@@ -19,6 +19,7 @@ namespace omc {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kDwBChunk = kDwCols * 16;
 
@@ -253,6 +254,154 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
     dw_finish_wave<ROWS, MODE>(a, acc, k0t, n0, lane, wave, block);
 }
 
+// ---- wave-specialised variant (at most one tile per compute unit, long contraction) ---------------
+// 16 waves: waves 0-7 only multiply (64 x 64 of the tile each), waves 8-15 only stage: each thread of
+// them brings in one 4 x 4 patch of X per step, the threads of waves 12-15 also one patch of dY.  Three LDS
+// stages; stage j is complete at barrier j, its fragments are read during round j + 1 and multiplied
+// during round j + 2; global loads run three steps ahead.  Tile columns sit in LDS so that a multiplying
+// wave's 64 columns are consecutive slots (column 64 h + 2 q + i at slot 64 h + 32 i + q).  The accumulators
+// are always parked, in the layout of the four-wave kernel, and the slab kernels do the update.
+constexpr int kDwWsStages = 3;
+constexpr int kDwWsStageBytes = 4 * 256 * 16 + 4 * kDwBChunk;
+
+__global__ __launch_bounds__(1024, 1) void dw_update_ws_kernel(DwArgs a) {
+    constexpr int kDwAChunk = 256 * 16;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kDwWsStages * kDwWsStageBytes];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t k0t = blockIdx.x * 256, n0 = blockIdx.y * kDwCols;
+    const uint32_t K = a.K, N = a.N;
+    const uint32_t nm = a.M / kDwStep / a.nsplit;           // this workgroup's share of the contraction, in steps
+    const uint32_t m_begin = blockIdx.z * nm * kDwStep;
+
+    if (wave < 8) {
+        const uint32_t wm = wave >> 1, wh = wave & 1u;
+        const uint32_t f_row = lane & 31u, f_half = lane >> 5;
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+        struct Frags {
+            bf16x8 a[2], b[2];
+        };
+        auto read_frags = [&](const uint8_t *st, int ks, Frags &f) {
+            const uint32_t chunk = 2 * ks + f_half;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const uint32_t row = 64 * wm + 32 * mi + f_row;
+                f.a[mi] = *reinterpret_cast<const bf16x8 *>(st + chunk * kDwAChunk + (dw_a_slot(row, chunk) << 4));
+            }
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                f.b[ni] = *reinterpret_cast<const bf16x8 *>(st + 4 * kDwAChunk + chunk * kDwBChunk +
+                                                            ((64u * wh + 32u * ni + f_row) << 4));
+        };
+        auto multiply_frags = [&](const Frags &f) {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+        };
+        Frags f0, f1;
+        __syncthreads();                                    // barrier 0: stage 0 is complete
+        read_frags(lds, 0, f0);
+        read_frags(lds, 1, f1);
+        __syncthreads();                                    // barrier 1
+        uint32_t nxt = kDwWsStageBytes;                     // LDS offset of stage j - 1
+        for (uint32_t j = 2; j < nm + 2; ++j) {
+            const bool more = j - 1 < nm;
+            multiply_frags(f0);
+            if (more) read_frags(lds + nxt, 0, f0);
+            multiply_frags(f1);
+            if (more) read_frags(lds + nxt, 1, f1);
+            nxt = (nxt == (kDwWsStages - 1) * kDwWsStageBytes) ? 0u : nxt + kDwWsStageBytes;
+            __syncthreads();                                // barrier j
+        }
+        // park: element (tile row, column c) goes where the four-wave kernel's lane (row's wave, c / 4) puts it
+        const uint32_t block = blockIdx.y * gridDim.x + blockIdx.x;
+        constexpr uint32_t kTileFloats = 256 * kDwCols;
+        float *mine = a.partials + (static_cast<uint64_t>(block) * a.nsplit + blockIdx.z) * kTileFloats;
+        const uint32_t owner = 64 * wm + 32 * f_half + 16 * wh + (f_row >> 1);
+        const uint32_t sub = 2 * (f_row & 1u);
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                __builtin_nontemporal_store(f32x2{acc[mi][0][v], acc[mi][1][v]},
+                                            reinterpret_cast<f32x2 *>(mine + (static_cast<uint32_t>(mi * 16 + v) * 256 + owner) * 4 + sub));
+        return;
+    }
+
+    // ---- staging waves ---------------------------------------------------------------------------------
+    const uint32_t pt = tid - 512u;
+    const bool does_y = wave >= 12;
+    const uint32_t x_kq = (pt >> 1) & 63u, x_mg = 2 * (pt >> 7) + (pt & 1u);
+    const uint32_t wt = tid & 255u;
+    const uint32_t y_nq = wt & 31u, y_mg = wt >> 5;
+    struct Regs {
+        u32x2 x[4], y[4];
+    };
+    Regs r[kDwWsStages];
+    auto load_stage = [&](Regs &g, uint32_t m0) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            g.x[rr] = *reinterpret_cast<const u32x2 *>(a.X + static_cast<uint64_t>(m0 + 4 * x_mg + rr) * K + k0t + 4 * x_kq);
+        if (!does_y) return;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            g.y[rr] = *reinterpret_cast<const u32x2 *>(a.dY + static_cast<uint64_t>(m0 + 4 * y_mg + rr) * N + n0 + 4 * y_nq);
+    };
+    // column i of a 4 x 4 patch of bf16 (rows = consecutive m): the four values as 8 bytes
+    auto patch_column = [&](const u32x2 (&rows)[4], int i) -> u32x2 {
+        const int d = i >> 1;
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        u32x2 out;
+        out[0] = __builtin_amdgcn_perm(rows[1][d], rows[0][d], sel);
+        out[1] = __builtin_amdgcn_perm(rows[3][d], rows[2][d], sel);
+        return out;
+    };
+    auto store_stage = [&](const Regs &g, uint8_t *st) {
+        const uint32_t xc = x_mg >> 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t row = 64 * i + x_kq;
+            *reinterpret_cast<u32x2 *>(st + xc * kDwAChunk + (dw_a_slot(row, xc) << 4) + 8u * (x_mg & 1u)) = patch_column(g.x, i);
+        }
+        if (!does_y) return;
+        const uint32_t yc = y_mg >> 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t c = 4 * y_nq + i;
+            const uint32_t slot = (c & 64u) + 32u * (c & 1u) + ((c & 63u) >> 1);
+            *reinterpret_cast<u32x2 *>(st + 4 * kDwAChunk + yc * kDwBChunk + (slot << 4) + 8u * (y_mg & 1u)) = patch_column(g.y, i);
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < kDwWsStages; ++u)
+        if (static_cast<uint32_t>(u) < nm) load_stage(r[u], m_begin + u * kDwStep);
+    uint32_t j = 0;
+    for (; j + kDwWsStages <= nm; j += kDwWsStages) {
+#pragma unroll
+        for (int u = 0; u < kDwWsStages; ++u) {
+            store_stage(r[u], lds + u * kDwWsStageBytes);
+            if (j + u + kDwWsStages < nm) load_stage(r[u], m_begin + (j + u + kDwWsStages) * kDwStep);
+            __syncthreads();                                // barrier j + u
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kDwWsStages - 1; ++u)
+        if (j + u < nm) {
+            store_stage(r[u], lds + u * kDwWsStageBytes);
+            __syncthreads();
+        }
+    __syncthreads();                                        // barriers nm and nm + 1: the multiplying waves drain
+    __syncthreads();
+}
+
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void dw_finalize_kernel(const Partial *__restrict__ ws, uint32_t nparts, uint64_t n,
                                                               int use_pvt, float *__restrict__ sb) {
@@ -269,8 +418,15 @@ static size_t dw_fit_bytes(uint32_t N, uint32_t K) {
 // that already gives two workgroups per compute unit; otherwise split the M rows (each split at least
 // 512 rows, at most 8 splits) and, if that is still not enough, take 128-row tiles.
 DwConfig dw_config(uint32_t M, uint32_t N, uint32_t K) {
-    DwConfig c{256, 1};
+    DwConfig c{256, 1, 0};
     const uint64_t tiles256 = static_cast<uint64_t>(K / 256) * (N / kDwCols);
+    // At most one workgroup per compute unit with at least 2048 rows of the contraction each, and at least
+    // half of the compute units busy: the wave-specialised kernel.
+    if (K % 256 == 0 && tiles256 <= 256) {
+        uint32_t sp = 1;
+        while (tiles256 * (2 * sp) <= 256 && sp < 8 && M % (2 * sp * kDwStep) == 0 && M / (2 * sp) >= 2048) sp *= 2;
+        if (M / sp >= 2048 && tiles256 * sp >= 128) return DwConfig{256, sp, 1};
+    }
     auto splits_for = [&](uint64_t tiles) {
         uint32_t sp = 1;
         while (tiles * sp < 512 && sp < 8 && M % (2 * sp * kDwStep) == 0 && M / (2 * sp) >= 512) sp *= 2;
@@ -304,7 +460,7 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
     a.dW_out = dW_out;
     a.ws = reinterpret_cast<Partial *>(w8);
     a.partials = reinterpret_cast<float *>(w8 + fit_bytes);
-    a.park = (cfg.nsplit > 1 || !byte_codes) ? 1u : 0u;
+    a.park = (cfg.nsplit > 1 || !byte_codes || cfg.ws) ? 1u : 0u;
     a.nsplit = cfg.nsplit;
     a.fp = fp;
     a.oc = OptConst{opt.lr, opt.momentum, opt.beta1, opt.beta2, opt.eps, opt.one_minus_beta1,
@@ -319,7 +475,8 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
         else if (opt.kind == OMC_MOMENTUM) dw_update_kernel<ROWS, kStepMomentum><<<grid, dim3(256), 0, st>>>(a); \
         else dw_update_kernel<ROWS, kStepAdam><<<grid, dim3(256), 0, st>>>(a);                    \
     } while (0)
-    if (cfg.rows == 128) OMC_DW_LAUNCH(128);
+    if (cfg.ws) dw_update_ws_kernel<<<grid, dim3(1024), 0, st>>>(a);
+    else if (cfg.rows == 128) OMC_DW_LAUNCH(128);
     else OMC_DW_LAUNCH(256);
 #undef OMC_DW_LAUNCH
     hipError_t e = hipGetLastError();
@@ -344,7 +501,7 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
 
 size_t dw_workspace_bytes(uint32_t bits, uint32_t M, uint32_t N, uint32_t K) {
     const DwConfig cfg = dw_config(M, N, K);
-    const bool park = cfg.nsplit > 1 || bits != 8;
+    const bool park = cfg.nsplit > 1 || bits != 8 || cfg.ws;
     const size_t partial_bytes = park ? static_cast<size_t>(cfg.nsplit) * K * N * sizeof(float) : 0;
     return dw_fit_bytes(N, K) + partial_bytes;
 }

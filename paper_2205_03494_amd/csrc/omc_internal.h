@@ -142,6 +142,7 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
 struct DwConfig {
     uint32_t rows;     // weight rows per tile: 256 or 128
     uint32_t nsplit;   // workgroups per tile along the contraction
+    uint32_t ws;       // 1: the 16-wave kernel with separate multiplying and staging waves (rows = 256, always parks)
 };
 DwConfig dw_config(uint32_t M, uint32_t N, uint32_t K);
 size_t dw_workspace_bytes(uint32_t bits, uint32_t M, uint32_t N, uint32_t K);

@@ -116,3 +116,10 @@ def test_fp32_as_a_format_is_plain_sgd():
 def test_large_matrix_takes_the_in_kernel_epilogue_on_256_row_tiles():
     # 4096 x 4096 weights = 512 tiles of 256 x 128: no split, the update runs in the GEMM kernel's epilogue
     run_case((4, 3), 64, 4096, 4096, 1, 0.05, steps=1, rows=(0, 2000, 4080))
+
+
+@pytest.mark.parametrize("EM,kind,lr", [((4, 3), 0, 0.05), ((3, 7), 1, 0.05), ((2, 3), 2, 1e-3)])
+def test_long_contraction_on_a_small_grid_takes_the_sixteen_wave_kernel(EM, kind, lr):
+    """64 tiles and 4096 rows: two workgroups of 16 waves per tile (eight multiplying, eight staging), each over
+    2048 rows; the accumulators pass through the workspace in the four-wave kernel's layout."""
+    run_case(EM, 4096, 2048, 1024, kind, lr, steps=2, rows=(0, 16, 320, 1008))
