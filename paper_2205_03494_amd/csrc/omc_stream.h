@@ -829,17 +829,29 @@ __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ pa
     float tmin = __builtin_huge_valf(), tmax = -__builtin_huge_valf();
     bool finite = true;
     const uint32_t total = nparts + (tail ? 1u : 0u);
-    for (uint32_t i = tid; i < total; i += 64 * NW) {
-        const Partial p = (i < nparts) ? parts[i] : *tail;
-        finite = finite && isfinite(p.sV);
-        if (finite) {
-            sV = dd_add(sV, p.sV);
-            sT = dd_add(sT, p.sT);
-            sVT = dd_add(sVT, p.sVT);
-            sTT = dd_add(sTT, p.sTT);
+    // a lane's partials are fetched eight at a time before they are added (same order of additions; the
+    // loads of a batch are in flight together instead of one memory round trip per partial)
+    constexpr uint32_t kBatch = 8, kStride = 64 * NW;
+    for (uint32_t i0 = tid; i0 < total; i0 += kBatch * kStride) {
+        Partial p[kBatch];
+#pragma unroll
+        for (uint32_t u = 0; u < kBatch; ++u) {
+            const uint32_t i = i0 + u * kStride;
+            if (i < total) p[u] = (i < nparts) ? parts[i] : *tail;
         }
-        tmin = fminf(tmin, p.tmin);
-        tmax = fmaxf(tmax, p.tmax);
+#pragma unroll
+        for (uint32_t u = 0; u < kBatch; ++u) {
+            if (i0 + u * kStride >= total) break;
+            finite = finite && isfinite(p[u].sV);
+            if (finite) {
+                sV = dd_add(sV, p[u].sV);
+                sT = dd_add(sT, p[u].sT);
+                sVT = dd_add(sVT, p[u].sVT);
+                sTT = dd_add(sTT, p[u].sTT);
+            }
+            tmin = fminf(tmin, p[u].tmin);
+            tmax = fmaxf(tmax, p[u].tmax);
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
