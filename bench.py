@@ -355,7 +355,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--blocks", type=int, default=17, help="Conformer blocks (17 = the benchmark workload)")
     ap.add_argument("--cpu-sample-blocks", type=int, default=4)
-    ap.add_argument("--cpu-iters", type=int, default=3)
+    ap.add_argument("--cpu-iters", type=int, default=6)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
     ap.add_argument("--leg-warmup-s", type=float, default=LEG_WARMUP_S, help="untimed wall time before each extra leg's measurement (profiler runs shorten it)")
     ap.add_argument("--step-only", action="store_true", help="skip the extra legs (set conversions, aggregation, formats, "
@@ -563,8 +563,8 @@ def main():
                    "launch": "one library call per step" if graph is None else
                              "HIP graph of two steps (one per gradient buffer), replayed; checked against eager launches",
 
-                   "kernel_ms": {"step_kernel<8,sgd>": kern_ms[0],
-                                 "step_fp32_kernel<sgd>": kern_ms[1] if nl > 2 else None,
+                   "kernel_ms": {"step_kernel<8,sgd> (fp32 variables ride along)": kern_ms[0],
+                                 "tail_kernel": kern_ms[1] if nl > 2 else None,
                                  "finalize_plan_kernel": kern_ms[-1]},
                    "parity_vs_oracle_on_sample": parity},
         "roofline": {"bound": "hbm", "kernel": "step_kernel<8,sgd>", "achieved": achieved,
@@ -589,7 +589,8 @@ def main():
             "cores": min(16, os.cpu_count() or 1), "kind": "oracle",
             "sample": f"first {min(args.cpu_sample_blocks, args.blocks)} Conformer blocks of the same set "
                       f"({cpu['n_elems']} params), {args.cpu_iters} iterations, "
-                      f"{1e3 * cpu['sec_per_iter']:.0f} ms per iteration",
+                      f"{1e3 * cpu['sec_per_iter']:.0f} ms per iteration on {min(16, os.cpu_count() or 1)} threads "
+                      f"({args.cpu_iters * cpu['sec_per_iter'] * min(16, os.cpu_count() or 1):.0f} core-seconds)",
         }
     print(json.dumps(out))
 
