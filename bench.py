@@ -148,6 +148,21 @@ def gemm_leg(torch, omc, synth, iters=20):
         tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
         rec = {"M": M, "N": N, "K": K, "ms": ms, "TFLOPs": tf, "frac_of_bf16_mfma_peak": tf / 2500.0,
                "hbm_bytes": 2 * M * K + K * N + 4 * M * N}
+        # the same product with the weights in the paper's 11-bit format (Table 1: S1E3M7), generic decode
+        gf11 = omc.fmt(3, 7)
+        codes11 = torch.zeros(omc.omc_packed_bytes(gf11, K * N), dtype=torch.uint8, device="cuda")
+        sb11 = torch.zeros(2, device="cuda")
+        omc.omc_compress(W, K * N, gf11, True, codes11, sb11, wsc)
+        warm(torch, lambda k: omc.omc_dequant_gemm(A, codes11, gf11, sb11, C, M, N, K, ws))
+        e0.record()
+        for _ in range(iters):
+            omc.omc_dequant_gemm(A, codes11, gf11, sb11, C, M, N, K, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        rec["S1E3M7_ms"] = ms
+        rec["S1E3M7_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+        del codes11
         # the same layer's input gradient: dX[M, K] = dY[M, N] @ Wbar^T
         del C
         dY = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 13)).view(np.int16)).cuda()

@@ -106,17 +106,25 @@ __device__ __forceinline__ void load_codes4(const uint32_t *__restrict__ codes, 
         const uint64_t bit = e * B;
         const uint64_t dw = bit >> 5;
         off = static_cast<uint32_t>(bit & 31u);
+        if (dw + 3 <= total_dwords) {                       // one 12-byte load (dword-aligned) ...
+            typedef uint32_t u32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));
+            const u32x3_a4 t = *reinterpret_cast<const u32x3_a4 *>(codes + dw);
+            raw[0] = t[0]; raw[1] = t[1]; raw[2] = t[2];
+        } else {                                            // ... except at the very end of the stream
 #pragma unroll
-        for (int i = 0; i < 3; ++i) raw[i] = (dw + i < total_dwords) ? codes[dw + i] : 0u;
+            for (int i = 0; i < 3; ++i) raw[i] = (dw + i < total_dwords) ? codes[dw + i] : 0u;
+        }
     }
 }
 template <bool BYTE>
 __device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32_t off, uint32_t B, int i) {
     if (BYTE) return raw[0] << (24 - 8 * i);
-    const uint32_t sh = off + i * B;                       // < 32 + 3 * 16
-    const uint64_t lo = (static_cast<uint64_t>(raw[1]) << 32) | raw[0];
-    const uint64_t hi = (static_cast<uint64_t>(raw[2]) << 32) | raw[1];
-    const uint32_t c = (sh < 32) ? static_cast<uint32_t>(lo >> sh) : static_cast<uint32_t>(hi >> (sh - 32));
+    // the 64 bits that start at the first code (two funnel shifts by the lane's offset, shared by the four
+    // codes), then a shift by i * B, which is the same in every lane; 4 B <= 64 for the widths the GEMM takes
+    const uint32_t n0 = __builtin_amdgcn_alignbit(raw[1], raw[0], off);
+    const uint32_t n1 = __builtin_amdgcn_alignbit(raw[2], raw[1], off);
+    const uint64_t n = (static_cast<uint64_t>(n1) << 32) | n0;
+    const uint32_t c = static_cast<uint32_t>(n >> (i * B));
     return c << (32 - B);
 }
 
