@@ -128,6 +128,27 @@ __device__ __forceinline__ uint32_t code_top_of(const uint32_t (&raw)[3], uint32
     return c << (32 - B);
 }
 
+// The fp32 bit patterns of four consecutive codes (what load_codes4 fetched).  HW: the hardware FP8 conversion.
+template <bool BYTE, bool HW>
+__device__ __forceinline__ void decode_codes4(const uint32_t (&raw)[3], uint32_t off, const FmtParams &fp, uint32_t (&v)[4]) {
+    if (HW) {
+        const f32x2 c01 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(raw[0]), false);
+        const f32x2 c23 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(raw[0]), true);
+        v[0] = __float_as_uint(c01[0]); v[1] = __float_as_uint(c01[1]);
+        v[2] = __float_as_uint(c23[0]); v[3] = __float_as_uint(c23[1]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = decode_bits(code_top_of<BYTE>(raw, off, fp.bits, i), fp);
+    }
+}
+// four fp32 bit patterns whose low 16 bits are zero, as four bf16 in 8 bytes
+__device__ __forceinline__ u32x2 pack_bf16x4(uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) {
+    u32x2 out;
+    out[0] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);   // bf16(v0) | bf16(v1) << 16
+    out[1] = __builtin_amdgcn_perm(v3, v2, 0x07060302u);
+    return out;
+}
+
 // DEC: 0 = any code width, 1 = byte codes.  HW (byte codes of S1E4M3 / bias 7 only): hardware FP8 conversion.
 // TRANS: the packed variable is [N x K] (output column major), i.e. C = A * W^T for the weights as
 // stored: the input-gradient GEMM of the layer whose forward pass is the non-transposed one.
@@ -207,59 +228,28 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
             }
         }
     };
-    auto store_w_column = [&](uint8_t *ldsA, int i, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) {
+    // decode the thread's 16 codes (four groups of four consecutive ones) and store them as 8-byte runs of four
+    // k-values: non-transposed, group = weight row and the runs are the patch's columns; transposed, group = four
+    // consecutive k-values of the thread's column and is a run itself
+    auto store_w = [&](const StageRegs &r, uint8_t *ldsA) {
         uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
-        u32x2 out;
-        out[0] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);   // bf16(v0) | bf16(v1) << 16
-        out[1] = __builtin_amdgcn_perm(v3, v2, 0x07060302u);
-        *reinterpret_cast<u32x2 *>(ldsW + wave * kWChunkBytes + ((32u * i + w_cg) << 4) + 8u * w_h) = out;
-    };
-    // decode and store of the patch in four parts (part i = column 4 cg + i; the hardware conversion
-    // yields two columns at a time, so its parts 1 and 3 are empty)
-    auto store_w_part = [&](const StageRegs &r, uint8_t *ldsA, int part) {
-        if (TRANS) {                                        // part = group of four consecutive k-values
-            uint32_t v[4];
-            if (HW) {
-                const f32x2 c01 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[part][0]), false);
-                const f32x2 c23 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[part][0]), true);
-                v[0] = __float_as_uint(c01[0]); v[1] = __float_as_uint(c01[1]);
-                v[2] = __float_as_uint(c23[0]); v[3] = __float_as_uint(c23[1]);
-            } else {
+        uint32_t v[4][4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    v[i] = decode_bits(code_top_of<BYTE>(r.w_raw[part], r.w_off[part], fp.bits, i), fp);
-            }
-            uint8_t *ldsW = ldsA + 4 * kAChunkBytes;
-            u32x2 out;
-            out[0] = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);
-            out[1] = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
-            *reinterpret_cast<u32x2 *>(ldsW + (2u * t_h + (part >> 1)) * kWChunkBytes + (t_slot << 4) + 8u * (part & 1)) = out;
-            return;
-        }
-        if (HW) {
-            if (part & 1) return;
-            f32x2 c[4];
+        for (int g = 0; g < 4; ++g) decode_codes4<BYTE, HW>(r.w_raw[g], r.w_off[g], fp, v[g]);
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr)
-                c[rr] = (part == 0) ? __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[rr][0]), false)
-                                    : __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.w_raw[rr][0]), true);
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                store_w_column(ldsA, part + j, __float_as_uint(c[0][j]), __float_as_uint(c[1][j]),
-                               __float_as_uint(c[2][j]), __float_as_uint(c[3][j]));
-        } else {
-            uint32_t v[4];
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr)
-                v[rr] = decode_bits(code_top_of<BYTE>(r.w_raw[rr], r.w_off[rr], fp.bits, part), fp);
-            store_w_column(ldsA, part, v[0], v[1], v[2], v[3]);
+        for (int i = 0; i < 4; ++i) {
+            if (TRANS)
+                *reinterpret_cast<u32x2 *>(ldsW + (2u * t_h + (i >> 1)) * kWChunkBytes + (t_slot << 4) + 8u * (i & 1)) =
+                    pack_bf16x4(v[i][0], v[i][1], v[i][2], v[i][3]);
+            else
+                *reinterpret_cast<u32x2 *>(ldsW + wave * kWChunkBytes + ((32u * i + w_cg) << 4) + 8u * w_h) =
+                    pack_bf16x4(v[0][i], v[1][i], v[2][i], v[3][i]);
         }
     };
     auto store_stage = [&](const StageRegs &r, uint8_t *ldsA) {
 #pragma unroll
         for (int p = 0; p < AP; ++p) store_a_piece(r, ldsA, p);
-#pragma unroll
-        for (int part = 0; part < 4; ++part) store_w_part(r, ldsA, part);
+        store_w(r, ldsA);
     };
 
     f32x16 acc[MI][4];
@@ -602,52 +592,19 @@ __device__ __forceinline__ void dequant_gemm_ws_body(const uint16_t *__restrict_
                 load_codes4<BYTE>(codes, total_dwords, e, fp.bits, r.raw[rr], r.off[rr]);
             }
         };
-        auto store_column = [&](uint8_t *st, int i, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3) {
+        auto store_w = [&](const WRegs &r, uint8_t *st) {      // as in the four-wave kernel, other column slots
             uint8_t *ldsW = st + 4 * kAChunkBytes;
-            u32x2 out;
-            out[0] = __builtin_amdgcn_perm(v1, v0, 0x07060302u);   // bf16(v0) | bf16(v1) << 16
-            out[1] = __builtin_amdgcn_perm(v3, v2, 0x07060302u);
-            const uint32_t slot = ws_slot_of_column(4 * w_cg + i);
-            *reinterpret_cast<u32x2 *>(ldsW + pw * kWChunkBytes + (slot << 4) + 8u * w_h) = out;
-        };
-        auto store_w = [&](const WRegs &r, uint8_t *st) {
+            uint32_t v[4][4];
 #pragma unroll
-            for (int part = 0; part < 4; ++part) {
-                if (TRANS) {                                // part = group of four consecutive k-values
-                    uint32_t v[4];
-                    if (HW) {
-                        const f32x2 c01 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[part][0]), false);
-                        const f32x2 c23 = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[part][0]), true);
-                        v[0] = __float_as_uint(c01[0]); v[1] = __float_as_uint(c01[1]);
-                        v[2] = __float_as_uint(c23[0]); v[3] = __float_as_uint(c23[1]);
-                    } else {
+            for (int g = 0; g < 4; ++g) decode_codes4<BYTE, HW>(r.raw[g], r.off[g], fp, v[g]);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            v[i] = decode_bits(code_top_of<BYTE>(r.raw[part], r.off[part], fp.bits, i), fp);
-                    }
-                    uint8_t *ldsW = st + 4 * kAChunkBytes;
-                    u32x2 out;
-                    out[0] = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);
-                    out[1] = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
-                    *reinterpret_cast<u32x2 *>(ldsW + (2u * t_h + (part >> 1)) * kWChunkBytes + (t_slot << 4) + 8u * (part & 1)) = out;
-                } else if (HW) {
-                    if (part & 1) continue;                 // the hardware conversion yields two columns at a time
-                    f32x2 c[4];
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        c[rr] = (part == 0) ? __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[rr][0]), false)
-                                            : __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(r.raw[rr][0]), true);
-#pragma unroll
-                    for (int jj = 0; jj < 2; ++jj)
-                        store_column(st, part + jj, __float_as_uint(c[0][jj]), __float_as_uint(c[1][jj]),
-                                     __float_as_uint(c[2][jj]), __float_as_uint(c[3][jj]));
-                } else {
-                    uint32_t v[4];
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        v[rr] = decode_bits(code_top_of<BYTE>(r.raw[rr], r.off[rr], fp.bits, part), fp);
-                    store_column(st, part, v[0], v[1], v[2], v[3]);
-                }
+            for (int i = 0; i < 4; ++i) {
+                if (TRANS)
+                    *reinterpret_cast<u32x2 *>(ldsW + (2u * t_h + (i >> 1)) * kWChunkBytes + (t_slot << 4) + 8u * (i & 1)) =
+                        pack_bf16x4(v[i][0], v[i][1], v[i][2], v[i][3]);
+                else
+                    *reinterpret_cast<u32x2 *>(ldsW + pw * kWChunkBytes + (ws_slot_of_column(4 * w_cg + i) << 4) + 8u * w_h) =
+                        pack_bf16x4(v[0][i], v[1][i], v[2][i], v[3][i]);
             }
         };
 #pragma unroll
@@ -694,7 +651,7 @@ __global__ __launch_bounds__(1024, 1) void dequant_gemm_ws_kernel(const uint16_t
 
 // DEC 2 = byte codes of S1E4M3 / bias 7: hardware conversion unless the pre-pass found a top code.
 template <int BM, int DEC, bool TRANS>
-__global__ __launch_bounds__(256, BM == 256 ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
+__global__ __launch_bounds__(256, (BM == 256 || DEC == 0) ? OMC_GEMM_WAVES : 3) void dequant_gemm_kernel(const uint16_t *__restrict__ A,
                                                               const uint32_t *__restrict__ codes, uint64_t total_dwords,
                                                               FmtParams fp, const float *__restrict__ sb,
                                                               float *__restrict__ C, uint32_t M, uint32_t N, uint32_t K,
