@@ -25,6 +25,16 @@ constexpr int kDwBChunk = kDwCols * 16;
 
 __device__ __forceinline__ uint32_t dw_a_slot(uint32_t row, uint32_t chunk) { return row ^ (2u * chunk); }
 
+// column i of a 4 x 4 patch of bf16 (rows = consecutive m): the four values as 8 bytes
+__device__ __forceinline__ u32x2 patch_column(const u32x2 (&rows)[4], int i) {
+    const int d = i >> 1;
+    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+    u32x2 out;
+    out[0] = __builtin_amdgcn_perm(rows[1][d], rows[0][d], sel);
+    out[1] = __builtin_amdgcn_perm(rows[3][d], rows[2][d], sel);
+    return out;
+}
+
 // ROWS = weight rows per tile (256 or 128); a wave owns ROWS / 4 tile rows = MI 32-row MFMA tiles.
 template <int ROWS, int MODE, bool WIDE>
 __device__ __forceinline__ void dw_epilogue(const DwArgs &a, const f32x16 (&acc)[ROWS / 128][4], uint32_t k0t, uint32_t n0,
@@ -148,15 +158,6 @@ __global__ __launch_bounds__(256, ROWS == 256 ? 2 : 3) void dw_update_kernel(DwA
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr)
             r.y[rr] = *reinterpret_cast<const u32x2 *>(a.dY + static_cast<uint64_t>(m0 + 4 * y_mg + rr) * N + n0 + 4 * y_nq);
-    };
-    // column i of a 4 x 4 patch of bf16 (rows = consecutive m): the four values as 8 bytes
-    auto patch_column = [&](const u32x2 (&rows)[4], int i) -> u32x2 {
-        const int d = i >> 1;
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 out;
-        out[0] = __builtin_amdgcn_perm(rows[1][d], rows[0][d], sel);
-        out[1] = __builtin_amdgcn_perm(rows[3][d], rows[2][d], sel);
-        return out;
     };
     auto store_stage = [&](uint8_t *ldsA) {
         uint8_t *ldsB = ldsA + 4 * kDwAChunk;
@@ -354,15 +355,6 @@ __global__ __launch_bounds__(1024, 1) void dw_update_ws_kernel(DwArgs a) {
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr)
             g.y[rr] = *reinterpret_cast<const u32x2 *>(a.dY + static_cast<uint64_t>(m0 + 4 * y_mg + rr) * N + n0 + 4 * y_nq);
-    };
-    // column i of a 4 x 4 patch of bf16 (rows = consecutive m): the four values as 8 bytes
-    auto patch_column = [&](const u32x2 (&rows)[4], int i) -> u32x2 {
-        const int d = i >> 1;
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 out;
-        out[0] = __builtin_amdgcn_perm(rows[1][d], rows[0][d], sel);
-        out[1] = __builtin_amdgcn_perm(rows[3][d], rows[2][d], sel);
-        return out;
     };
     auto store_stage = [&](const Regs &g, uint8_t *st) {
         const uint32_t xc = x_mg >> 1;
