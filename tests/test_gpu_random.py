@@ -94,3 +94,42 @@ def test_wide_mantissa_formats(EM):
     assert abs(int(sb.view(np.int32)[0]) - int(wsb.view(np.int32)[0])) <= 1
     assert abs(float(sb[1]) - float(wsb[1])) <= 1e-9 * 0.05
     assert bits_equal(gpu_decompress(packed, n, gf, sb), orc.decompress(packed, n, of, sb))
+
+
+@pytest.mark.parametrize("seed", range(40, 52))
+def test_random_sets_aggregation(seed):
+    """Random number of clients, each quantizing its own random subset of a random variable set."""
+    from test_gpu_aggregate import run_case
+    specs, mask, fmts, rng = random_set(seed)
+    fmts = [f if f is not None else (4, 3) for f in fmts]              # a format for whoever quantizes the variable
+    R = int(rng.integers(1, 9))
+    masks = [np.array([bool(m and rng.random() < 0.8) for m in mask]) for _ in range(R)]
+    run_case(specs, fmts, masks, seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(60, 72))
+def test_random_gemm_shapes(seed):
+    """Forward and input-gradient GEMM on random multiples of the tile sizes and random formats of at most seven
+    mantissa bits, against the oracle on every row."""
+    from test_gpu_gemm import check, run_gemm, run_gemm_dx
+    from gpu_util import pair
+    rng = np.random.default_rng(2000 + seed)
+    E, Mb = int(rng.integers(1, 9)), int(rng.integers(0, 8))
+    if rng.random() < 0.4:
+        E, Mb = 4, 3
+    of, gf = pair(E, Mb)
+    M = 256 * int(rng.integers(1, 3))
+    N = 128 * int(rng.integers(1, 4))
+    K = 128 * int(rng.integers(1, 5)) if rng.random() < 0.7 else 2048 + 128 * int(rng.integers(0, 3))
+    A = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, seed))
+    W = synth.normal_f32(K * N, 1 / np.sqrt(K), seed + 1)
+    packed, sb = orc.compress(W, of)
+    if (E, Mb) == (4, 3) and rng.random() < 0.5:                        # plant a top code: the generic decode must take over
+        codes = orc.unpack(packed, K * N, 8)
+        codes[int(rng.integers(0, K * N))] = 0x7F
+        packed = orc.pack(codes, 8)
+    C = run_gemm(A, packed, gf, sb, M, N, K)
+    check(C, orc.dequant_gemm(A, packed, of, sb, M, N, K, threads=8), (0, M))
+    dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, seed + 2))
+    dX = run_gemm_dx(dY, packed, gf, sb, M, N, K)
+    check(dX, orc.dequant_gemm_dx(dY, packed, of, sb, M, N, K, threads=8), (0, M))
