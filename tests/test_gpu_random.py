@@ -133,3 +133,16 @@ def test_random_gemm_shapes(seed):
     dY = synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, seed + 2))
     dX = run_gemm_dx(dY, packed, gf, sb, M, N, K)
     check(dX, orc.dequant_gemm_dx(dY, packed, of, sb, M, N, K, threads=8), (0, M))
+
+
+@pytest.mark.parametrize("seed", range(80, 90))
+def test_random_weight_gradient_steps(seed):
+    """The fused weight-gradient step on random shapes, formats, optimizers: the two-stage check of test_gpu_dw."""
+    from test_gpu_dw import run_case
+    rng = np.random.default_rng(3000 + seed)
+    EM = [(4, 3), (3, 7), (2, 3), (4, 14), (5, 10), (5, 2), (8, 7), (6, 9)][int(rng.integers(0, 8))]
+    M = 32 * int(rng.integers(1, 40))
+    N = 128 * int(rng.integers(1, 4))
+    K = 256 * int(rng.integers(1, 3))
+    kind = int(rng.integers(0, 3))
+    run_case(EM, M, N, K, kind, [0.05, 0.05, 1e-3][kind], use_pvt=bool(rng.random() < 0.8), steps=2)
