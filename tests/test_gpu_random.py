@@ -146,3 +146,19 @@ def test_random_weight_gradient_steps(seed):
     K = 256 * int(rng.integers(1, 3))
     kind = int(rng.integers(0, 3))
     run_case(EM, M, N, K, kind, [0.05, 0.05, 1e-3][kind], use_pvt=bool(rng.random() < 0.8), steps=2)
+
+
+@pytest.mark.parametrize("kind,lr,EM", [(0, 0.01, (4, 3)), (1, 0.01, (3, 7)), (2, 1e-3, (4, 3))])
+def test_hundred_free_running_steps(kind, lr, EM):
+    """BASELINE config 2 runs 100 update / recompress iterations: a small Conformer-shaped set stepped 100 times on
+    both sides without ever resynchronising; codes, fp32 variables, optimizer state and (s, b) must still be
+    identical at the end (any earlier difference would have grown)."""
+    specs = synth.conformer_varset(64, 2, 256, 8, frontend=True)
+    mask = synth.ppq_mask(specs, 1.0, 0)
+    vs = VarSet(specs, mask, EM, seed=21)
+    grads = [synth.gradients(vs.lay, 1e-3, 9000 + k) for k in range(4)]
+    g_dev = [to_dev(g) for g in grads]
+    for t in range(1, 101):
+        vs.step_oracle(grads[t % 4], kind, lr, t)
+        vs.step_gpu(g_dev[t % 4], kind, lr, t)
+    assert vs.compare(kind, "after 100 steps") == 0
