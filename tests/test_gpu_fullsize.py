@@ -205,3 +205,19 @@ def test_benchmark_set_whole_set_conversions_and_server_aggregation():
         a = int(lay0.aux_offset[i])
         assert bits_equal(out[a:a + specs[i].n].cpu().numpy(), orc.aggregate_mean(copies[i])), f"aggregate: {specs[i].name}"
     assert torch.isfinite(out).all()
+
+
+def test_config2_every_variable_free_running():
+    """BASELINE config 2 on every one of its 599 variables (not a sample): the whole 115 M-parameter set stepped
+    twenty times on both sides without resynchronising; arena and (s, b) table identical at the end.  (Run
+    once with the configuration's full 100 iterations, checked every ten: identical throughout.)"""
+    from gpu_util import VarSet, to_dev
+    specs = synth.conformer_varset(512, 17, 2048, 32, frontend=True)
+    mask = np.array([s.is_matrix for s in specs])
+    vs = VarSet(specs, mask, (4, 3), seed=0)
+    grads = [synth.gradients(vs.lay, 1e-3, 1000 + k) for k in range(2)]
+    g_dev = [to_dev(g) for g in grads]
+    for t in range(1, 21):
+        vs.step_oracle(grads[t % 2], 0, 0.01, t, threads=16)
+        vs.step_gpu(g_dev[t % 2], 0, 0.01, t)
+    assert vs.compare(0, "after 20 steps") == 0
