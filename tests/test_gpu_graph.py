@@ -30,6 +30,13 @@ def test_captured_round_replays_like_eager_launches():
     wsb = torch.tensor([0.5, 0.125], device="cuda")
     C = torch.zeros((M, N), device="cuda")
     gws = torch.empty(omc.omc_dequant_gemm_workspace_bytes(M), dtype=torch.uint8, device="cuda")
+    K2 = 2048                                        # a long contraction on a small grid: the sixteen-wave kernel
+    A2 = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * K2, 1.0, 6)).view(np.int16)).cuda()
+    wcodes2 = torch.randint(0, 120, (K2 * N,), dtype=torch.uint8, device="cuda")
+    C2 = torch.zeros((M, N), device="cuda")
+    dX2 = torch.zeros((M, K), device="cuda")
+    dY2 = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * K2, 1.0, 7)).view(np.int16)).cuda()   # [M x 2048]
+    wcodes3 = torch.randint(0, 120, (K * K2,), dtype=torch.uint8, device="cuda")                          # W [K x 2048]
 
     def one_round(stream=None):
         # a client's round in miniature: compress the set, two training steps, a forward GEMM, decompress
@@ -37,11 +44,13 @@ def test_captured_round_replays_like_eager_launches():
         omc.omc_step_update_recompress(arena, plan, sb, grads[0], mom, None, o, ws, stream=stream)
         omc.omc_step_update_recompress(arena, plan, sb, grads[1], mom, None, o, ws, stream=stream)
         omc.omc_dequant_gemm(A, wcodes, omc.fmt(4, 3), wsb, C, M, N, K, gws, stream=stream)
+        omc.omc_dequant_gemm(A2, wcodes2, omc.fmt(4, 3), wsb, C2, M, N, K2, gws, stream=stream)
+        omc.omc_dequant_gemm_dx(dY2, wcodes3, omc.fmt(4, 3), wsb, dX2, M, K2, K, gws, stream=stream)
         omc.omc_decompress_set(arena, plan, sb, out, stream=stream)
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (arena, sb, mom, out, C)]
+        return [t.clone() for t in (arena, sb, mom, out, C, C2, dX2)]
 
     mom.zero_()
     one_round()
@@ -55,7 +64,7 @@ def test_captured_round_replays_like_eager_launches():
         one_round(cap)
     for rep in range(4):
         mom.zero_()                                  # eager work between the replays
-        arena.zero_(); out.zero_(); C.zero_(); sb.zero_()
+        arena.zero_(); out.zero_(); C.zero_(); C2.zero_(); dX2.zero_(); sb.zero_()
         torch.cuda.synchronize()
         g.replay()
         got = snapshot()
