@@ -122,6 +122,22 @@ def warm(torch, fn, seconds=None):
             return k
 
 
+def copy_ceiling(torch, n=1 << 28, iters=20):
+    """GB/s of the runtime's own device-to-device copy of 1 GiB (2 GiB moved): the practical ceiling for a
+    kernel that writes as much as it reads, measured in the same run."""
+    src = torch.empty(n, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    warm(torch, lambda k: dst.copy_(src))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    return 8.0 * n / (ms * 1e-3) / 1e9
+
+
 def gemm_leg(torch, omc, synth, iters=20):
     """Forward-path dequant-fused GEMM (BASELINE config 5): bf16 activations [8192 x 1024] times S1E4M3
     weights [1024 x 4096], and [8192 x 4096] times [4096 x 1024]; fp32 accumulate and output."""
@@ -589,6 +605,9 @@ def main():
     del grads, arena0
     torch.cuda.empty_cache()
     if not args.step_only:
+        ceil = copy_ceiling(torch)
+        out["roofline"]["copy_kernel_GBps"] = ceil        # device-to-device copy of 1 GiB in this run
+        out["roofline"]["frac_of_copy_kernel"] = out["roofline"]["achieved"] / ceil
         out["set_conversions"] = set_conversion_leg(torch, omc, wl, n_q, n_f)
         del wl
         torch.cuda.empty_cache()
