@@ -221,7 +221,14 @@ uint64_t omc_plan_transport_bytes(const void *plan_host);
  * up to two kernels for the ragged tails (n % 2048 != 0) of quantized variables; then, only if no
  * full-tile kernel ran, one kernel for the fp32 variables; then the per-variable
  * finalize, if any variable is quantized.  omc_plan_launches gives the count; nevents must be at
- * least twice that (OMC_ERR_SIZE otherwise).  Results are identical to the plain call. */
+ * least twice that (OMC_ERR_SIZE otherwise).  Results are identical to the plain call.
+ * A full-tile kernel may be enqueued as two launches, one event pair around both: packed codes are
+ * read and rewritten in place by every step, so when a set holds more than 264 MiB of them, the
+ * work items holding the first 224 MiB (in launch order) access their codes with ordinary cached
+ * loads and stores, which lets them come back from the GPU's 256 MB memory-side cache at the
+ * next step, and the work items after that limit access theirs with the non-temporal hint so that
+ * they do not push the first ones out.  Gradients and optimizer state always carry the hint.
+ * Values are the same either way. */
 uint32_t omc_plan_launches(const void *plan_host);
 omc_status omc_step_update_recompress_events(void *arena, size_t arena_bytes, const void *plan_host,
                                              const void *plan_dev, float *sb_table, const float *grads,

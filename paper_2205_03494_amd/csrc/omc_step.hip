@@ -1,6 +1,15 @@
 // omc_step_update_recompress: orchestration over the plan's groups, the fp32-variable kernels
 // and the per-variable finalize.
+#include <algorithm>
+
 #include "omc_step_impl.h"
+
+#ifndef OMC_TUNE_KEEP_BUDGET_MIB
+#define OMC_TUNE_KEEP_BUDGET_MIB 224     // packed codes that stay cached when the set's codes do not fit as a whole
+#endif
+#ifndef OMC_TUNE_KEEP_ALL_MIB
+#define OMC_TUNE_KEEP_ALL_MIB 264        // up to this size all codes stay cached
+#endif
 
 namespace omc {
 
@@ -69,6 +78,23 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     }
     fuse = fuse && fp32_group != nullptr;
     bool fused_done = false;
+    // Packed codes are read and rewritten by every step and come back from the memory-side cache at the
+    // next step if they still sit there; gradients are new every step and never do.  Work items get to keep
+    // their codes cached, in launch order, up to a budget below that cache's 256 MB; the codes of all other
+    // items carry the non-temporal hint and pass it by.  A group whose items fall on both sides of the limit
+    // is launched in two parts.
+    uint64_t keep_budget = static_cast<uint64_t>(OMC_TUNE_KEEP_BUDGET_MIB) << 20;
+    {   // a set that exceeds the cache by little still gets most of its hits and is not worth a second, small launch
+        uint64_t all_codes = 0;
+        for (uint32_t gi = 0; gi < ph->ngroups; ++gi)
+            if (groups[gi].kind == kGroupFull) all_codes += static_cast<uint64_t>(groups[gi].nitems) * kChunkElems * groups[gi].bits / 8;
+        if (all_codes <= (static_cast<uint64_t>(OMC_TUNE_KEEP_ALL_MIB) << 20)) keep_budget = all_codes;
+    }
+    auto take = [&](uint32_t nitems, uint64_t item_bytes) -> uint32_t {   // how many of nitems the budget still covers
+        const uint64_t k = std::min<uint64_t>(nitems, keep_budget / item_bytes);
+        keep_budget -= k * item_bytes;
+        return static_cast<uint32_t>(k);
+    };
     for (uint32_t gi = 0; gi < ph->ngroups; ++gi) {
         const PlanGroup &g = groups[gi];
         if (g.nitems == 0) continue;
@@ -77,11 +103,12 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
         sa.nitems = g.nitems;
         sa.fp32_first = 0;
         sa.fp32_nitems = 0;
-        if (fuse && g.kind == kGroupFull && !fused_done) {
+        auto ride_along = [&]() {                                          // with the first full-tile launch of the step
+            if (!fuse || fused_done) return;
             sa.fp32_first = fp32_group->first_item;
             sa.fp32_nitems = fp32_group->nitems;
             fused_done = true;
-        }
+        };
         int rc = mark(0);
         if (rc != 0) return rc;
         if (g.kind == kGroupTail) {
@@ -93,12 +120,19 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
             else if (opt.kind == OMC_MOMENTUM) step_fp32_kernel<kStepMomentum><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             else step_fp32_kernel<kStepAdam><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             rc = static_cast<int>(hipGetLastError());
-        } else if (opt.kind == OMC_SGD) {
-            rc = launch_step_group_sgd(g.bits, g.wide, sa, st);
-        } else if (opt.kind == OMC_MOMENTUM) {
-            rc = launch_step_group_momentum(g.bits, g.wide, sa, st);
         } else {
-            rc = launch_step_group_adam(g.bits, g.wide, sa, st);
+            const uint32_t kept = take(g.nitems, static_cast<uint64_t>(kChunkElems) * g.bits / 8);
+            for (int part = 0; part < 2 && rc == 0; ++part) {              // the cached items, then the streaming ones
+                sa.first_item = g.first_item + (part == 0 ? 0 : kept);
+                sa.nitems = part == 0 ? kept : g.nitems - kept;
+                if (sa.nitems == 0) continue;
+                sa.fp32_first = 0;
+                sa.fp32_nitems = 0;
+                ride_along();
+                if (opt.kind == OMC_SGD) rc = launch_step_group_sgd(g.bits, g.wide, sa, part == 0, st);
+                else if (opt.kind == OMC_MOMENTUM) rc = launch_step_group_momentum(g.bits, g.wide, sa, part == 0, st);
+                else rc = launch_step_group_adam(g.bits, g.wide, sa, part == 0, st);
+            }
         }
         if (rc != 0) return rc;
         rc = mark(1);

@@ -103,7 +103,9 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
     }
 }
 
-template <int B, int MODE, int VARIANT>
+// KEEP: the launch's work items keep their packed codes cached from step to step; without it the code
+// loads and stores carry the non-temporal hint.
+template <int B, int MODE, int VARIANT, bool KEEP>
 __global__ __launch_bounds__(64, (VARIANT == 3 ? OMC_TUNE_WAVES_FP6 : Tuning<MODE, B>::waves)) void step_kernel(StepArgs sa) {
     __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
     if (blockIdx.x >= sa.nitems) {                       // the workgroups past the end serve fp32 variables
@@ -125,25 +127,26 @@ __global__ __launch_bounds__(64, (VARIANT == 3 ? OMC_TUNE_WAVES_FP6 : Tuning<MOD
     a.s = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var)]);
     a.b = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var) + 1]);
     const FmtParams fp = pv.fp;
-    do_chunk<B, MODE, VARIANT>(a, fp, sa.oc, it.chunk, lds, sa.ws + item);
+    do_chunk<B, MODE, VARIANT, KEEP>(a, fp, sa.oc, it.chunk, lds, sa.ws + item);
 }
 
-template <int MODE>
-inline int launch_step_group_mode(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st) {
+template <int MODE, bool KEEP>
+inline int launch_step_group_keep(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st) {
+    const dim3 grid(sa.nitems + sa.fp32_nitems), block(64);
     // the hardware-conversion variant pays off where the vector ALU is the limit: plain SGD
     if (bits == 8 && variant == 2 && MODE <= OMC_TUNE_OCP_MAXMODE) {
-        step_kernel<8, MODE, 2><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);
+        step_kernel<8, MODE, 2, KEEP><<<grid, block, 0, st>>>(sa);
         return static_cast<int>(hipGetLastError());
     }
     if (bits == 6 && variant == 3 && MODE <= OMC_TUNE_FP6_MAXMODE) {
-        step_kernel<6, MODE, 3><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);
+        step_kernel<6, MODE, 3, KEEP><<<grid, block, 0, st>>>(sa);
         return static_cast<int>(hipGetLastError());
     }
     switch (bits) {
 #define X(BITS)                                                              \
     case BITS:                                                               \
-        if (variant == 1) step_kernel<BITS, MODE, 1><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);   \
-        else step_kernel<BITS, MODE, 0><<<dim3(sa.nitems + sa.fp32_nitems), dim3(64), 0, st>>>(sa);       \
+        if (variant == 1) step_kernel<BITS, MODE, 1, KEEP><<<grid, block, 0, st>>>(sa);   \
+        else step_kernel<BITS, MODE, 0, KEEP><<<grid, block, 0, st>>>(sa);       \
         break;
         OMC_FOR_EACH_BITS(X)
 #undef X
@@ -153,8 +156,14 @@ inline int launch_step_group_mode(uint32_t bits, uint32_t variant, const StepArg
     return static_cast<int>(hipGetLastError());
 }
 
-int launch_step_group_sgd(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st);
-int launch_step_group_momentum(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st);
-int launch_step_group_adam(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st);
+template <int MODE>
+inline int launch_step_group_mode(uint32_t bits, uint32_t variant, const StepArgs &sa, bool keep, hipStream_t st) {
+    return keep ? launch_step_group_keep<MODE, true>(bits, variant, sa, st)
+                : launch_step_group_keep<MODE, false>(bits, variant, sa, st);
+}
+
+int launch_step_group_sgd(uint32_t bits, uint32_t variant, const StepArgs &sa, bool keep, hipStream_t st);
+int launch_step_group_momentum(uint32_t bits, uint32_t variant, const StepArgs &sa, bool keep, hipStream_t st);
+int launch_step_group_adam(uint32_t bits, uint32_t variant, const StepArgs &sa, bool keep, hipStream_t st);
 
 }  // namespace omc

@@ -128,6 +128,18 @@ __device__ __forceinline__ void lds_fence() { __syncthreads(); }  // one wave pe
 #ifndef OMC_TUNE_NT_STATE
 #define OMC_TUNE_NT_STATE 1      // optimizer state and decompressed output, loads and stores
 #endif
+// Cache hints of a work item's in-place streams.  Packed codes are read and rewritten by every step
+// and come back from the memory-side cache at the next step if they still sit there: KEEP marks a
+// work item whose codes are meant to stay (the host grants this to as many items as fit), the
+// others carry the non-temporal hint and stream past.  The conversions (compress / decompress) keep
+// the codes cached, as every step after them reads them.  Optimizer state is always non-temporal:
+// keeping part of it cached instead was measured to be slower, not faster.
+template <int MODE, bool KEEP>
+struct StreamHints {
+    static constexpr bool nt_codes = (MODE >= kStepSgd) ? !KEEP : (OMC_TUNE_NT_LOADS & 2) != 0;
+    static constexpr bool nt_state = OMC_TUNE_NT_STATE != 0;
+};
+
 template <bool NT>
 __device__ __forceinline__ void load_f32_pieces(const float *__restrict__ src, uint32_t lane, f32x4 (&g)[8]) {
 #pragma unroll
@@ -184,28 +196,28 @@ struct CodePieces {
     }
 };
 
-template <int B>
+template <int B, bool NT = (OMC_TUNE_NT_LOADS & 2) != 0>
 __device__ __forceinline__ void load_code_pieces(const uint32_t *__restrict__ src, uint32_t lane,
                                                  u32x4 (&cq)[CodePieces<B>::rounds]) {
 #pragma unroll
     for (int j = 0; j < CodePieces<B>::rounds; ++j) {
         const uint32_t q = j * 64u + lane;
         if (CodePieces<B>::in_tile(j, q))
-            cq[j] = (OMC_TUNE_NT_LOADS & 2) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src) + q)
-                                            : reinterpret_cast<const u32x4 *>(src)[q];
+            cq[j] = NT ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src) + q)
+                       : reinterpret_cast<const u32x4 *>(src)[q];
         else
             cq[j] = u32x4{0u, 0u, 0u, 0u};
     }
 }
 
-template <int B>
+template <int B, bool NT = (OMC_TUNE_NT_LOADS & 2) != 0>
 __device__ __forceinline__ void store_code_pieces(uint32_t *__restrict__ dst, uint32_t lane,
                                                   const u32x4 (&cq)[CodePieces<B>::rounds]) {
 #pragma unroll
     for (int j = 0; j < CodePieces<B>::rounds; ++j) {
         const uint32_t q = j * 64u + lane;
         if (CodePieces<B>::in_tile(j, q)) {
-            if (OMC_TUNE_NT_LOADS & 2) __builtin_nontemporal_store(cq[j], reinterpret_cast<u32x4 *>(dst) + q);
+            if (NT) __builtin_nontemporal_store(cq[j], reinterpret_cast<u32x4 *>(dst) + q);
             else reinterpret_cast<u32x4 *>(dst)[q] = cq[j];
         }
     }
@@ -407,11 +419,12 @@ struct Stage {
     f32x4 gq[8], mq[8], vq[8];
 };
 
-template <int B, int MODE>
+template <int B, int MODE, bool KEEP>
 __device__ __forceinline__ void issue_loads(const TileArgs &a, uint64_t e0, uint32_t lane, Stage<B, MODE> &st) {
     const uint64_t dw0 = (e0 >> 5) * B;                   // first dword of the tile
-    if (MODE != kCompress) load_code_pieces<B>(a.codes + dw0, lane, st.cq);
-    constexpr bool nt_in = (OMC_TUNE_NT_LOADS & 1) != 0, nt_state = OMC_TUNE_NT_STATE != 0;
+    constexpr bool nt_codes = StreamHints<MODE, KEEP>::nt_codes, nt_state = StreamHints<MODE, KEEP>::nt_state;
+    if (MODE != kCompress) load_code_pieces<B, nt_codes>(a.codes + dw0, lane, st.cq);
+    constexpr bool nt_in = (OMC_TUNE_NT_LOADS & 1) != 0;
     if (MODE == kCompress) load_f32_pieces<nt_in>(a.vin + e0, lane, st.gq);
     if (MODE >= kStepSgd) load_f32_pieces<nt_in>(a.grad + e0, lane, st.gq);
     if (MODE >= kStepMomentum) load_f32_pieces<nt_state>(a.st0 + e0, lane, st.mq);
@@ -649,7 +662,7 @@ __device__ __forceinline__ bool cycle_mx_fp6(const TileArgs &a, const OptConst &
 // Everything after the loads of the full tile at e0 have been issued into `st`.  When PREFETCH,
 // the loads of the next tile are issued into the same registers as soon as they are free, so
 // that they are in flight while this tile is computed.
-template <int B, int MODE, int VARIANT, bool PREFETCH>
+template <int B, int MODE, int VARIANT, bool PREFETCH, bool KEEP>
 __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
                                             uint64_t e0, uint32_t lane, uint32_t *lds, Stage<B, MODE> &st,
                                             FitAcc &acc) {
@@ -661,7 +674,7 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
     if (MODE >= kStepMomentum) pieces_to_lanes(st.mq, rm, lds, lane);
     if (MODE == kStepAdam) pieces_to_lanes(st.vq, rv, lds, lane);
 
-    if (PREFETCH) issue_loads<B, MODE>(a, e0 + kTileElems, lane, st);
+    if (PREFETCH) issue_loads<B, MODE, KEEP>(a, e0 + kTileElems, lane, st);
 
     uint32_t o[B];
     if constexpr (VARIANT == 2 && B == 8 && MODE != kDecompress) {
@@ -684,21 +697,21 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
     if (MODE >= kStepMomentum) {
         f32x4 out[8];
         lanes_to_pieces(rm, out, lds, lane);
-        store_f32_pieces<OMC_TUNE_NT_STATE != 0>(a.st0 + e0, lane, out);
+        store_f32_pieces<StreamHints<MODE, KEEP>::nt_state>(a.st0 + e0, lane, out);
     }
     if (MODE == kStepAdam) {
         f32x4 out[8];
         lanes_to_pieces(rv, out, lds, lane);
-        store_f32_pieces<OMC_TUNE_NT_STATE != 0>(a.st1 + e0, lane, out);
+        store_f32_pieces<StreamHints<MODE, KEEP>::nt_state>(a.st1 + e0, lane, out);
     }
     u32x4 cout[CodePieces<B>::rounds];
     lanes_to_code_pieces<B>(o, cout, lds, lane);
-    store_code_pieces<B>(a.codes + (e0 >> 5) * B, lane, cout);
+    store_code_pieces<B, StreamHints<MODE, KEEP>::nt_codes>(a.codes + (e0 >> 5) * B, lane, cout);
 }
 
 // One work item of the full-tile kernels: tiles [chunk*kTilesPerChunk, ...) of one variable, as far
 // as full tiles go, reduced into one Partial.  The caller guarantees at least one full tile.
-template <int B, int MODE, int VARIANT>
+template <int B, int MODE, int VARIANT, bool KEEP = true>
 __device__ __forceinline__ void do_chunk(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
                                          uint32_t chunk, uint32_t *lds, Partial *partial_out) {
     const uint32_t lane = threadIdx.x;
@@ -710,14 +723,14 @@ __device__ __forceinline__ void do_chunk(const TileArgs &a, const FmtParams &fp,
         (full_tiles - first_tile < kTilesPerChunk) ? full_tiles - first_tile : kTilesPerChunk);
     const uint64_t begin = first_tile * kTileElems;
     Stage<B, MODE> st;
-    issue_loads<B, MODE>(a, begin, lane, st);
+    issue_loads<B, MODE, KEEP>(a, begin, lane, st);
     for (uint32_t t = 0; t + 1 < ntiles; ++t) {
         const uint64_t e0 = begin + static_cast<uint64_t>(t) * kTileElems;
-        finish_tile<B, MODE, VARIANT, Tuning<MODE, B>::prefetch>(a, fp, oc, e0, lane, lds, st, acc);
-        if (!Tuning<MODE, B>::prefetch) issue_loads<B, MODE>(a, e0 + kTileElems, lane, st);
+        finish_tile<B, MODE, VARIANT, Tuning<MODE, B>::prefetch, KEEP>(a, fp, oc, e0, lane, lds, st, acc);
+        if (!Tuning<MODE, B>::prefetch) issue_loads<B, MODE, KEEP>(a, e0 + kTileElems, lane, st);
     }
-    finish_tile<B, MODE, VARIANT, false>(a, fp, oc, begin + static_cast<uint64_t>(ntiles - 1) * kTileElems, lane,
-                                      lds, st, acc);
+    finish_tile<B, MODE, VARIANT, false, KEEP>(a, fp, oc, begin + static_cast<uint64_t>(ntiles - 1) * kTileElems,
+                                               lane, lds, st, acc);
     if (MODE != kDecompress) acc.reduce_and_store(partial_out);
 }
 
