@@ -5,6 +5,10 @@
 // copy is read once in the form it arrived in (packed codes or fp32), the mean is written once.
 #include "omc_stream.h"
 
+#ifndef OMC_TUNE_AGG_NT
+#define OMC_TUNE_AGG_NT 1      // the clients' codes are read once per round: non-temporal
+#endif
+
 namespace omc {
 
 #ifndef OMC_AGG_WAVES
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(64, OMC_AGG_WAVES) void aggregate_kernel(AggArgs aa
                 const float sc = to_scalar_regs(aa.p.sb[r][2 * static_cast<uint64_t>(it.var)]);
                 const float of = to_scalar_regs(aa.p.sb[r][2 * static_cast<uint64_t>(it.var) + 1]);
                 u32x4 cq[CodePieces<B>::rounds];
-                load_code_pieces<B>(codes + (e0 >> 5) * B, lane, cq);
+                load_code_pieces<B, OMC_TUNE_AGG_NT != 0>(codes + (e0 >> 5) * B, lane, cq);
                 uint32_t w[B];
                 code_pieces_to_lanes<B>(cq, w, lds, lane);
 #pragma unroll
@@ -140,7 +144,7 @@ __device__ __forceinline__ void aggregate_byte_slab(const AggArgs &aa, const Agg
             const float of = to_scalar_regs(aa.p.sb[r][2 * static_cast<uint64_t>(var) + 1]);
             uint32_t w[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = c[64 * j + lane];
+            for (int j = 0; j < 4; ++j) w[j] = OMC_TUNE_AGG_NT ? __builtin_nontemporal_load(c + (64 * j + lane)) : c[64 * j + lane];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float vt[4];
