@@ -144,6 +144,31 @@ def test_config4_full_size_momentum_11bit():
     assert ns >= 6
 
 
+def test_large_mixed_set_adam_launches_on_both_sides_of_the_cache_budget():
+    """604 M-parameter set, 90 % of the matrices quantized in three widths, Adam: 0.79 GB of packed codes.  The
+    step keeps the first 224 MiB of codes cached: all of the 8-bit group's launch and a part of the 11-bit
+    group's, which is launched in two parts, while the 16-bit group streams as a whole; the fp32 matrices ride
+    along with the first launch.  Sampled: the variables around the cut, and the usual first / last / largest."""
+    specs = synth.conformer_varset(1024, 24, 4096, 32, frontend=False)
+    mask = synth.ppq_mask(specs, 0.9, 5)
+    choices = [(4, 3), (3, 7), (5, 10)]
+    fmts = [choices[i % 3] for i in range(len(specs))]
+    bits = lambda i: 1 + sum(fmts[i])
+    by_width = {b: [i for i in range(len(specs)) if mask[i] and bits(i) == b] for b in (8, 11, 16)}
+    assert sum(specs[i].n for i in by_width[8]) < (224 << 20) < sum(specs[i].n * bits(i) // 8 for b in (8, 11) for i in by_width[b])
+    done, near = sum(specs[i].n for i in by_width[8]), []
+    for k, i in enumerate(by_width[11]):
+        done += specs[i].n * 11 // 8
+        if done > (224 << 20):
+            near = by_width[11][max(k - 1, 0):k + 2]
+            break
+    assert near
+    first = near + [by_width[8][-1], by_width[16][0]]
+    ns, total = run_fullsize(specs, mask, fmts, kind=2, lr=1e-3, steps=2, seed=6, max_sample_elems=24_000_000,
+                             first_samples=first)
+    assert ns >= 8
+
+
 def _device_values(specs, lay, seed, delta_seed=None):
     gen = torch.Generator(device="cuda").manual_seed(seed)
     vals = torch.empty(lay.aux_elems, device="cuda")
