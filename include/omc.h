@@ -103,8 +103,14 @@ typedef struct {
  *                 V' = V - fl( fl(lr*fl(m'/bias_corr1)) / fl(fl(sqrt(fl(v'/bias_corr2))) + eps) )
  *                                                                         state0 = m, state1 = v
  * one_minus_beta* = fp32(1 - beta*) and bias_corr* = fp32(1 - beta*^t) are computed by the caller
- * in fp64 and rounded once. */
+ * in fp64 and rounded once.
+ * flags: OMC_OPT_STREAM_CODES tells the step that other work runs on the GPU between two steps (the
+ * forward and backward pass of a training loop), so that nothing of the packed codes is left in the
+ * memory-side cache when the next step starts: all code accesses then carry the non-temporal hint
+ * instead of the first 224 MiB staying cached (see omc_step_update_recompress_events).  It changes
+ * memory traffic only, never a value.  Unknown bits are OMC_ERR_OPT. */
 typedef enum { OMC_SGD = 0, OMC_MOMENTUM = 1, OMC_ADAM = 2 } omc_opt_kind;
+#define OMC_OPT_STREAM_CODES 1u
 typedef struct {
     int32_t kind; /* omc_opt_kind */
     float lr;
@@ -112,6 +118,7 @@ typedef struct {
     float beta1, beta2, eps;
     float one_minus_beta1, one_minus_beta2;
     float bias_corr1, bias_corr2;
+    uint32_t flags; /* OMC_OPT_* */
 } omc_opt;
 
 /* ---- host-only helpers (no device work) ------------------------------------------------- */

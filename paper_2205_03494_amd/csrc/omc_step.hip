@@ -84,7 +84,9 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     // items carry the non-temporal hint and pass it by.  A group whose items fall on both sides of the limit
     // is launched in two parts.
     uint64_t keep_budget = static_cast<uint64_t>(OMC_TUNE_KEEP_BUDGET_MIB) << 20;
-    {   // a set that exceeds the cache by little still gets most of its hits and is not worth a second, small launch
+    if (opt.flags & OMC_OPT_STREAM_CODES) {
+        keep_budget = 0;      // the caller runs other work between steps: nothing would survive in the cache
+    } else {   // a set that exceeds the cache by little still gets most of its hits and is not worth a second, small launch
         uint64_t all_codes = 0;
         for (uint32_t gi = 0; gi < ph->ngroups; ++gi)
             if (groups[gi].kind == kGroupFull) all_codes += static_cast<uint64_t>(groups[gi].nitems) * kChunkElems * groups[gi].bits / 8;

@@ -29,6 +29,7 @@ OMC_OK = 0
 OMC_VAR_QUANTIZED = 1
 OMC_VAR_NO_PVT = 2
 OMC_SGD, OMC_MOMENTUM, OMC_ADAM = 0, 1, 2
+OMC_OPT_STREAM_CODES = 1
 OMC_BIAS_DEFAULT = -1
 
 
@@ -45,7 +46,7 @@ class omc_opt(C.Structure):
     _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("momentum", C.c_float),
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("one_minus_beta1", C.c_float), ("one_minus_beta2", C.c_float),
-                ("bias_corr1", C.c_float), ("bias_corr2", C.c_float)]
+                ("bias_corr1", C.c_float), ("bias_corr2", C.c_float), ("flags", C.c_uint32)]
 
 
 def _sig(name, restype, *argtypes):
@@ -116,10 +117,10 @@ def fmt(exp_bits: int, man_bits: int, bias: int = OMC_BIAS_DEFAULT) -> omc_forma
 
 
 def opt(kind: int, lr: float, momentum: float = 0.9, beta1: float = 0.9, beta2: float = 0.999,
-        eps: float = 1e-8, t: int = 1) -> omc_opt:
+        eps: float = 1e-8, t: int = 1, flags: int = 0) -> omc_opt:
     """Hyper-parameters; the derived constants are computed in fp64 here and rounded once (omc.h)."""
     return omc_opt(kind, lr, momentum, beta1, beta2, eps, 1.0 - beta1, 1.0 - beta2,
-                   1.0 - beta1 ** t, 1.0 - beta2 ** t)
+                   1.0 - beta1 ** t, 1.0 - beta2 ** t, flags)
 
 
 def _ptr(t: Optional[torch.Tensor]):

@@ -103,9 +103,9 @@ class VarSet:
         orc.step_varset(self.o_arena, self.o_table, self.o_sb, g, self.o_m, self.o_v,
                         orc.Opt(kind=kind, lr=lr, t=t), threads=threads)
 
-    def step_gpu(self, g_dev, kind, lr, t):
+    def step_gpu(self, g_dev, kind, lr, t, flags=0):
         omc.omc_step_update_recompress(self.g_arena, self.plan, self.g_sb, g_dev, self.g_m, self.g_v,
-                                       omc.opt(kind, lr, t=t), self.ws)
+                                       omc.opt(kind, lr, t=t, flags=flags), self.ws)
 
     def compare(self, kind, what=""):
         """Bit-exact on the arena (codes and fp32 values) and optimizer state; returns the number

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layouts_match_header():
     assert C.sizeof(omc.omc_format) == 4
     assert C.sizeof(omc.omc_var) == 32
-    assert C.sizeof(omc.omc_opt) == 40
+    assert C.sizeof(omc.omc_opt) == 44
 
 
 def test_format_validation_and_constants_agree_with_oracle():
@@ -144,6 +144,7 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert call(arena=None) == 1
     assert call(s1=None) == 6
     assert call(o=omc.opt(7, 1e-3)) == 6
+    assert call(o=omc.opt(omc.OMC_ADAM, 1e-3, flags=2)) == 6          # unknown flag bit
     assert call(ab=100) == 3
     assert call(aux=10) == 3
     assert call(wsb=8) == 5
