@@ -12,7 +12,10 @@ namespace omc {
 // between lanes, tiles or variables.
 constexpr int kLaneElems = 32;
 constexpr int kTileElems = 64 * kLaneElems;           // 2048
-constexpr int kTilesPerChunk = 4;                     // tiles reduced into one partial
+#ifndef OMC_TUNE_TILES_PER_CHUNK
+#define OMC_TUNE_TILES_PER_CHUNK 2
+#endif
+constexpr int kTilesPerChunk = OMC_TUNE_TILES_PER_CHUNK;   // tiles reduced into one partial
 constexpr int kChunkElems = kTileElems * kTilesPerChunk;
 constexpr int kLdsDwords = kTileElems + kTileElems / 32;  // padded code tile for B = 32
 

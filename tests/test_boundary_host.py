@@ -105,8 +105,8 @@ def test_plan_item_list_covers_every_chunk_once():
     offs = np.frombuffer(buf[32:56].tobytes(), dtype=np.uint64)
     item_off = int(offs[1])
     items = np.frombuffer(buf[item_off:item_off + 8 * nitems].tobytes(), dtype=np.uint32).reshape(-1, 2)
-    def n_items(s, q):      # quantized: chunks of 4 full 2048-element tiles, plus one item for a ragged tail
-        return ((s.n // 2048 + 3) // 4 + (1 if s.n % 2048 else 0)) if q else (s.n + 8191) // 8192
+    def n_items(s, q):      # quantized: chunks of 2 full 2048-element tiles, plus one item for a ragged tail
+        return ((s.n // 2048 + 1) // 2 + (1 if s.n % 2048 else 0)) if q else (s.n + 4095) // 4096
     counts = {}
     for v, c in items.tolist():
         counts.setdefault(v, []).append(c)

@@ -46,7 +46,7 @@ def gpu_compress_set(lay, plan, vals, nvars):
 
 def ragged_specs():
     # sizes around the tile and chunk borders, a tail-only variable, vectors
-    ns = [1, 31, 2047, 2048, 2049, 8192, 8193, 5 * 8192 + 77, 3 * 2048, 40000, 100, 2048 * 9 + 1]
+    ns = [1, 31, 2047, 2048, 2049, 4096, 4097, 8192, 8193, 5 * 8192 + 77, 3 * 2048, 40000, 100, 2048 * 9 + 1]
     return [synth.VarSpec(f"v{i}", (n,), max(n, 1), i % 4 != 3) for i, n in enumerate(ns)]
 
 

@@ -60,8 +60,8 @@ def test_compress_adversarial_values(EM):
     assert bits_equal(sb, wsb)
 
 
-@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 2047, 2048, 2049, 8191, 8192, 8193, 3 * 8192 + 2048 + 5,
-                               512 * 512])
+@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 2047, 2048, 2049, 4095, 4096, 4097, 8191, 8192, 8193,
+                               3 * 8192 + 2048 + 5, 512 * 512])
 @pytest.mark.parametrize("EM", [(4, 3), (3, 7), (5, 10), (2, 3)])
 def test_compress_decompress_sizes(n, EM):
     of, gf = pair(*EM)
