@@ -79,10 +79,10 @@ __global__ __launch_bounds__(64, OMC_AGG_WAVES) void aggregate_kernel(AggArgs aa
     const AggVar av = to_scalar_regs(reinterpret_cast<const AggVar *>(aa.plan + aa.var_off)[it.var]);
     const AggSrc *src = reinterpret_cast<const AggSrc *>(aa.plan + aa.src_off) + static_cast<uint64_t>(it.var) * aa.nreplicas;
     const FmtParams fp = av.fp;
-    const uint64_t first_tile = static_cast<uint64_t>(it.chunk) * kTilesPerChunk;
+    const uint64_t first_tile = static_cast<uint64_t>(it.chunk) * tiles_per_chunk(B);
     const uint64_t full_tiles = av.n / kTileElems;
     const uint32_t ntiles = static_cast<uint32_t>(
-        (full_tiles - first_tile < kTilesPerChunk) ? full_tiles - first_tile : kTilesPerChunk);
+        (full_tiles - first_tile < tiles_per_chunk(B)) ? full_tiles - first_tile : tiles_per_chunk(B));
     for (uint32_t t = 0; t < ntiles; ++t) {
         const uint64_t e0 = (first_tile + t) * kTileElems;
         float acc[32];
@@ -185,10 +185,10 @@ __global__ __launch_bounds__(64, 8) void aggregate_byte_kernel(AggArgs aa) {
     const AggVar av = to_scalar_regs(reinterpret_cast<const AggVar *>(aa.plan + aa.var_off)[it.var]);
     const AggSrc *src = reinterpret_cast<const AggSrc *>(aa.plan + aa.src_off) + static_cast<uint64_t>(it.var) * aa.nreplicas;
     const FmtParams fp = av.fp;
-    const uint64_t first_tile = static_cast<uint64_t>(it.chunk) * kTilesPerChunk;
+    const uint64_t first_tile = static_cast<uint64_t>(it.chunk) * tiles_per_chunk(8);
     const uint64_t full_tiles = av.n / kTileElems;
     const uint32_t ntiles = static_cast<uint32_t>(
-        (full_tiles - first_tile < kTilesPerChunk) ? full_tiles - first_tile : kTilesPerChunk);
+        (full_tiles - first_tile < tiles_per_chunk(8)) ? full_tiles - first_tile : tiles_per_chunk(8));
     const bool hw = fp.variant == 2;
     for (uint32_t sl = 0; sl < 2 * ntiles; ++sl) {
         const uint64_t e0 = first_tile * kTileElems + static_cast<uint64_t>(sl) * 1024;

@@ -109,7 +109,7 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
             if (v.n % kTileElems) tails[fp.wide] = true;
             bytes = packed_bytes_u(bits, v.n);
             ++nquant;
-            nitems += (v.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk + (v.n % kTileElems ? 1 : 0);
+            nitems += (v.n / kTileElems + tiles_per_chunk(bits) - 1) / tiles_per_chunk(bits) + (v.n % kTileElems ? 1 : 0);
         } else {
             any_fp32 = true;
             bytes = 4 * v.n;
@@ -181,7 +181,7 @@ size_t omc_packed_bytes(omc_format f, uint64_t n) {
 
 size_t omc_compress_workspace_bytes(uint64_t n) {
     if (n == 0 || n > kMaxElems) return 0;
-    return static_cast<size_t>((n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk + 1) * sizeof(Partial);
+    return static_cast<size_t>((n / kTileElems + kMinTilesPerChunk - 1) / kMinTilesPerChunk + 1) * sizeof(Partial);
 }
 
 omc_status omc_compress(const float *v, uint64_t n, omc_format f, int use_pvt, void *codes, float *sb,
@@ -267,7 +267,7 @@ omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_h
             if (g.kind == kGroupFull) {
                 if (!q || pv[i].fp.bits != g.bits || pv[i].fp.variant != g.wide || v.n < kTileElems) continue;
                 pv[i].first_item = next;
-                pv[i].nitems = static_cast<uint32_t>((v.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
+                pv[i].nitems = static_cast<uint32_t>((v.n / kTileElems + tiles_per_chunk(g.bits) - 1) / tiles_per_chunk(g.bits));
                 for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
             } else if (g.kind == kGroupTail) {
                 if (!q || pv[i].fp.wide != g.wide || v.n % kTileElems == 0) continue;
@@ -481,7 +481,7 @@ static omc_status agg_layout(const void *const *plans_host, uint32_t R, AggLayou
         if (al->any_quant[i]) {
             if (n >= kTileElems) present[fmt[i].bits] = true;
             if (n % kTileElems) tails = true;
-            nitems += (n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk + (n % kTileElems ? 1 : 0);
+            nitems += (n / kTileElems + tiles_per_chunk(fmt[i].bits) - 1) / tiles_per_chunk(fmt[i].bits) + (n % kTileElems ? 1 : 0);
         } else {
             flat = true;
             nitems += (n + kChunkElems - 1) / kChunkElems;
@@ -555,7 +555,7 @@ omc_status omc_aggregate_plan_build(const void *const *plans_host, uint32_t nrep
             const bool q = al.any_quant[i] != 0;
             if (g.kind == kGroupFull) {
                 if (!q || av[i].fp.bits != g.bits || n < kTileElems) continue;
-                const uint32_t c_end = static_cast<uint32_t>((n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
+                const uint32_t c_end = static_cast<uint32_t>((n / kTileElems + tiles_per_chunk(g.bits) - 1) / tiles_per_chunk(g.bits));
                 for (uint32_t c = 0; c < c_end; ++c) items[next++] = PlanItem{i, c};
             } else if (g.kind == kGroupTail) {
                 if (!q || n % kTileElems == 0) continue;

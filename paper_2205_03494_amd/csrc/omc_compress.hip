@@ -44,7 +44,8 @@ static int launch_tail(bool wide, uint32_t grid, const CodecArgs &ca, hipStream_
 int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb, Partial *ws,
                     void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
+    const uint32_t tpc = tiles_per_chunk(va.fp.bits);
+    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + tpc - 1) / tpc);
     const bool has_tail = (va.n % kTileElems) != 0;
     CodecArgs ca{};
     ca.arena = static_cast<uint8_t *>(codes);

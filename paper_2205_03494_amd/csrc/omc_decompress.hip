@@ -19,7 +19,8 @@ static int launch_full(uint32_t bits, uint32_t grid, const CodecArgs &ca, hipStr
 
 int launch_decompress(const void *codes, const VarArgs &va, const float *sb, float *out, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + kTilesPerChunk - 1) / kTilesPerChunk);
+    const uint32_t tpc = tiles_per_chunk(va.fp.bits);
+    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + tpc - 1) / tpc);
     CodecArgs ca{};
     ca.arena = static_cast<uint8_t *>(const_cast<void *>(codes));   // never written in this mode
     ca.single.n = va.n;

@@ -16,7 +16,11 @@ constexpr int kTileElems = 64 * kLaneElems;           // 2048
 #define OMC_TUNE_TILES_PER_CHUNK 2
 #endif
 constexpr int kTilesPerChunk = OMC_TUNE_TILES_PER_CHUNK;   // tiles reduced into one partial
-constexpr int kChunkElems = kTileElems * kTilesPerChunk;
+constexpr int kChunkElems = kTileElems * kTilesPerChunk;   // an fp32 variable's work item
+// Tiles per work item of a quantized variable, by code width (measured: 6-bit kernels do better with
+// four, all others with two).  Host and device agree on it through this one function.
+__host__ __device__ constexpr uint32_t tiles_per_chunk(uint32_t bits) { return bits == 6 ? 2u * kTilesPerChunk : kTilesPerChunk; }
+constexpr uint32_t kMinTilesPerChunk = kTilesPerChunk;
 constexpr int kLdsDwords = kTileElems + kTileElems / 32;  // padded code tile for B = 32
 
 // Constants derived from a format once on the host; uniform per variable (scalar registers).

@@ -89,7 +89,7 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     } else {   // a set that exceeds the cache by little still gets most of its hits and is not worth a second, small launch
         uint64_t all_codes = 0;
         for (uint32_t gi = 0; gi < ph->ngroups; ++gi)
-            if (groups[gi].kind == kGroupFull) all_codes += static_cast<uint64_t>(groups[gi].nitems) * kChunkElems * groups[gi].bits / 8;
+            if (groups[gi].kind == kGroupFull) all_codes += static_cast<uint64_t>(groups[gi].nitems) * tiles_per_chunk(groups[gi].bits) * kTileElems * groups[gi].bits / 8;
         if (all_codes <= (static_cast<uint64_t>(OMC_TUNE_KEEP_ALL_MIB) << 20)) keep_budget = all_codes;
     }
     auto take = [&](uint32_t nitems, uint64_t item_bytes) -> uint32_t {   // how many of nitems the budget still covers
@@ -123,7 +123,7 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
             else step_fp32_kernel<kStepAdam><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             rc = static_cast<int>(hipGetLastError());
         } else {
-            const uint32_t kept = take(g.nitems, static_cast<uint64_t>(kChunkElems) * g.bits / 8);
+            const uint32_t kept = take(g.nitems, static_cast<uint64_t>(tiles_per_chunk(g.bits)) * kTileElems * g.bits / 8);
             for (int part = 0; part < 2 && rc == 0; ++part) {              // the cached items, then the streaming ones
                 sa.first_item = g.first_item + (part == 0 ? 0 : kept);
                 sa.nitems = part == 0 ? kept : g.nitems - kept;
