@@ -51,15 +51,21 @@ struct OptConst {
 #ifndef OMC_TUNE_WAVES_ADAM
 #define OMC_TUNE_WAVES_ADAM 2
 #endif
+#ifndef OMC_TUNE_ADAM_WIDE_BITS
+#define OMC_TUNE_ADAM_WIDE_BITS 13
+#endif
 #ifndef OMC_TUNE_PREFETCH_HEAVY
 #define OMC_TUNE_PREFETCH_HEAVY 0
 #endif
 template <int MODE, int B>
 struct Tuning {
     static constexpr int light = (B <= 12) ? OMC_TUNE_WAVES_LIGHT : (OMC_TUNE_WAVES_LIGHT > 3 ? 3 : OMC_TUNE_WAVES_LIGHT);
-    static constexpr int waves = (MODE == kStepAdam) ? OMC_TUNE_WAVES_ADAM
+    // Adam on codes of OMC_TUNE_ADAM_WIDE_BITS bits or more does not fit 256 registers without spilling (and
+    // scratch is memory traffic): one wave per SIMD with the next tile's loads in flight instead
+    static constexpr bool adam_wide = MODE == kStepAdam && B >= OMC_TUNE_ADAM_WIDE_BITS;
+    static constexpr int waves = adam_wide ? 1 : (MODE == kStepAdam) ? OMC_TUNE_WAVES_ADAM
                                  : (MODE == kStepMomentum) ? OMC_TUNE_WAVES_MOMENTUM : light;
-    static constexpr bool prefetch = (MODE <= kStepSgd) ? (OMC_TUNE_PREFETCH != 0) : (OMC_TUNE_PREFETCH_HEAVY != 0);
+    static constexpr bool prefetch = (MODE <= kStepSgd) ? (OMC_TUNE_PREFETCH != 0) : (adam_wide || OMC_TUNE_PREFETCH_HEAVY != 0);
 };
 
 // A value that is the same in every lane (read through a vector load, e.g. from the plan) moved
