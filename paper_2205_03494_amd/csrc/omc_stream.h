@@ -51,6 +51,9 @@ struct OptConst {
 #ifndef OMC_TUNE_WAVES_ADAM
 #define OMC_TUNE_WAVES_ADAM 2
 #endif
+#ifndef OMC_TUNE_DIRECT
+#define OMC_TUNE_DIRECT 1
+#endif
 #ifndef OMC_TUNE_ADAM_WIDE_BITS
 #define OMC_TUNE_ADAM_WIDE_BITS 13
 #endif
@@ -62,6 +65,8 @@ struct Tuning {
     static constexpr int light = (B <= 12) ? OMC_TUNE_WAVES_LIGHT : (OMC_TUNE_WAVES_LIGHT > 3 ? 3 : OMC_TUNE_WAVES_LIGHT);
     // Adam on codes of OMC_TUNE_ADAM_WIDE_BITS bits or more does not fit 256 registers without spilling (and
     // scratch is memory traffic): one wave per SIMD with the next tile's loads in flight instead
+    // byte-multiple code widths: lanes own 4-element groups, fp32 streams skip the LDS transposition
+    static constexpr bool direct = (B % 8 == 0) && (OMC_TUNE_DIRECT != 0);
     static constexpr bool adam_wide = MODE == kStepAdam && B >= OMC_TUNE_ADAM_WIDE_BITS;
     static constexpr int waves = adam_wide ? 1 : (MODE == kStepAdam) ? OMC_TUNE_WAVES_ADAM
                                  : (MODE == kStepMomentum) ? OMC_TUNE_WAVES_MOMENTUM : light;
@@ -266,6 +271,41 @@ __device__ __forceinline__ void lanes_to_code_pieces(const uint32_t (&o)[B], u32
             cq[j] = u32x4{0u, 0u, 0u, 0u};
         }
     }
+    lds_fence();
+}
+
+// Byte-multiple code widths (B = 8 k): a lane that owns the four consecutive elements of each of its
+// eight 16-byte fp32 pieces (elements 256 j + 4 lane ..) owns whole dwords of the packed tile too,
+// k of them per piece: tile dwords k (64 j + lane) + h, h < k, in the lane-local order j k + h that the
+// element loops expect.  The fp32 streams then need no transposition at all; the codes still pass
+// through LDS, so that their global accesses stay 16 bytes per lane.
+template <int B>
+__device__ __forceinline__ void code_pieces_to_strided_lanes(const u32x4 (&cq)[CodePieces<B>::rounds], uint32_t (&w)[B],
+                                                             uint32_t *lds, uint32_t lane) {
+    constexpr uint32_t k = B / 8;
+    u32x4 *l4 = reinterpret_cast<u32x4 *>(lds);
+#pragma unroll
+    for (int r = 0; r < CodePieces<B>::rounds; ++r) l4[r * 64u + lane] = cq[r];   // rounds * 64 == 16 B pieces exactly
+    lds_fence();
+#pragma unroll
+    for (uint32_t j = 0; j < 8; ++j)
+#pragma unroll
+        for (uint32_t h = 0; h < k; ++h) w[j * k + h] = lds[k * (64u * j + lane) + h];
+    lds_fence();
+}
+
+template <int B>
+__device__ __forceinline__ void strided_lanes_to_code_pieces(const uint32_t (&o)[B], u32x4 (&cq)[CodePieces<B>::rounds],
+                                                             uint32_t *lds, uint32_t lane) {
+    constexpr uint32_t k = B / 8;
+#pragma unroll
+    for (uint32_t j = 0; j < 8; ++j)
+#pragma unroll
+        for (uint32_t h = 0; h < k; ++h) lds[k * (64u * j + lane) + h] = o[j * k + h];
+    lds_fence();
+    const u32x4 *l4 = reinterpret_cast<const u32x4 *>(lds);
+#pragma unroll
+    for (int r = 0; r < CodePieces<B>::rounds; ++r) cq[r] = l4[r * 64u + lane];
     lds_fence();
 }
 
@@ -672,13 +712,27 @@ template <int B, int MODE, int VARIANT, bool PREFETCH, bool KEEP>
 __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
                                             uint64_t e0, uint32_t lane, uint32_t *lds, Stage<B, MODE> &st,
                                             FitAcc &acc) {
-    // hand every lane its 32 consecutive elements
+    // hand every lane its 32 elements: consecutive ones, or (byte-multiple code widths) the four
+    // consecutive elements of each of its eight 16-byte pieces, which the fp32 loads delivered already
+    constexpr bool kDirect = Tuning<MODE, B>::direct;
     uint32_t w[B];
     float rg[32], rm[32], rv[32];
-    if (MODE != kCompress) code_pieces_to_lanes<B>(st.cq, w, lds, lane);
-    if (MODE == kCompress || MODE >= kStepSgd) pieces_to_lanes(st.gq, rg, lds, lane);
-    if (MODE >= kStepMomentum) pieces_to_lanes(st.mq, rm, lds, lane);
-    if (MODE == kStepAdam) pieces_to_lanes(st.vq, rv, lds, lane);
+    if constexpr (kDirect) {
+        if (MODE != kCompress) code_pieces_to_strided_lanes<B>(st.cq, w, lds, lane);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (MODE == kCompress || MODE >= kStepSgd) rg[4 * j + i] = st.gq[j][i];
+                if (MODE >= kStepMomentum) rm[4 * j + i] = st.mq[j][i];
+                if (MODE == kStepAdam) rv[4 * j + i] = st.vq[j][i];
+            }
+    } else {
+        if (MODE != kCompress) code_pieces_to_lanes<B>(st.cq, w, lds, lane);
+        if (MODE == kCompress || MODE >= kStepSgd) pieces_to_lanes(st.gq, rg, lds, lane);
+        if (MODE >= kStepMomentum) pieces_to_lanes(st.mq, rm, lds, lane);
+        if (MODE == kStepAdam) pieces_to_lanes(st.vq, rv, lds, lane);
+    }
 
     if (PREFETCH) issue_loads<B, MODE, KEEP>(a, e0 + kTileElems, lane, st);
 
@@ -694,24 +748,33 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
     }
 
     // back to the coalesced layouts and out
+    auto to_pieces = [&](const float (&r)[32], f32x4 (&out)[8]) {
+        if constexpr (kDirect) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) out[j] = f32x4{r[4 * j + 0], r[4 * j + 1], r[4 * j + 2], r[4 * j + 3]};
+        } else {
+            lanes_to_pieces(r, out, lds, lane);
+        }
+    };
     if (MODE == kDecompress) {
         f32x4 out[8];
-        lanes_to_pieces(rg, out, lds, lane);
+        to_pieces(rg, out);
         store_f32_pieces<OMC_TUNE_NT_STATE != 0>(a.vout + e0, lane, out);
         return;
     }
     if (MODE >= kStepMomentum) {
         f32x4 out[8];
-        lanes_to_pieces(rm, out, lds, lane);
+        to_pieces(rm, out);
         store_f32_pieces<StreamHints<MODE, KEEP>::nt_state>(a.st0 + e0, lane, out);
     }
     if (MODE == kStepAdam) {
         f32x4 out[8];
-        lanes_to_pieces(rv, out, lds, lane);
+        to_pieces(rv, out);
         store_f32_pieces<StreamHints<MODE, KEEP>::nt_state>(a.st1 + e0, lane, out);
     }
     u32x4 cout[CodePieces<B>::rounds];
-    lanes_to_code_pieces<B>(o, cout, lds, lane);
+    if constexpr (kDirect) strided_lanes_to_code_pieces<B>(o, cout, lds, lane);
+    else lanes_to_code_pieces<B>(o, cout, lds, lane);
     store_code_pieces<B, StreamHints<MODE, KEEP>::nt_codes>(a.codes + (e0 >> 5) * B, lane, cout);
 }
 
