@@ -66,7 +66,9 @@ struct Tuning {
     // Adam on codes of OMC_TUNE_ADAM_WIDE_BITS bits or more does not fit 256 registers without spilling (and
     // scratch is memory traffic): one wave per SIMD with the next tile's loads in flight instead
     // byte-multiple code widths: lanes own 4-element groups, fp32 streams skip the LDS transposition
-    static constexpr bool direct = (B % 8 == 0) && (OMC_TUNE_DIRECT != 0);
+    // (not for 8-bit momentum: the registers it saves raise that kernel's occupancy from two to three waves
+    // per SIMD, which measures 2 % slower there)
+    static constexpr bool direct = (B % 8 == 0) && (OMC_TUNE_DIRECT != 0) && !(MODE == kStepMomentum && B == 8);
     static constexpr bool adam_wide = MODE == kStepAdam && B >= OMC_TUNE_ADAM_WIDE_BITS;
     static constexpr int waves = adam_wide ? 1 : (MODE == kStepAdam) ? OMC_TUNE_WAVES_ADAM
                                  : (MODE == kStepMomentum) ? OMC_TUNE_WAVES_MOMENTUM : light;
