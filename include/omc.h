@@ -234,8 +234,9 @@ uint64_t omc_plan_transport_bytes(const void *plan_host);
  * work items holding the first 224 MiB (in launch order) access their codes with ordinary cached
  * loads and stores, which lets them come back from the GPU's 256 MB memory-side cache at the
  * next step, and the work items after that limit access theirs with the non-temporal hint so that
- * they do not push the first ones out.  Gradients and optimizer state always carry the hint.
- * Values are the same either way. */
+ * they do not push the first ones out.  Gradients and optimizer state always carry the hint; the
+ * values of fp32 variables share what the codes leave of the 224 MiB under OMC_SGD and carry the
+ * hint otherwise.  Values are the same either way. */
 uint32_t omc_plan_launches(const void *plan_host);
 omc_status omc_step_update_recompress_events(void *arena, size_t arena_bytes, const void *plan_host,
                                              const void *plan_dev, float *sb_table, const float *grads,

@@ -7,6 +7,9 @@
 #ifndef OMC_TUNE_KEEP_BUDGET_MIB
 #define OMC_TUNE_KEEP_BUDGET_MIB 224     // packed codes that stay cached when the set's codes do not fit as a whole
 #endif
+#ifndef OMC_TUNE_KEEP_FP32
+#define OMC_TUNE_KEEP_FP32 1             // bit k: optimizer kind k keeps fp32 values cached (measured: pays for SGD only)
+#endif
 #ifndef OMC_TUNE_KEEP_ALL_MIB
 #define OMC_TUNE_KEEP_ALL_MIB 264        // up to this size all codes stay cached
 #endif
@@ -83,14 +86,19 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     // their codes cached, in launch order, up to a budget below that cache's 256 MB; the codes of all other
     // items carry the non-temporal hint and pass it by.  A group whose items fall on both sides of the limit
     // is launched in two parts.
-    uint64_t keep_budget = static_cast<uint64_t>(OMC_TUNE_KEEP_BUDGET_MIB) << 20;
-    if (opt.flags & OMC_OPT_STREAM_CODES) {
-        keep_budget = 0;      // the caller runs other work between steps: nothing would survive in the cache
-    } else {   // a set that exceeds the cache by little still gets most of its hits and is not worth a second, small launch
+    uint64_t keep_budget = 0;                              // bytes of packed codes that stay cached
+    uint32_t fp32_keep_items = 0;                          // fp32 work items whose values stay cached
+    if (!(opt.flags & OMC_OPT_STREAM_CODES)) {             // (set: the caller runs other work between steps, nothing would survive)
+        const uint64_t cache = static_cast<uint64_t>(OMC_TUNE_KEEP_BUDGET_MIB) << 20;
         uint64_t all_codes = 0;
         for (uint32_t gi = 0; gi < ph->ngroups; ++gi)
             if (groups[gi].kind == kGroupFull) all_codes += static_cast<uint64_t>(groups[gi].nitems) * tiles_per_chunk(groups[gi].bits) * kTileElems * groups[gi].bits / 8;
-        if (all_codes <= (static_cast<uint64_t>(OMC_TUNE_KEEP_ALL_MIB) << 20)) keep_budget = all_codes;
+        // a set that exceeds the cache by little still gets most of its hits and is not worth a second, small launch
+        keep_budget = all_codes <= (static_cast<uint64_t>(OMC_TUNE_KEEP_ALL_MIB) << 20) ? all_codes : cache;
+        // what the codes leave goes to the values of the fp32 variables, which are read and rewritten in place as well
+        // (optimizer state is not worth keeping: measured slower)
+        const uint64_t left = cache > all_codes ? cache - all_codes : 0;
+        if (fp32_group && ((OMC_TUNE_KEEP_FP32 >> opt.kind) & 1)) fp32_keep_items = static_cast<uint32_t>(std::min<uint64_t>(fp32_group->nitems, left / (4ull * kChunkElems)));
     }
     auto take = [&](uint32_t nitems, uint64_t item_bytes) -> uint32_t {   // how many of nitems the budget still covers
         const uint64_t k = std::min<uint64_t>(nitems, keep_budget / item_bytes);
@@ -109,6 +117,7 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
             if (!fuse || fused_done) return;
             sa.fp32_first = fp32_group->first_item;
             sa.fp32_nitems = fp32_group->nitems;
+            sa.fp32_keep_items = fp32_keep_items;
             fused_done = true;
         };
         int rc = mark(0);
@@ -118,6 +127,8 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
             else if (opt.kind == OMC_MOMENTUM) rc = launch_tail<kStepMomentum>(g.wide != 0, sa, st);
             else rc = launch_tail<kStepAdam>(g.wide != 0, sa, st);
         } else if (g.kind == kGroupFp32) {
+            sa.fp32_first = g.first_item;
+            sa.fp32_keep_items = fp32_keep_items;
             if (opt.kind == OMC_SGD) step_fp32_kernel<kStepSgd><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             else if (opt.kind == OMC_MOMENTUM) step_fp32_kernel<kStepMomentum><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);
             else step_fp32_kernel<kStepAdam><<<dim3(g.nitems), dim3(64), 0, st>>>(sa);

@@ -25,6 +25,7 @@ struct StepArgs {
     float *st0, *st1;
     Partial *ws;
     OptConst oc;
+    uint32_t fp32_keep_items;           // the first so many fp32 work items keep their values cached from step to step
 };
 
 // Variables kept in fp32 (paper Sec. 2.4, 2.5): the update alone, 16-byte pieces, coalesced.
@@ -37,9 +38,10 @@ struct StepArgs {
 #ifndef OMC_TUNE_FP32_BATCH
 #define OMC_TUNE_FP32_BATCH 4
 #endif
-template <int MODE>
-__device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) {
+template <int MODE, bool KEEPW>
+__device__ __forceinline__ void fp32_item_body(const StepArgs &sa, uint32_t item) {
     constexpr bool NT = OMC_TUNE_FP32_NT != 0;
+    constexpr bool NTW = NT && !KEEPW;                   // the values themselves: read and rewritten by every step
     constexpr int kFp32Batch = OMC_TUNE_FP32_BATCH;
     const PlanItem *items = reinterpret_cast<const PlanItem *>(sa.plan + sa.item_off);
     const PlanVar *vars = reinterpret_cast<const PlanVar *>(sa.plan + sa.var_off);
@@ -54,13 +56,13 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
     const uint64_t begin = static_cast<uint64_t>(it.chunk) * kChunkElems;
     constexpr int kIters = kChunkElems / 256;
     static_assert(kIters % kFp32Batch == 0, "batches tile the chunk");
-    auto ld = [&](const float *p) {
+    auto ld = [&](const float *p, bool nt = NT) {
         const f32x4 *q = reinterpret_cast<const f32x4 *>(p);
-        return NT ? __builtin_nontemporal_load(q) : *q;
+        return nt ? __builtin_nontemporal_load(q) : *q;
     };
-    auto st = [&](float *p, const f32x4 &x) {
+    auto st = [&](float *p, const f32x4 &x, bool nt = NT) {
         f32x4 *q = reinterpret_cast<f32x4 *>(p);
-        if (NT) __builtin_nontemporal_store(x, q); else *q = x;
+        if (nt) __builtin_nontemporal_store(x, q); else *q = x;
     };
     for (int j0 = 0; j0 < kIters; j0 += kFp32Batch) {
         const uint64_t e0 = begin + (static_cast<uint64_t>(j0) * 64 + lane) * 4;
@@ -69,7 +71,7 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
 #pragma unroll
             for (int u = 0; u < kFp32Batch; ++u) {
                 const uint64_t e = e0 + static_cast<uint64_t>(u) * 256;
-                xw[u] = ld(w + e);
+                xw[u] = ld(w + e, NTW);
                 xg[u] = ld(g + e);
                 xm[u] = (MODE >= kStepMomentum) ? ld(m + e) : f32x4{0, 0, 0, 0};
                 xv[u] = (MODE == kStepAdam) ? ld(v + e) : f32x4{0, 0, 0, 0};
@@ -84,7 +86,7 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
                     xm[u][c] = tm;
                     xv[u][c] = tv;
                 }
-                st(w + e, xw[u]);
+                st(w + e, xw[u], NTW);
                 if (MODE >= kStepMomentum) st(m + e, xm[u]);
                 if (MODE == kStepAdam) st(v + e, xv[u]);
             }
@@ -101,6 +103,12 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
             }
         }
     }
+}
+
+template <int MODE>
+__device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) {
+    if (item - sa.fp32_first < sa.fp32_keep_items) fp32_item_body<MODE, true>(sa, item);
+    else fp32_item_body<MODE, false>(sa, item);
 }
 
 // KEEP: the launch's work items keep their packed codes cached from step to step; without it the code
