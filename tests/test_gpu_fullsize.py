@@ -123,6 +123,26 @@ def test_config3_full_size_partial_quantization_three_formats_adam():
     assert ns >= 6
 
 
+def test_config3_set_under_sgd_fp32_values_on_both_sides_of_the_cache_budget():
+    """Same set as configuration 3 under plain SGD: 78 MB of codes stay cached and the 249 MB of fp32 matrices get
+    what is left of the budget, so their work items fall on both sides of that limit within one launch."""
+    specs = synth.conformer_varset(512, 17, 2048, 32, frontend=True)
+    mask = synth.ppq_mask(specs, 0.5, 3)
+    choices = [(4, 3), (3, 7), (5, 10)]
+    fmts = [choices[i % 3] for i in range(len(specs))]
+    f32 = [i for i in range(len(specs)) if not mask[i] and specs[i].is_matrix]
+    done, cut = 0, None
+    for k, i in enumerate(f32):                        # fp32 items follow the plan's variable order
+        done += 4 * specs[i].n
+        if done > (224 << 20) - 78_000_000:
+            cut = f32[max(k - 1, 0):k + 2]
+            break
+    assert cut
+    ns, total = run_fullsize(specs, mask, fmts, kind=0, lr=0.01, steps=2, seed=7, max_sample_elems=14_000_000,
+                             first_samples=cut + [f32[0], f32[-1]])
+    assert ns >= 6
+
+
 def test_config4_full_size_momentum_11bit():
     specs = synth.conformer_varset(1024, 24, 4096, 32, frontend=False)
     mask = np.array([s.is_matrix for s in specs])
