@@ -22,8 +22,10 @@
  *     as their buffers do not.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
  *     on it and the call returns without synchronising.
- *   - Arguments are validated on the host before anything is enqueued: a status other than
- *     OMC_OK means that no kernel was launched and no buffer was touched.
+ *   - Arguments are validated on the host before anything is enqueued: every status other than
+ *     OMC_OK and OMC_ERR_DEVICE means that no kernel was launched and no buffer was touched.
+ *     OMC_ERR_DEVICE is the HIP runtime refusing a launch; a call that needs several launches may
+ *     then already have enqueued the earlier ones, so the buffers it writes are undefined.
  *   - Device buffers of packed codes, fp32 values, gradients and optimizer state must be
  *     16-byte aligned (OMC_ERR_ALIGN otherwise).
  *
@@ -48,7 +50,11 @@
  * (s, b) minimise || s*Vtilde + b*1 - V ||_2 over the n elements:
  *     s = (n SUM V Vt - SUM V SUM Vt) / (n SUM Vt^2 - (SUM Vt)^2),   b = (SUM V - s SUM Vt) / n,
  * evaluated in fp64 and stored as fp32; s = 1 when all Vtilde_k are equal (the degenerate case).
- * The sums are accumulated in fp64 in a fixed order, so results are bit-identical from run to run.
+ * The four sums are accumulated in a fixed order, so results are bit-identical from run to run:
+ * in fp64 for formats of fewer than 16 mantissa bits (every term is exact; the additions round, which
+ * moves the fp32 result only if it lies within ~1e-16 of a rounding boundary), and in fp64 with the
+ * rounding error of every addition carried along (about 106 bits) for man_bits >= 16, where b is a
+ * difference of nearly equal sums and plain fp64 additions would show in its last bits.
  */
 #ifndef OMC_H
 #define OMC_H
@@ -93,8 +99,8 @@ typedef struct {
     uint32_t flags;       /* OMC_VAR_* */
 } omc_var;
 
-/* The parameter update applied to the decompressed values (Sec. 2.1: "applies the gradients to
- * update them"; the paper does not name the client optimizer).  Every fp32 operation is rounded
+/* The parameter update applied to the decompressed values (Sec. 2.1, backward path; the paper does
+ * not name the client optimizer).  Every fp32 operation is rounded
  * on its own, in the order written:
  *   OMC_SGD       V' = V - fl(lr*g)
  *   OMC_MOMENTUM  m' = fl(fl(momentum*m) + g);                       V' = V - fl(lr*m')         state0 = m
@@ -172,10 +178,12 @@ omc_status omc_decompress(const void *codes, uint64_t n, omc_format f, const flo
  * omc_plan_build: validates the table (formats, n >= 1, alignment of offsets, no two variables
  *   overlapping in the arena or in the aux range) and fills plan_host[0 .. plan_bytes).
  * omc_plan_workspace_bytes / omc_plan_arena_bytes / omc_plan_aux_elems: device workspace a step
- *   needs, and the extent of arena / aux that the plan addresses (0 for a corrupt blob). */
+ *   needs, and the extent of arena / aux that the plan addresses (0 for a corrupt blob).
+ * omc_workspace_bytes: the same workspace size straight from a variable table (0 if invalid). */
 size_t omc_plan_bytes(const omc_var *vars_host, uint32_t nvars);
 omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_host, size_t plan_bytes);
 size_t omc_plan_workspace_bytes(const void *plan_host);
+size_t omc_workspace_bytes(const omc_var *vars_host, uint32_t nvars);
 size_t omc_plan_arena_bytes(const void *plan_host);
 uint64_t omc_plan_aux_elems(const void *plan_host);
 

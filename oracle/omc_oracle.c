@@ -347,33 +347,56 @@ typedef struct {
     float bias_corr1, bias_corr2;      /* fp32(1 - beta^t)  computed in fp64 by the caller */
 } orc_opt;
 
+/* fl(x): the fp32 number nearest to the double x.  Each operation below is carried out on the exact
+ * double images of its fp32 operands and then rounded with fl().  For +, -, *, / and sqrt of fp32
+ * operands this equals the correctly rounded fp32 operation (a double keeps more than 2*24+2 bits, so
+ * the intermediate rounding to double cannot move the final one): "every operation rounded on its own". */
+static float fl(double x) { return (float)x; }
+
+/* plain SGD:  w <- w - lr g */
+static float sgd_rule(float w, float g, const orc_opt *o)
+{
+    float scaled_g = fl((double)o->lr * (double)g);
+    return fl((double)w - (double)scaled_g);
+}
+
+/* SGD with momentum (no dampening, no Nesterov):  m <- mu m + g;  w <- w - lr m */
+static float momentum_rule(float w, float g, float *m, const orc_opt *o)
+{
+    float decayed = fl((double)o->momentum * (double)*m);
+    *m = fl((double)decayed + (double)g);
+    float stepv = fl((double)o->lr * (double)*m);
+    return fl((double)w - (double)stepv);
+}
+
+/* Adam:  m <- b1 m + (1-b1) g;  v <- b2 v + ((1-b2) g) g;
+ *        w <- w - (lr (m / c1)) / (sqrt(v / c2) + eps),  c1 = 1-b1^t, c2 = 1-b2^t */
+static float adam_rule(float w, float g, float *m, float *v, const orc_opt *o)
+{
+    float first_old = fl((double)o->beta1 * (double)*m);
+    float first_new = fl((double)o->one_minus_beta1 * (double)g);
+    *m = fl((double)first_old + (double)first_new);
+
+    float second_old = fl((double)o->beta2 * (double)*v);
+    float g_weighted = fl((double)o->one_minus_beta2 * (double)g);
+    float second_new = fl((double)g_weighted * (double)g);
+    *v = fl((double)second_old + (double)second_new);
+
+    float m_unbiased = fl((double)*m / (double)o->bias_corr1);
+    float v_unbiased = fl((double)*v / (double)o->bias_corr2);
+    float numerator = fl((double)o->lr * (double)m_unbiased);
+    float root = fl(sqrt((double)v_unbiased));
+    float denominator = fl((double)root + (double)o->eps);
+    float stepv = fl((double)numerator / (double)denominator);
+    return fl((double)w - (double)stepv);
+}
+
 static float update_one(float w, float g, float *m, float *v, const orc_opt *o)
 {
-    if (o->kind == 0) {
-        float d = o->lr * g;
-        return w - d;
-    } else if (o->kind == 1) {
-        float mm = o->momentum * (*m);
-        float mn = mm + g;
-        *m = mn;
-        float d = o->lr * mn;
-        return w - d;
-    } else {
-        float m1 = o->beta1 * (*m);
-        float m2 = o->one_minus_beta1 * g;
-        float mn = m1 + m2;
-        float v1 = o->beta2 * (*v);
-        float v2 = o->one_minus_beta2 * g;
-        float v3 = v2 * g;
-        float vn = v1 + v3;
-        *m = mn; *v = vn;
-        float mhat = mn / o->bias_corr1;
-        float vhat = vn / o->bias_corr2;
-        float num = o->lr * mhat;
-        float rt = sqrtf(vhat);
-        float den = rt + o->eps;
-        float d = num / den;
-        return w - d;
+    switch (o->kind) {
+    case 0:  return sgd_rule(w, g, o);
+    case 1:  return momentum_rule(w, g, m, o);
+    default: return adam_rule(w, g, m, v, o);
     }
 }
 

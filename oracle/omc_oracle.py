@@ -18,12 +18,16 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "omc_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
+# tests/test_oracle_mutations.py points this at deliberately broken builds to show that the pins notice
+_LIB_OVERRIDE = os.environ.get("OMC_ORACLE_LIBRARY")
 
 GCC_FLAGS = ["-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (always when force, else when stale or missing)."""
+    if _LIB_OVERRIDE and not force:
+        return _LIB_OVERRIDE
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         subprocess.check_call(["gcc", *GCC_FLAGS, _SRC, "-o", _LIB, "-lm"])

@@ -44,6 +44,7 @@ bool make_fmt_params(omc_format f, FmtParams *out) {
     const int top_exp = top_field(f) - bias;
     p.wide = (M == 23 || top_exp + 23 - M > 127) ? 1u : 0u;
     p.variant = (E == 4 && M == 3 && bias == 7) ? 2u : (E == 2 && M == 3 && bias == 1) ? 3u : p.wide;
+    if (M >= 16) p.variant += kVariantExact;   // the fit's sums carry their rounding errors along
     p.exp_adj = 127 + M;
     p.dec_scale = std::ldexp(1.0f, 127 - bias);
     p.enc_scale = std::ldexp(1.0f, bias - 127);
@@ -62,16 +63,55 @@ constexpr uint64_t kMaxElems = 1ull << 36;
 
 static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
+// 64-bit checksum of the plan body (everything after the header), eight bytes at a time in four
+// independent lanes so that it runs at memory speed: every entry point verifies it.
+static uint64_t body_checksum(const uint8_t *p, uint64_t nbytes) {
+    uint64_t h[4] = {0x9e3779b97f4a7c15ull, 0xc2b2ae3d27d4eb4full, 0x165667b19e3779f9ull, 0x27d4eb2f165667c5ull};
+    const uint64_t nwords = nbytes / 8;
+    uint64_t i = 0;
+    for (; i + 4 <= nwords; i += 4)
+        for (int l = 0; l < 4; ++l) {
+            uint64_t w;
+            std::memcpy(&w, p + 8 * (i + l), 8);
+            h[l] = (h[l] ^ w) * 0x100000001b3ull;
+            h[l] = (h[l] << 29) | (h[l] >> 35);
+        }
+    for (; i < nwords; ++i) {
+        uint64_t w;
+        std::memcpy(&w, p + 8 * i, 8);
+        h[0] = (h[0] ^ w) * 0x100000001b3ull;
+        h[0] = (h[0] << 29) | (h[0] >> 35);
+    }
+    uint64_t tail = 0;
+    std::memcpy(&tail, p + 8 * nwords, nbytes - 8 * nwords);
+    uint64_t r = (h[0] ^ tail) * 0x100000001b3ull;
+    for (int l = 1; l < 4; ++l) r = ((r << 31) | (r >> 33)) ^ (h[l] * 0x9e3779b97f4a7c15ull);
+    return r ^ nbytes;
+}
+
+// Header consistency, checksum of the body, and bounds of everything the host reads from the body
+// (the launch groups).  The item and variable tables are what the checksum vouches for: the builder
+// wrote them from a validated variable table.
 const PlanHeader *plan_check(const void *plan_host) {
     if (!plan_host) return nullptr;
     const PlanHeader *ph = static_cast<const PlanHeader *>(plan_host);
     if (ph->magic != kPlanMagic || ph->version != kPlanVersion) return nullptr;
+    if (ph->nvars == 0 || ph->nitems > 0x7fffffffu || ph->ngroups > kVariants * 33u + 3u) return nullptr;
     if (ph->var_off != sizeof(PlanHeader)) return nullptr;
     if (ph->item_off != ph->var_off + static_cast<uint64_t>(ph->nvars) * sizeof(PlanVar)) return nullptr;
     if (ph->group_off != ph->item_off + static_cast<uint64_t>(ph->nitems) * sizeof(PlanItem)) return nullptr;
     if (ph->total_bytes != align_up(ph->group_off + static_cast<uint64_t>(ph->ngroups) * sizeof(PlanGroup), 16))
         return nullptr;
     if (ph->ws_bytes != std::max<uint64_t>(16, static_cast<uint64_t>(ph->nitems) * sizeof(Partial))) return nullptr;
+    const uint8_t *base = static_cast<const uint8_t *>(plan_host);
+    if (ph->checksum != body_checksum(base + sizeof(PlanHeader), ph->total_bytes - sizeof(PlanHeader))) return nullptr;
+    const PlanGroup *groups = reinterpret_cast<const PlanGroup *>(base + ph->group_off);
+    for (uint32_t g = 0; g < ph->ngroups; ++g) {
+        if (groups[g].kind > kGroupFp32) return nullptr;
+        if (static_cast<uint64_t>(groups[g].first_item) + groups[g].nitems > ph->nitems) return nullptr;
+        if (groups[g].kind == kGroupFull && (groups[g].bits < 2 || groups[g].bits > 32 || groups[g].wide >= kVariants))
+            return nullptr;
+    }
     return ph;
 }
 
@@ -87,7 +127,7 @@ struct PlanLayout {
 static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *pl) {
     if (!vars) return OMC_ERR_NULL;
     if (nvars == 0) return OMC_ERR_SIZE;
-    bool present[132] = {false};  // 4 * bits + variant
+    bool present[kVariants * 33] = {false};  // kVariants * bits + variant
     bool tails[2] = {false, false};
     bool any_fp32 = false;
     uint64_t nitems = 0;
@@ -105,7 +145,7 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
             const uint32_t bits = 1u + v.fmt.exp_bits + v.fmt.man_bits;
             FmtParams fp;
             make_fmt_params(v.fmt, &fp);
-            if (v.n >= kTileElems) present[4 * bits + fp.variant] = true;
+            if (v.n >= kTileElems) present[kVariants * bits + fp.variant] = true;
             if (v.n % kTileElems) tails[fp.wide] = true;
             bytes = packed_bytes_u(bits, v.n);
             ++nquant;
@@ -127,8 +167,8 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
     };
     if (overlaps(data) || overlaps(aux)) return OMC_ERR_SIZE;
     pl->groups.clear();
-    for (uint32_t k = 8; k < 132; ++k)
-        if (present[k]) pl->groups.push_back(PlanGroup{kGroupFull, k / 4, k % 4, 0, 0, 0});
+    for (uint32_t k = 2 * kVariants; k < kVariants * 33; ++k)
+        if (present[k]) pl->groups.push_back(PlanGroup{kGroupFull, k / kVariants, k % kVariants, 0, 0, 0});
     for (uint32_t w = 0; w < 2; ++w)
         if (tails[w]) pl->groups.push_back(PlanGroup{kGroupTail, 0, w, 0, 0, 0});
     if (any_fp32) pl->groups.push_back(PlanGroup{kGroupFp32, 0, 0, 0, 0, 0});
@@ -296,8 +336,14 @@ omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_h
     ph->arena_bytes = arena_bytes;
     ph->aux_elems = aux_elems;
     ph->ws_bytes = std::max<uint64_t>(16, static_cast<uint64_t>(pl.nitems) * sizeof(Partial));
-    ph->checksum = 0;
+    ph->checksum = body_checksum(base + sizeof(PlanHeader), pl.total - sizeof(PlanHeader));
     return OMC_OK;
+}
+
+size_t omc_workspace_bytes(const omc_var *vars_host, uint32_t nvars) {
+    PlanLayout pl;
+    if (plan_layout(vars_host, nvars, &pl) != OMC_OK) return 0;
+    return static_cast<size_t>(std::max<uint64_t>(16, static_cast<uint64_t>(pl.nitems) * sizeof(Partial)));
 }
 
 size_t omc_plan_workspace_bytes(const void *plan_host) {

@@ -5,10 +5,22 @@ namespace omc {
 
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void finalize_single_kernel(const Partial *__restrict__ ws, uint32_t nparts,
-                                                                  int has_tail, uint64_t n, int use_pvt,
+                                                                  int has_tail, uint64_t n, int use_pvt, int exact,
                                                                   float *__restrict__ sb) {
     __shared__ double red[NW * 10];
-    finalize_variable<NW>(ws, nparts, has_tail ? ws + nparts : nullptr, n, use_pvt != 0, sb, red);
+    finalize_variable<NW>(ws, nparts, has_tail ? ws + nparts : nullptr, n, use_pvt != 0, exact != 0, sb, red);
+}
+
+// Variants 0 / 1 (add-subtract or ldexp rounding) and, for code widths that can hold 16 mantissa bits,
+// 4 / 5 (the same with error-carrying sums).
+template <int BITS>
+static void launch_generic_variant(uint32_t variant, uint32_t grid, const CodecArgs &ca, hipStream_t st) {
+    if constexpr (BITS >= 18) {
+        if (variant == 4) { codec_kernel<BITS, kCompress, 4><<<dim3(grid), dim3(64), 0, st>>>(ca); return; }
+        if (variant == 5) { codec_kernel<BITS, kCompress, 5><<<dim3(grid), dim3(64), 0, st>>>(ca); return; }
+    }
+    if (variant == 1) codec_kernel<BITS, kCompress, 1><<<dim3(grid), dim3(64), 0, st>>>(ca);
+    else codec_kernel<BITS, kCompress, 0><<<dim3(grid), dim3(64), 0, st>>>(ca);
 }
 
 // One full-tile launch: `grid` workgroups of the kernel for (bits, variant).
@@ -24,8 +36,7 @@ static int launch_full(uint32_t bits, uint32_t variant, uint32_t grid, const Cod
     switch (bits) {
 #define X(BITS)                                                                                  \
     case BITS:                                                                                   \
-        if (variant == 1) codec_kernel<BITS, kCompress, 1><<<dim3(grid), dim3(64), 0, st>>>(ca); \
-        else codec_kernel<BITS, kCompress, 0><<<dim3(grid), dim3(64), 0, st>>>(ca);              \
+        launch_generic_variant<BITS>(variant, grid, ca, st);                                     \
         break;
         OMC_FOR_EACH_BITS(X)
 #undef X
@@ -65,12 +76,13 @@ int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes,
         if (rc != 0) return rc;
     }
     // the width of the reduction depends on the size alone, so results do not depend on the run
+    const int exact = variant_exact(va.fp.variant) ? 1 : 0;
     if (nchunks <= 256)
-        finalize_single_kernel<1><<<dim3(1), dim3(64), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
+        finalize_single_kernel<1><<<dim3(1), dim3(64), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
     else if (nchunks <= 2048)
-        finalize_single_kernel<4><<<dim3(1), dim3(256), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
+        finalize_single_kernel<4><<<dim3(1), dim3(256), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
     else
-        finalize_single_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, sb);
+        finalize_single_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
     return static_cast<int>(hipGetLastError());
 }
 

@@ -3,7 +3,10 @@
 // compress, discard).  The weight gradient dW = X^T dY is formed on the matrix cores and consumed in
 // the epilogue of the same kernel: the tile's codes are read, decoded and transformed (Sec. 2.2,
 // 2.3), updated with the accumulators as gradient, rounded and written back, and the sums of the fit
-// are taken on the way.  The fp32 gradient never exists in memory (unless the caller asks for a copy).
+// are taken on the way.  With an 8-bit format and enough tiles for the chip the fp32 gradient never exists
+// in memory (unless the caller asks for a copy); on the other routes -- contraction split between
+// workgroups, code widths other than 8, the 16-wave kernel -- the accumulators pass through the workspace
+// once and a second kernel consumes them.
 //
 // Tiling.  Workgroup = 4 waves, tile of W = 256 rows (k) x 128 columns (n), contraction over the M rows of
 // X and dY in steps of 32.  Both operands are contraction-strided in memory, so threads load 4 x 4
@@ -122,6 +125,7 @@ __device__ __forceinline__ void dw_finish_wave(const DwArgs &a, const f32x16 (&a
     if (lane == 0) {
         Partial p;
         p.sV = fit.sV; p.sT = fit.sT; p.sVT = fit.sVT; p.sTT = fit.sTT;
+        p.lV = p.lT = p.lVT = p.lTT = 0.0;               // 8-bit formats: plain fp64 sums
         p.tmin = tmin; p.tmax = tmax; p.pad[0] = p.pad[1] = 0;
         *slot = p;
     }
@@ -396,9 +400,9 @@ __global__ __launch_bounds__(1024, 1) void dw_update_ws_kernel(DwArgs a) {
 
 template <int NW>
 __global__ __launch_bounds__(64 * NW) void dw_finalize_kernel(const Partial *__restrict__ ws, uint32_t nparts, uint64_t n,
-                                                              int use_pvt, float *__restrict__ sb) {
+                                                              int use_pvt, int exact, float *__restrict__ sb) {
     __shared__ double red[NW * 10];
-    finalize_variable<NW>(ws, nparts, nullptr, n, use_pvt != 0, sb, red);
+    finalize_variable<NW>(ws, nparts, nullptr, n, use_pvt != 0, exact != 0, sb, red);
 }
 
 // one Partial per 16-row x 128-column slab (the finest grain any of the update kernels uses)
@@ -477,17 +481,18 @@ int launch_dw_update(const uint16_t *X, const uint16_t *dY, void *codes, const F
     if (a.park) {                                          // the slab kernels do the update, whatever the code width
         const uint32_t tx = K / cfg.rows;
         int rc;
-        if (opt.kind == OMC_SGD) rc = launch_dw_generic_sgd(fp.bits, fp.wide, cfg.rows, a, tiles, tx, st);
-        else if (opt.kind == OMC_MOMENTUM) rc = launch_dw_generic_momentum(fp.bits, fp.wide, cfg.rows, a, tiles, tx, st);
-        else rc = launch_dw_generic_adam(fp.bits, fp.wide, cfg.rows, a, tiles, tx, st);
+        if (opt.kind == OMC_SGD) rc = launch_dw_generic_sgd(fp.bits, fp.variant == 2 || fp.variant == 3 ? 0u : fp.variant, cfg.rows, a, tiles, tx, st);
+        else if (opt.kind == OMC_MOMENTUM) rc = launch_dw_generic_momentum(fp.bits, fp.variant == 2 || fp.variant == 3 ? 0u : fp.variant, cfg.rows, a, tiles, tx, st);
+        else rc = launch_dw_generic_adam(fp.bits, fp.variant == 2 || fp.variant == 3 ? 0u : fp.variant, cfg.rows, a, tiles, tx, st);
         if (rc != 0) return rc;
         nparts = static_cast<uint32_t>(static_cast<uint64_t>(K) * N / kTileElems);
     }
     const uint64_t n = static_cast<uint64_t>(K) * N;
     // the width of the reduction depends on the sizes alone, so results do not depend on the run
-    if (nparts <= 256) dw_finalize_kernel<1><<<dim3(1), dim3(64), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
-    else if (nparts <= 2048) dw_finalize_kernel<4><<<dim3(1), dim3(256), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
-    else dw_finalize_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(a.ws, nparts, n, use_pvt, sb);
+    const int exact = variant_exact(fp.variant) ? 1 : 0;
+    if (nparts <= 256) dw_finalize_kernel<1><<<dim3(1), dim3(64), 0, st>>>(a.ws, nparts, n, use_pvt, exact, sb);
+    else if (nparts <= 2048) dw_finalize_kernel<4><<<dim3(1), dim3(256), 0, st>>>(a.ws, nparts, n, use_pvt, exact, sb);
+    else dw_finalize_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(a.ws, nparts, n, use_pvt, exact, sb);
     return static_cast<int>(hipGetLastError());
 }
 

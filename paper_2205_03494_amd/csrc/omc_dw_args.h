@@ -23,11 +23,11 @@ struct DwArgs {
 };
 
 // Second kernel of omc_dw_update_recompress for code widths other than 8: one launcher per optimizer.
-int launch_dw_generic_sgd(uint32_t bits, uint32_t wide, uint32_t rows, const DwArgs &a, uint32_t tiles, uint32_t tiles_x,
+int launch_dw_generic_sgd(uint32_t bits, uint32_t variant, uint32_t rows, const DwArgs &a, uint32_t tiles, uint32_t tiles_x,
                           hipStream_t st);
-int launch_dw_generic_momentum(uint32_t bits, uint32_t wide, uint32_t rows, const DwArgs &a, uint32_t tiles, uint32_t tiles_x,
+int launch_dw_generic_momentum(uint32_t bits, uint32_t variant, uint32_t rows, const DwArgs &a, uint32_t tiles, uint32_t tiles_x,
                                hipStream_t st);
-int launch_dw_generic_adam(uint32_t bits, uint32_t wide, uint32_t rows, const DwArgs &a, uint32_t tiles, uint32_t tiles_x,
+int launch_dw_generic_adam(uint32_t bits, uint32_t variant, uint32_t rows, const DwArgs &a, uint32_t tiles, uint32_t tiles_x,
                            hipStream_t st);
 
 }  // namespace omc

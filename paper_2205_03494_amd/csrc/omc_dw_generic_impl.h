@@ -10,7 +10,7 @@
 
 namespace omc {
 
-template <int B, int MODE, bool WIDE>
+template <int B, int MODE, bool WIDE, bool EXACT = false>
 __global__ __launch_bounds__(64, 2) void dw_reduce_update_generic_kernel(DwArgs a, uint32_t tiles_x, uint32_t rows) {
     __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
     const uint32_t lane = threadIdx.x;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(64, 2) void dw_reduce_update_generic_kernel(DwArgs 
             __builtin_nontemporal_store(og[j], reinterpret_cast<f32x4 *>(row_f32(a.dW_out, q >> 5)) + (q & 31u));
         }
     }
-    cycle_generic<B, MODE, WIDE>(ta, a.fp, a.oc, w, rg, rm, rv, o, fit);
+    cycle_generic<B, MODE, WIDE, EXACT>(ta, a.fp, a.oc, w, rg, rm, rv, o, fit);
 
     // ---- back out -----------------------------------------------------------------------------------------
     if (MODE >= kStepMomentum) {
@@ -135,18 +135,30 @@ __global__ __launch_bounds__(64, 2) void dw_reduce_update_generic_kernel(DwArgs 
         const uint32_t q = j * 64u + lane;
         if (CodePieces<B>::in_tile(j, q)) reinterpret_cast<u32x4 *>(row_codes(q / B))[q % B] = cout[j];
     }
-    fit.reduce_and_store(a.ws + blockIdx.x);
+    fit.template reduce_and_store<EXACT>(a.ws + blockIdx.x);
+}
+
+// variant: FmtParams::variant (0 / 1 rounding by add-subtract / ldexp; 4 / 5 the same with error-carrying sums,
+// which only code widths of 18 bits and more can ask for)
+template <int BITS, int MODE>
+inline void launch_dw_generic_variant(uint32_t variant, dim3 grid, const DwArgs &a, uint32_t tiles_x, uint32_t rows,
+                                      hipStream_t st) {
+    if constexpr (BITS >= 18) {
+        if (variant == 4) { dw_reduce_update_generic_kernel<BITS, MODE, false, true><<<grid, dim3(64), 0, st>>>(a, tiles_x, rows); return; }
+        if (variant == 5) { dw_reduce_update_generic_kernel<BITS, MODE, true, true><<<grid, dim3(64), 0, st>>>(a, tiles_x, rows); return; }
+    }
+    if (variant == 1) dw_reduce_update_generic_kernel<BITS, MODE, (BITS >= 9)><<<grid, dim3(64), 0, st>>>(a, tiles_x, rows);
+    else dw_reduce_update_generic_kernel<BITS, MODE, false><<<grid, dim3(64), 0, st>>>(a, tiles_x, rows);
 }
 
 template <int MODE>
-inline int launch_dw_generic_mode(uint32_t bits, uint32_t wide, uint32_t rows, const DwArgs &a, uint32_t tiles,
+inline int launch_dw_generic_mode(uint32_t bits, uint32_t variant, uint32_t rows, const DwArgs &a, uint32_t tiles,
                                   uint32_t tiles_x, hipStream_t st) {
     const dim3 grid(tiles * 4u * (rows / 128u) * 2u);        // one wave per slab of 16 rows
     switch (bits) {
-#define X(BITS)                                                                                                        \
-    case BITS:                                                                                                         \
-        if (wide) dw_reduce_update_generic_kernel<BITS, MODE, (BITS >= 9)><<<grid, dim3(64), 0, st>>>(a, tiles_x, rows); \
-        else dw_reduce_update_generic_kernel<BITS, MODE, false><<<grid, dim3(64), 0, st>>>(a, tiles_x, rows);           \
+#define X(BITS)                                                                  \
+    case BITS:                                                                   \
+        launch_dw_generic_variant<BITS, MODE>(variant, grid, a, tiles_x, rows, st); \
         break;
         OMC_FOR_EACH_BITS(X)
 #undef X

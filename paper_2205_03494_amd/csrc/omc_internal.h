@@ -37,24 +37,34 @@ struct FmtParams {
     uint32_t wide;           // 1: round with ldexp/rint (top binade + 23 - M would overflow fp32, or M == 23)
     uint32_t variant;        // kernel variant: 0 add/subtract rounding, 1 = wide, 2 = the format is OCP FP8 E4M3
                              // except for its top code (S1E4M3, bias 7), 3 = the format is the OCP microscaling
-                             // 6-bit E2M3 element (S1E2M3, bias 1): hardware conversions apply
+                             // 6-bit E2M3 element (S1E2M3, bias 1): hardware conversions apply; 4 / 5 = 0 / 1
+                             // with the fit's sums carried as (sum, error) pairs (16 or more mantissa bits)
     int32_t exp_adj;         // 127 + M
     float dec_scale;         // 2^(127 - bias)
     float enc_scale;         // 2^(bias - 127)
     float maxval;            // largest representable magnitude
 };
 
-// Per-chunk partial sums of the least-squares fit (paper Sec. 2.3).
+// Kernel variants 4 and 5 (see FmtParams::variant).
+constexpr uint32_t kVariantExact = 4;
+__host__ __device__ constexpr bool variant_exact(uint32_t variant) { return variant >= kVariantExact; }
+__host__ __device__ constexpr bool variant_wide(uint32_t variant) { return variant == 1 || variant == 5; }
+constexpr uint32_t kVariants = 6;
+
+// Per-chunk partial sums of the least-squares fit (paper Sec. 2.3).  The four sums are unevaluated
+// pairs s + l: the kernels of formats with fewer than 16 mantissa bits leave l = 0, the others carry
+// the rounding errors of their additions there (see FitAcc).
 struct Partial {
     double sV, sT, sVT, sTT;
+    double lV, lT, lVT, lTT;
     float tmin, tmax;
     uint32_t pad[2];
 };
-static_assert(sizeof(Partial) == 48, "Partial layout");
+static_assert(sizeof(Partial) == 80, "Partial layout");
 
 // ---- plan blob ---------------------------------------------------------------------------
 constexpr uint32_t kPlanMagic = 0x434d4f50u;  // "POMC"
-constexpr uint32_t kPlanVersion = 4;
+constexpr uint32_t kPlanVersion = 5;
 
 struct PlanHeader {
     uint32_t magic, version;

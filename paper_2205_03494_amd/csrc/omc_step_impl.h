@@ -146,6 +146,17 @@ __global__ __launch_bounds__(64, (VARIANT == 3 ? OMC_TUNE_WAVES_FP6 : Tuning<MOD
     do_chunk<B, MODE, VARIANT, KEEP>(a, fp, sa.oc, it.chunk, lds, sa.ws + item);
 }
 
+// Variants 0 / 1 and, for code widths that can hold 16 mantissa bits, 4 / 5 (error-carrying sums).
+template <int BITS, int MODE, bool KEEP>
+inline void launch_step_generic_variant(uint32_t variant, dim3 grid, dim3 block, const StepArgs &sa, hipStream_t st) {
+    if constexpr (BITS >= 18) {
+        if (variant == 4) { step_kernel<BITS, MODE, 4, KEEP><<<grid, block, 0, st>>>(sa); return; }
+        if (variant == 5) { step_kernel<BITS, MODE, 5, KEEP><<<grid, block, 0, st>>>(sa); return; }
+    }
+    if (variant == 1) step_kernel<BITS, MODE, 1, KEEP><<<grid, block, 0, st>>>(sa);
+    else step_kernel<BITS, MODE, 0, KEEP><<<grid, block, 0, st>>>(sa);
+}
+
 template <int MODE, bool KEEP>
 inline int launch_step_group_keep(uint32_t bits, uint32_t variant, const StepArgs &sa, hipStream_t st) {
     const dim3 grid(sa.nitems + sa.fp32_nitems), block(64);
@@ -161,8 +172,7 @@ inline int launch_step_group_keep(uint32_t bits, uint32_t variant, const StepArg
     switch (bits) {
 #define X(BITS)                                                              \
     case BITS:                                                               \
-        if (variant == 1) step_kernel<BITS, MODE, 1, KEEP><<<grid, block, 0, st>>>(sa);   \
-        else step_kernel<BITS, MODE, 0, KEEP><<<grid, block, 0, st>>>(sa);       \
+        launch_step_generic_variant<BITS, MODE, KEEP>(variant, grid, block, sa, st); \
         break;
         OMC_FOR_EACH_BITS(X)
 #undef X

@@ -393,24 +393,78 @@ __device__ __forceinline__ float apply_update(float w, float g, float &m, float 
 }
 
 // ---- fit accumulators -----------------------------------------------------------------------------
+// Unevaluated sum hi + lo of two doubles, and the additions that keep one (Knuth's two-sum for the
+// error of an addition; used by the wide-mantissa kernels and by the finalize).
+struct DD {
+    double hi, lo;
+};
+__device__ __forceinline__ DD dd_add(DD a, double x) {
+    const double s = a.hi + x;
+    const double bb = s - a.hi;
+    const double err = (a.hi - (s - bb)) + (x - bb);
+    const double lo = a.lo + err;
+    DD r;
+    r.hi = s + lo;
+    r.lo = lo - (r.hi - s);
+    return r;
+}
+__device__ __forceinline__ DD dd_add(DD a, DD b) { return dd_add(dd_add(a, b.hi), b.lo); }
+__device__ __forceinline__ DD dd_shfl_xor(DD a, int off) {
+    DD r;
+    r.hi = __shfl_xor(a.hi, off);
+    r.lo = __shfl_xor(a.lo, off);
+    return r;
+}
+// s += x with the rounding error of the addition added to l
+__device__ __forceinline__ void sum_with_error(double &s, double &l, double x) {
+    const double t = s + x;
+    const double bb = t - s;
+    const double e = (s - (t - bb)) + (x - bb);
+    s = t;
+    l += e;
+}
+
+// The four sums of Sec. 2.3 over the elements a lane has seen.  Every term is exact in fp64 (an fp32
+// value, or the product of two).  EXACT = false: plain fp64 additions; a lane adds 32 to 128 terms and
+// their rounding errors stay some 2^-50 of the sums, which moves the fp32 result of the closed form only
+// when that result lies within ~1e-16 of a rounding boundary -- as long as b is a visible fraction of
+// the values, i.e. for formats of fewer than 16 mantissa bits.  EXACT = true (16 mantissa bits and more,
+// where b = (SUM V - s SUM Vt) / n cancels to ~2^-M of the values): every addition's error is kept in a
+// second word (lV ..), so that sum + error carries about 106 bits and its rounding to fp64 is the
+// correctly rounded sum, as the definition of the fit asks for.
 struct FitAcc {
     double sV, sT, sVT, sTT;
+    double lV, lT, lVT, lTT;
     uint32_t t0;     // bit pattern of the first decompressed value this lane saw
     uint32_t diff;   // OR of (bits ^ t0) over all values this lane saw
     bool have;
     __device__ __forceinline__ void clear() {
         sV = sT = sVT = sTT = 0.0;
+        lV = lT = lVT = lTT = 0.0;
         t0 = 0u;
         diff = 0u;
         have = false;
     }
+    template <bool EXACT = false>
     __device__ __forceinline__ void add(float x, float tq) {
         const double dx = static_cast<double>(x), dt = static_cast<double>(tq);
-        sV += dx;
-        sT += dt;
-        sVT = fma(dx, dt, sVT);   // the product of two fp32 values is exact in fp64
-        sTT = fma(dt, dt, sTT);
+        if constexpr (EXACT) {
+            sum_with_error(sV, lV, dx);
+            sum_with_error(sT, lT, dt);
+            sum_with_error(sVT, lVT, dx * dt);   // the product of two fp32 values is exact in fp64
+            sum_with_error(sTT, lTT, dt * dt);
+        } else {
+            sV += dx;
+            sT += dt;
+            sVT = fma(dx, dt, sVT);              // one rounding: the product itself is exact
+            sTT = fma(dt, dt, sTT);
+        }
         diff |= __float_as_uint(tq) ^ t0;
+    }
+    template <bool EXACT = false>
+    __device__ __forceinline__ void pin_sums() {
+        asm volatile("" : "+v"(sV), "+v"(sT), "+v"(sVT), "+v"(sTT), "+v"(diff));
+        if constexpr (EXACT) asm volatile("" : "+v"(lV), "+v"(lT), "+v"(lVT), "+v"(lTT));
     }
     __device__ __forceinline__ void seed(float tq) {   // before the first add
         if (!have) t0 = __float_as_uint(tq);
@@ -427,21 +481,37 @@ struct FitAcc {
     }
     // butterfly over the 64 lanes; every lane ends with the same totals, in an order that does
     // not depend on scheduling; lane 0 stores them
+    template <bool EXACT = false>
     __device__ __forceinline__ void reduce_and_store(Partial *out) {
         float tmin, tmax;
         lane_range(tmin, tmax);
+        if constexpr (EXACT) {
+            DD dV{sV, lV}, dT{sT, lT}, dVT{sVT, lVT}, dTT{sTT, lTT};
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            sV += __shfl_xor(sV, off);
-            sT += __shfl_xor(sT, off);
-            sVT += __shfl_xor(sVT, off);
-            sTT += __shfl_xor(sTT, off);
-            tmin = fminf(tmin, __shfl_xor(tmin, off));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, off));
+            for (int off = 32; off >= 1; off >>= 1) {
+                dV = dd_add(dV, dd_shfl_xor(dV, off));
+                dT = dd_add(dT, dd_shfl_xor(dT, off));
+                dVT = dd_add(dVT, dd_shfl_xor(dVT, off));
+                dTT = dd_add(dTT, dd_shfl_xor(dTT, off));
+                tmin = fminf(tmin, __shfl_xor(tmin, off));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, off));
+            }
+            sV = dV.hi; lV = dV.lo; sT = dT.hi; lT = dT.lo; sVT = dVT.hi; lVT = dVT.lo; sTT = dTT.hi; lTT = dTT.lo;
+        } else {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                sV += __shfl_xor(sV, off);
+                sT += __shfl_xor(sT, off);
+                sVT += __shfl_xor(sVT, off);
+                sTT += __shfl_xor(sTT, off);
+                tmin = fminf(tmin, __shfl_xor(tmin, off));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, off));
+            }
         }
-        if (threadIdx.x == 0) {
+        if ((threadIdx.x & 63u) == 0) {
             Partial p;
             p.sV = sV; p.sT = sT; p.sVT = sVT; p.sTT = sTT;
+            p.lV = EXACT ? lV : 0.0; p.lT = EXACT ? lT : 0.0; p.lVT = EXACT ? lVT : 0.0; p.lTT = EXACT ? lTT : 0.0;
             p.tmin = tmin; p.tmax = tmax; p.pad[0] = p.pad[1] = 0;
             *out = p;
         }
@@ -482,7 +552,7 @@ __device__ __forceinline__ void issue_loads(const TileArgs &a, uint64_t e0, uint
 // The cycle over a lane's 32 elements, generic formats: decode -> transform -> update -> round ->
 // pack, and the fit's sums.  w: the lane's B code dwords; rg / rm / rv: gradient (or the values to
 // compress) and optimizer state, updated in place; o: the lane's B output dwords.
-template <int B, int MODE, bool WIDE>
+template <int B, int MODE, bool WIDE, bool EXACT = false>
 __device__ __forceinline__ void cycle_generic(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
                                               uint32_t (&w)[B], float (&rg)[32], float (&rm)[32], float (&rv)[32],
                                               uint32_t (&o)[B], FitAcc &acc) {
@@ -533,11 +603,12 @@ __device__ __forceinline__ void cycle_generic(const TileArgs &a, const FmtParams
         encode<WIDE>(x, fp, code, tq);
         pack_at<B>(o, i, code);
         if (i == 0) acc.seed(tq);
-        acc.add(x, tq);
+        acc.template add<EXACT>(x, tq);
 #if OMC_TUNE_SCHED_GROUP > 0
         if ((i + 1) % OMC_TUNE_SCHED_GROUP == 0) {        // group end: pin what the group produced
             constexpr int G = OMC_TUNE_SCHED_GROUP;
             pin(acc.sV); pin(acc.sT); pin(acc.sVT); pin(acc.sTT); pin(acc.diff);
+            if constexpr (EXACT) { pin(acc.lV); pin(acc.lT); pin(acc.lVT); pin(acc.lTT); }
             pin(o[((i + 1) * B - 1) >> 5]);
             if (MODE >= kStepMomentum) {
 #pragma unroll
@@ -746,7 +817,7 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
         if (!cycle_mx_fp6<MODE>(a, oc, w, rg, rm, rv, o, acc))
             cycle_generic<B, MODE, false>(a, fp, oc, w, rg, rm, rv, o, acc);
     } else {
-        cycle_generic<B, MODE, VARIANT == 1>(a, fp, oc, w, rg, rm, rv, o, acc);
+        cycle_generic<B, MODE, variant_wide(VARIANT), variant_exact(VARIANT)>(a, fp, oc, w, rg, rm, rv, o, acc);
     }
 
     // back to the coalesced layouts and out
@@ -802,14 +873,15 @@ __device__ __forceinline__ void do_chunk(const TileArgs &a, const FmtParams &fp,
     }
     finish_tile<B, MODE, VARIANT, false, KEEP>(a, fp, oc, begin + static_cast<uint64_t>(ntiles - 1) * kTileElems,
                                                lane, lds, st, acc);
-    if (MODE != kDecompress) acc.reduce_and_store(partial_out);
+    if (MODE != kDecompress) acc.template reduce_and_store<variant_exact(VARIANT)>(partial_out);
 }
 
 // ---- the ragged tail of a variable ----------------------------------------------------------------------
 // Elements [e0, n) with e0 a multiple of 2048 and n - e0 < 2048, by one wave.  Same ownership as
 // a full tile (lane l: elements e0 + 32 l ...), same arithmetic, but the code width is a run-time
 // value, every access is bounds-checked and goes straight to global memory.  Lanes past the end
-// write zero bits up to the end of the (16-byte padded) packed buffer.
+// write zero bits up to the end of the (16-byte padded) packed buffer.  The sums of the fit are kept
+// with their rounding errors for the formats whose full-tile kernels do so (fp.variant).
 template <int MODE, bool WIDE>
 __device__ __forceinline__ void do_tail(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
                                         Partial *partial_out) {
@@ -819,6 +891,7 @@ __device__ __forceinline__ void do_tail(const TileArgs &a, const FmtParams &fp, 
     const uint64_t lane_e0 = e0 + static_cast<uint64_t>(lane) * kLaneElems;
     const uint64_t lane_dw0 = (lane_e0 >> 5) * B;            // the lane's first dword
     const uint32_t cmask = (B == 32) ? 0xffffffffu : ((1u << B) - 1u);
+    const bool exact = variant_exact(fp.variant);
     FitAcc acc;
     acc.clear();
     uint64_t outbits = 0;
@@ -858,7 +931,7 @@ __device__ __forceinline__ void do_tail(const TileArgs &a, const FmtParams &fp, 
         encode<WIDE>(x, fp, code, tq);
         if (live) {
             acc.seed(tq);
-            acc.add(x, tq);
+            if (exact) acc.add<true>(x, tq); else acc.add<false>(x, tq);
         }
         outbits |= static_cast<uint64_t>(code) << fill;
         fill += B;
@@ -870,40 +943,22 @@ __device__ __forceinline__ void do_tail(const TileArgs &a, const FmtParams &fp, 
             ++outidx;
         }
     }
-    if (MODE != kDecompress) acc.reduce_and_store(partial_out);
+    if (MODE != kDecompress) {
+        if (exact) acc.reduce_and_store<true>(partial_out); else acc.reduce_and_store<false>(partial_out);
+    }
 }
 
 // ---- finalize: per-variable (s, b) from the partials (paper Sec. 2.3) -----------------------------
-struct DD {  // unevaluated sum hi + lo
-    double hi, lo;
-};
-__device__ __forceinline__ DD dd_add(DD a, double x) {
-    const double s = a.hi + x;
-    const double bb = s - a.hi;
-    const double err = (a.hi - (s - bb)) + (x - bb);
-    const double lo = a.lo + err;
-    DD r;
-    r.hi = s + lo;
-    r.lo = lo - (r.hi - s);
-    return r;
-}
-__device__ __forceinline__ DD dd_add(DD a, DD b) { return dd_add(dd_add(a, b.hi), b.lo); }
-__device__ __forceinline__ DD dd_shfl_xor(DD a, int off) {
-    DD r;
-    r.hi = __shfl_xor(a.hi, off);
-    r.lo = __shfl_xor(a.lo, off);
-    return r;
-}
-
 // Called by a whole workgroup of NW waves (blockDim.x == 64 * NW).  Sums the variable's partials
 // (a run of `nparts` from the full-tile kernels and, if `tail` is not null, one more from the tail
 // kernel) with compensated additions in an order fixed by (nparts, NW) alone: thread t takes
 // partials t, t + 64 NW, ...; lanes combine by a butterfly; waves combine in index order.  Then the
-// closed form in fp64, stored as fp32.  `red` is LDS scratch of NW * 10 doubles.
+// closed form in fp64, stored as fp32.  `red` is LDS scratch of NW * 10 doubles.  `exact`: the partials
+// carry error words (formats of 16 or more mantissa bits), which are added as well.
 template <int NW>
 __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ parts, uint32_t nparts,
                                                   const Partial *__restrict__ tail, uint64_t n, bool use_pvt,
-                                                  float *sb_out, double *red) {
+                                                  bool exact, float *sb_out, double *red) {
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     if (!use_pvt) {
         if (tid == 0) { sb_out[0] = 1.0f; sb_out[1] = 0.0f; }
@@ -932,6 +987,12 @@ __device__ __forceinline__ void finalize_variable(const Partial *__restrict__ pa
                 sT = dd_add(sT, p[u].sT);
                 sVT = dd_add(sVT, p[u].sVT);
                 sTT = dd_add(sTT, p[u].sTT);
+                if (exact) {                        // the error words of the wide-mantissa kernels (zero otherwise)
+                    sV = dd_add(sV, p[u].lV);
+                    sT = dd_add(sT, p[u].lT);
+                    sVT = dd_add(sVT, p[u].lVT);
+                    sTT = dd_add(sTT, p[u].lTT);
+                }
             }
             tmin = fminf(tmin, p[u].tmin);
             tmax = fmaxf(tmax, p[u].tmax);
@@ -1005,7 +1066,7 @@ __global__ __launch_bounds__(64 * NW) void finalize_plan_kernel(const uint8_t *_
     if (!(pv.flags & OMC_VAR_QUANTIZED)) return;
     finalize_variable<NW>(pv.nitems ? ws + pv.first_item : ws, pv.nitems,
                           pv.tail_item != kNoItem ? ws + pv.tail_item : nullptr, pv.n,
-                          !(pv.flags & OMC_VAR_NO_PVT), sb_table + 2 * static_cast<uint64_t>(blockIdx.x), red);
+                          !(pv.flags & OMC_VAR_NO_PVT), variant_exact(pv.fp.variant), sb_table + 2 * static_cast<uint64_t>(blockIdx.x), red);
 }
 constexpr int kFinalizeWaves = 4;
 

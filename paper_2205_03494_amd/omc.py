@@ -68,6 +68,7 @@ _decompress = _sig("omc_decompress", C.c_int, _vp, C.c_uint64, omc_format, _vp, 
 _plan_bytes = _sig("omc_plan_bytes", C.c_size_t, _vp, C.c_uint32)
 _plan_build = _sig("omc_plan_build", C.c_int, _vp, C.c_uint32, _vp, C.c_size_t)
 _plan_ws = _sig("omc_plan_workspace_bytes", C.c_size_t, _vp)
+_workspace_bytes = _sig("omc_workspace_bytes", C.c_size_t, _vp, C.c_uint32)
 _plan_arena = _sig("omc_plan_arena_bytes", C.c_size_t, _vp)
 _plan_aux = _sig("omc_plan_aux_elems", C.c_uint64, _vp)
 _step = _sig("omc_step_update_recompress", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -92,7 +93,7 @@ _gemm_dx = _sig("omc_dequant_gemm_dx", C.c_int, _vp, _vp, omc_format, _vp, _vp, 
 
 EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_format_max",
             "omc_packed_bytes", "omc_compress_workspace_bytes", "omc_compress", "omc_decompress",
-            "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_plan_arena_bytes",
+            "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_workspace_bytes", "omc_plan_arena_bytes",
             "omc_plan_aux_elems", "omc_plan_launches", "omc_step_update_recompress",
             "omc_step_update_recompress_events", "omc_compress_set", "omc_decompress_set",
             "omc_plan_transport_bytes", "omc_aggregate_plan_bytes", "omc_aggregate_plan_build",
@@ -209,6 +210,10 @@ def make_var_table(vars_: Sequence[dict]):
         f = v.get("fmt") or omc_format(8, 23, OMC_BIAS_DEFAULT)
         tab[i] = omc_var(int(v["data_offset"]), int(v["aux_offset"]), int(v["n"]), f, flags)
     return tab
+
+
+def omc_workspace_bytes(var_table) -> int:
+    return _workspace_bytes(C.cast(var_table, _vp), len(var_table))
 
 
 def omc_plan_build(var_table, device="cuda") -> Plan:

@@ -68,7 +68,7 @@ def test_plan_build_validates_the_table():
     size, st, buf = _plan_status(good)
     assert st == 0 and size > 0
     # 5000 quantized elements: one item for the two full tiles, one for the ragged tail; one fp32 item
-    assert omc._plan_ws(buf.ctypes.data) == 48 * 3
+    assert omc._plan_ws(buf.ctypes.data) == 80 * 3     # four sums as (value, error) pairs + range per item
     assert omc._plan_arena(buf.ctypes.data) == 6880 + 400
     assert omc._plan_aux(buf.ctypes.data) == 5100
     # misaligned offsets
@@ -87,6 +87,38 @@ def test_plan_build_validates_the_table():
     # empty table / NULL
     assert omc._plan_build(None, 1, buf.ctypes.data, buf.size) == 1
     assert omc._plan_bytes(C.cast(_table(good), C.c_void_p), 0) == 0
+
+
+def test_plan_body_is_covered_by_a_checksum_and_group_bounds():
+    """A damaged or stale host blob must be refused before anything is enqueued: the kernels index the device
+    copy with group offsets and counts read from the host copy."""
+    f = omc.fmt(3, 7)
+    vs = [dict(data_offset=0, aux_offset=0, n=50000, fmt=f, quantized=True),
+          dict(data_offset=68752, aux_offset=50000, n=3000, quantized=False),
+          dict(data_offset=68752 + 12000, aux_offset=53000, n=9000, fmt=omc.fmt(4, 3), quantized=True)]
+    size, st, buf = _plan_status(vs)
+    assert st == 0
+    assert omc._plan_ws(buf.ctypes.data) > 0
+    assert omc.omc_workspace_bytes(_table(vs)) == omc._plan_ws(buf.ctypes.data)
+    assert omc.omc_workspace_bytes(_table([dict(vs[0], n=0)])) == 0
+    hdr = np.frombuffer(buf[:32].tobytes(), dtype=np.uint32)
+    offs = np.frombuffer(buf[32:56].tobytes(), dtype=np.uint64)
+    var_off, item_off, group_off = (int(x) for x in offs)
+    A = 0x100000
+    o = omc.opt(omc.OMC_SGD, 0.1)
+    def step(blob):
+        return omc._step(A, 1 << 20, blob.ctypes.data, A, A, A, None, None, 1 << 20, C.byref(o), A, 1 << 16, None)
+    rng = np.random.default_rng(0)
+    # one flipped bit anywhere in the body: variable table, item list, group table
+    for pos in [var_off + 3, var_off + 40, item_off + 5, group_off + 8, group_off + 12, size - 17] + \
+            [int(x) for x in rng.integers(var_off, size - 16, 40)]:
+        bad = buf.copy()
+        bad[pos] ^= 1 << int(rng.integers(0, 8))
+        assert omc._plan_ws(bad.ctypes.data) == 0, pos
+        assert step(bad) == 8, pos                                  # OMC_ERR_PLAN, nothing enqueued
+    # a blob truncated to its header, and one of another version
+    bad = buf.copy(); bad[4:8] = np.frombuffer(np.uint32(hdr[1] + 1).tobytes(), np.uint8)
+    assert step(bad) == 8
 
 
 def test_plan_item_list_covers_every_chunk_once():
@@ -120,15 +152,15 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     f = omc.fmt(4, 3)
     A = 0x1000  # a fake, aligned, never dereferenced address
     # NULL pointers
-    assert omc._compress(None, 10, f, 1, A, A, A, 48, None) == 1
+    assert omc._compress(None, 10, f, 1, A, A, A, 4096, None) == 1
     assert omc._decompress(None, 10, f, None, A, None) == 1
     # bad format / size / alignment / workspace
-    assert omc._compress(A, 10, omc.fmt(0, 0), 1, 0x100000, A, A, 48, None) == 2
-    assert omc._compress(A, 0, f, 1, 0x100000, A, A, 48, None) == 3
-    assert omc._compress(A + 4, 10, f, 1, 0x100000, A, A, 48, None) == 4
+    assert omc._compress(A, 10, omc.fmt(0, 0), 1, 0x100000, A, A, 4096, None) == 2
+    assert omc._compress(A, 0, f, 1, 0x100000, A, A, 4096, None) == 3
+    assert omc._compress(A + 4, 10, f, 1, 0x100000, A, A, 4096, None) == 4
     assert omc._compress(A, 10, f, 1, 0x100000, A, None, 0, None) == 5
     assert omc._compress(A, 10000, f, 1, 0x100000, A, 0x200000, 48, None) == 5
-    assert omc._compress(A, 10, f, 1, A, A, 0x200000, 48, None) == 3          # in == out
+    assert omc._compress(A, 10, f, 1, A, A, 0x200000, 4096, None) == 3          # in == out
     assert omc._decompress(A, 10, f, None, A + 8, None) == 4
     # step: plan / optimizer / sizes
     vs = [dict(data_offset=0, aux_offset=0, n=5000, fmt=f, quantized=True)]
@@ -246,9 +278,9 @@ def test_dw_update_rejects_bad_arguments():
     o = omc.opt(omc.OMC_SGD, 0.1)
     def call(X=A, dY=A, codes=A, fm=f, sb=A, st0=None, st1=None, opt=o, M=64, N=128, K=256, ws=A, wsb=1 << 20):
         return omc._dw(X, dY, codes, fm, sb, 1, st0, st1, omc.C.byref(opt), None, M, N, K, ws, wsb, None)
-    assert omc.omc_dw_update_workspace_bytes(f, 64, 128, 256) == 768                        # no split: the fit's partials only
-    assert omc.omc_dw_update_workspace_bytes(f, 8192, 128, 256) == 768 + 8 * 4 * 128 * 256  # 8 splits of 1024 rows
-    assert omc.omc_dw_update_workspace_bytes(omc.fmt(3, 7), 64, 128, 256) == 768 + 4 * 128 * 256   # other widths park once
+    assert omc.omc_dw_update_workspace_bytes(f, 64, 128, 256) == 1280                        # no split: the fit's partials only
+    assert omc.omc_dw_update_workspace_bytes(f, 8192, 128, 256) == 1280 + 8 * 4 * 128 * 256  # 8 splits of 1024 rows
+    assert omc.omc_dw_update_workspace_bytes(omc.fmt(3, 7), 64, 128, 256) == 1280 + 4 * 128 * 256   # other widths park once
     assert omc.omc_dw_update_workspace_bytes(f, 64, 100, 256) == 0
     assert call(X=None) == 1
     assert call(fm=omc.fmt(9, 7)) == 2                   # not a format

@@ -2,7 +2,9 @@
 consumed by the update in the same kernel).  Two-stage check, because the gradient is a long fp32
 accumulation while the update decides integer codes:
   1. the gradient the kernel used (dW_out) against the oracle's fp64 X^T dY, to the GEMM tolerance;
-  2. codes, (s, b) and optimizer state against the oracle's step fed with exactly that gradient: bit for bit."""
+  2. codes, (s, b) and optimizer state against the oracle's step fed with exactly that gradient: bit for bit.
+Every case is run a second time on its own copies of the buffers with dW_out = NULL -- the call a training loop
+makes, where the gradient is not written anywhere -- and must leave the same codes, (s, b) and state, bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -15,7 +17,8 @@ from test_gpu_gemm import check
 pytestmark = pytest.mark.gpu
 
 
-def run_case(EM, M, N, K, kind, lr, use_pvt=True, steps=2, grad_scale=1.0, want_dw=True, rows=None):
+def run_case(EM, M, N, K, kind, lr, use_pvt=True, steps=2, grad_scale=1.0, rows=None):
+    want_dw = True
     of, gf = pair(*EM)
     n = K * N
     W = synth.normal_f32(n, 0.05, 2)
@@ -27,12 +30,26 @@ def run_case(EM, M, N, K, kind, lr, use_pvt=True, steps=2, grad_scale=1.0, want_
     st1_d = None if st1 is None else to_dev(st1)
     ws = torch.empty(omc.omc_dw_update_workspace_bytes(gf, M, N, K), dtype=torch.uint8, device="cuda")
     dW_d = torch.full((K, N), float("nan"), device="cuda") if want_dw else None
+    # the same steps without a gradient copy, on separate buffers (workspace included)
+    codes_n, sb_n = codes_d.clone(), sb_d.clone()
+    st0_n = None if st0_d is None else st0_d.clone()
+    st1_n = None if st1_d is None else st1_d.clone()
+    ws_n = torch.empty_like(ws)
     for t in range(1, steps + 1):
         X = synth.to_bf16_bits(synth.normal_f32(M * K, 1.0, 10 + t))
         dY = synth.to_bf16_bits(synth.normal_f32(M * N, grad_scale / M, 20 + t))
-        omc.omc_dw_update_recompress(to_dev(X), to_dev(dY), codes_d, gf, sb_d, use_pvt, st0_d, st1_d,
+        X_d, dY_d = to_dev(X), to_dev(dY)
+        omc.omc_dw_update_recompress(X_d, dY_d, codes_d, gf, sb_d, use_pvt, st0_d, st1_d,
                                      omc.opt(kind, lr, t=t), dW_d, M, N, K, ws)
+        omc.omc_dw_update_recompress(X_d, dY_d, codes_n, gf, sb_n, use_pvt, st0_n, st1_n,
+                                     omc.opt(kind, lr, t=t), None, M, N, K, ws_n)
         torch.cuda.synchronize()
+        assert torch.equal(codes_n, codes_d), f"dW_out = NULL: codes differ at step {t}"
+        assert torch.equal(sb_n.view(torch.int32), sb_d.view(torch.int32)), f"dW_out = NULL: (s, b) differ at step {t}"
+        if st0_d is not None:
+            assert torch.equal(st0_n.view(torch.int32), st0_d.view(torch.int32)), f"dW_out = NULL: state0 differs at step {t}"
+        if st1_d is not None:
+            assert torch.equal(st1_n.view(torch.int32), st1_d.view(torch.int32)), f"dW_out = NULL: state1 differs at step {t}"
         g = dW_d.cpu().numpy()
         assert np.all(np.isfinite(g))
         if rows is None:
@@ -77,7 +94,7 @@ def test_without_the_transformation_and_with_saturating_updates():
 
 def test_config5_layer_sampled_gradient_rows():
     # the feed-forward layer of the benchmark shape: X [8192 x 1024], W [1024 x 4096]
-    run_case((4, 3), 8192, 4096, 1024, 0, 0.01, steps=1, rows=(0, 500, 1008))
+    run_case((4, 3), 8192, 4096, 1024, 0, 0.01, steps=1, rows=(0, 300, 500, 700, 1008))   # every 256-row tile, full width
 
 
 @pytest.mark.parametrize("kind,lr", [(0, 0.05), (1, 0.05), (2, 1e-3)])
@@ -91,6 +108,14 @@ def test_other_code_widths_take_the_two_kernel_path(EM, kind, lr):
 def test_other_code_widths_with_split_contraction_and_several_tiles():
     run_case((3, 7), 2048, 256, 512, 1, 0.05, steps=2)
     run_case((2, 3), 1024, 128, 256, 0, 0.05, steps=2, grad_scale=20.0)
+
+
+@pytest.mark.parametrize("EM", [(4, 18), (5, 23), (8, 16)])
+def test_wide_mantissa_formats_keep_exact_fit_sums(EM):
+    """16 and more mantissa bits: the slab kernel carries the rounding errors of the fit's sums like the streaming
+    kernels of these formats do, so (s, b) still match the oracle bit for bit."""
+    run_case(EM, 96, 128, 256, 1, 0.05)
+    run_case(EM, 1024, 256, 512, 0, 0.05, steps=1)
 
 
 def test_fp32_as_a_format_is_plain_sgd():

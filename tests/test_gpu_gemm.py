@@ -19,6 +19,19 @@ def run_gemm(A_bits, packed, gf, sb, M, N, K):
     return C.cpu().numpy()
 
 
+def tile_sample_rows(M, seed, tile=256, per_quarter=1):
+    """Rows to check at full size: from every 256-row tile of the output one row out of each 64-row quarter (the
+    share of one wave of the four-wave kernels), at seeded offsets."""
+    rng = np.random.default_rng(seed)
+    rows = [t * tile + 64 * q + int(rng.integers(0, 64)) for t in range(M // tile) for q in range(4) for _ in range(per_quarter)]
+    return np.array(sorted(set(rows)))
+
+
+def check_rows(C, ref, rows):
+    """check() on a list of rows: ref holds the oracle's result for exactly those rows, in order."""
+    return check(C[rows], ref, (0, len(rows)))
+
+
 def check(C, ref, rows):
     ref = np.asarray(ref)
     got = C[rows[0]:rows[1]].astype(np.float64)
@@ -67,10 +80,14 @@ def test_config5_shapes_sampled_rows(shape):
     packed, sb = orc.compress(W, of)
     C = run_gemm(A, packed, gf, sb, M, N, K)
     assert np.all(np.isfinite(C))
-    for r0 in (0, 4000, M - 24):
+    # rows of C depend on their own row of A only: the oracle multiplies the sampled rows as a matrix of their own
+    rows = tile_sample_rows(M, seed=K)
+    assert rows.size == 4 * (M // 256)
+    ref = orc.dequant_gemm(np.ascontiguousarray(A.reshape(M, K)[rows]).ravel(), packed, of, sb, rows.size, N, K, threads=8)
+    assert check_rows(C, ref, rows) < 1e-5
+    for r0 in (0, M - 24):                                      # and two runs of consecutive rows at the ends
         ref = orc.dequant_gemm(A, packed, of, sb, M, N, K, rows=(r0, r0 + 24), threads=8)
-        rel = check(C, ref, (r0, r0 + 24))
-        assert rel < 1e-5
+        assert check(C, ref, (r0, r0 + 24)) < 1e-5
 
 
 @pytest.mark.parametrize("K", [256, 2048])                  # 2048: the kernel for long contractions on small grids
@@ -144,10 +161,12 @@ def test_dx_config5_shapes_sampled_rows(shape):
     packed, sb = orc.compress(W, of)
     dX = run_gemm_dx(dY, packed, gf, sb, M, N, K)
     assert np.all(np.isfinite(dX))
-    for r0 in (0, 4000, M - 24):
+    rows = tile_sample_rows(M, seed=N)
+    ref = orc.dequant_gemm_dx(np.ascontiguousarray(dY.reshape(M, N)[rows]).ravel(), packed, of, sb, rows.size, N, K, threads=8)
+    assert check_rows(dX, ref, rows) < 1e-5
+    for r0 in (0, M - 24):
         ref = orc.dequant_gemm_dx(dY, packed, of, sb, M, N, K, rows=(r0, r0 + 24), threads=8)
-        rel = check(dX, ref, (r0, r0 + 24))
-        assert rel < 1e-5
+        assert check(dX, ref, (r0, r0 + 24)) < 1e-5
 
 
 @pytest.mark.parametrize("shape", [(256, 128, 32), (512, 256, 160), (256, 128, 4096), (256, 2048, 128)])
