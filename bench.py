@@ -1,19 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the OMC hot path on one MI355X.
 
-A "step" is one training iteration over the whole variable set: for every quantized weight
-matrix decompress -> SGD update -> recompress (fused in one kernel), for every fp32 variable the
-update alone, then the per-variable (s, b) finalize -- i.e. one omc_step_update_recompress call.
-The workload is the Conformer-encoder-shaped set of about 115 M weight-matrix parameters
-(17 blocks, d_model 512, FFN 2048, depthwise kernel 32, plus a front end), every weight matrix in
-the 8-bit S1E4M3 code with the per-variable transformation, biases and norm vectors in fp32,
-values N(0, 1/sqrt(fan_in)), gradients N(0, 1e-3), all seeded and synthetic and resident in HBM
-before the timed region.
+A "step" is one training iteration over a whole variable set: for every quantized weight matrix
+decompress -> parameter update -> recompress (fused in one kernel per code width), for every fp32
+variable the update alone, then the per-variable (s, b) finalize -- one omc_step_update_recompress
+call with default flags.
 
-Prints one JSON line.  `value` is compressed-parameter GB/s (packed bytes of the quantized
-variables stepped per second); `roofline` prices the dominant kernel's algorithmic HBM bytes
-(6 B per 8-bit element: code in, gradient in, code out) against 8 TB/s; `cpu_baseline` is the CPU
-oracle timed on a bounded sample of the same variable set on this machine's host cores.
+Headline workload (the largest single-GPU configuration of the baseline): a Conformer-encoder-shaped
+set of about 604 M weight-matrix parameters (24 blocks, d_model 1024, FFN 4096, 16 heads, depthwise
+kernel 32), every weight matrix in the 11-bit S1E3M7 code with the per-variable transformation,
+biases and norm vectors in fp32, SGD with momentum 0.9 and fp32 momentum, values
+N(0, 1/sqrt(fan_in)), gradients N(0, 1e-3); all seeded, synthetic and resident in HBM before the
+timed region.  The baseline's other step configurations (the 115 M-parameter set in S1E4M3 under SGD;
+the same set half quantized in three formats under Adam) are measured the same way and reported
+under `other_step_configs`, each with its own roofline block.
+
+Prints one JSON line.  `value` is compressed-parameter GB/s (packed bytes of the quantized variables
+stepped per second, whole step, back-to-back steps as the contract asks).  Every `roofline` block prices
+its configuration's dominant kernel: algorithmic HBM bytes of one launch over that launch's duration
+(HIP events on the launch stream) against 8 TB/s.  A training loop runs a forward and a backward pass
+between two steps, so `achieved` / `frac` are taken with the caches flushed between steps (a 512 MiB
+device copy, untimed); the back-to-back figure and the opt-in OMC_OPT_KEEP_CODES policy are listed
+beside it.  `cpu_baseline` is the CPU oracle timed on a bounded sample of the headline set on this
+machine's host cores, one thread and all cores.
 """
 import argparse
 import json
@@ -25,86 +34,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-
-
-def build_workload(torch, omc, synth, blocks, d_model, ffn, seed=0):
-    """Config-2 variable set, compressed on the GPU by the library itself."""
-    import numpy as np
-    specs = synth.conformer_varset(d_model, blocks, ffn, 32, frontend=True)
-    mask = np.array([s.is_matrix for s in specs])
-    gf = omc.fmt(4, 3)
-    lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(gf, n))
-    vals = synth.init_values(lay, seed)
-    vals_d = torch.from_numpy(vals).cuda()
-    arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
-    sb = torch.zeros((len(specs), 2), dtype=torch.float32, device="cuda")
-    sb[:, 0] = 1.0
-    table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gf,
-                  quantized=bool(mask[i])) for i, s in enumerate(specs)]
-    plan = omc.omc_plan_build(omc.make_var_table(table))
-    ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
-    omc.omc_compress_set(vals_d, plan, arena, sb, ws)
-    torch.cuda.synchronize()
-    return dict(specs=specs, mask=mask, lay=lay, vals=vals, vals_d=vals_d, arena=arena, sb=sb, plan=plan, table=table)
-
-
-def cpu_baseline(wl, synth, sample_blocks, iters, threads, gpu_after=None):
-    """The oracle as it stands on a bounded sample: the variables of the first `sample_blocks`
-    Conformer blocks, `iters` iterations.  Also returns the oracle's state for a parity check."""
-    import numpy as np
-    from concurrent.futures import ThreadPoolExecutor
-    from oracle import omc_oracle as orc
-    specs, lay, mask = wl["specs"], wl["lay"], wl["mask"]
-    of = orc.Format(4, 3)
-    pick = [i for i, s in enumerate(specs)
-            if s.name.startswith("block") and int(s.name.split("/")[0][5:]) < sample_blocks]
-    sub_specs = [specs[i] for i in pick]
-    sub_mask = mask[pick]
-    sub_lay = synth.make_layout(sub_specs, sub_mask, lambda n: orc.packed_bytes(n, of.bits))
-    arena = np.zeros(sub_lay.arena_bytes, np.uint8)
-    sbt = np.zeros((len(pick), 2), np.float32)
-    sbt[:, 0] = 1.0
-
-    def init(j):
-        i = pick[j]
-        s = specs[i]
-        a = int(lay.aux_offset[i])
-        x = wl["vals"][a:a + s.n]
-        d = int(sub_lay.data_offset[j])
-        if sub_mask[j]:
-            p, sb = orc.compress(x, of)
-            arena[d:d + p.size] = p
-            sbt[j] = sb
-        else:
-            arena[d:d + 4 * s.n] = x.view(np.uint8)
-
-    with ThreadPoolExecutor(threads) as ex:
-        list(ex.map(init, range(len(pick))))
-    table = orc.make_var_table(dict(data_offset=int(sub_lay.data_offset[j]), aux_offset=int(sub_lay.aux_offset[j]),
-                                    n=specs[i].n, fmt=of, quantized=bool(sub_mask[j]))
-                               for j, i in enumerate(pick))
-    grads = []
-    for gset in wl["grads_host"]:
-        g = np.zeros(sub_lay.aux_elems, np.float32)
-        for j, i in enumerate(pick):
-            a, b = int(lay.aux_offset[i]), int(sub_lay.aux_offset[j])
-            g[b:b + specs[i].n] = gset[a:a + specs[i].n]
-        grads.append(g)
-    n_elems = sum(specs[i].n for i in pick)
-    packed_bytes = sum(orc.packed_bytes(specs[i].n, 8) for j, i in enumerate(pick) if sub_mask[j])
-    first = None
-    t0 = time.perf_counter()
-    for t in range(iters):
-        orc.step_varset(arena, table, sbt, grads[t % len(grads)], None, None,
-                        orc.Opt(kind=0, lr=0.01, t=t + 1), threads=threads)
-        if t == 0:
-            first = (arena.copy(), sbt.copy())
-    dt = (time.perf_counter() - t0) / iters
-    return dict(pick=pick, sub_lay=sub_lay, sub_mask=sub_mask, first=first, sec_per_iter=dt,
-                n_elems=n_elems, packed_bytes=packed_bytes)
-
-
 LEG_WARMUP_S = 0.15
+
+STEP_CONFIGS = {
+    # name: (d_model, blocks, ffn, conv_k, front end), quantized fraction of the matrices (None = all), formats, optimizer, lr, text
+    "config4": dict(dims=(1024, 24, 4096, 32, False), frac=None, formats=[(3, 7)], kind="momentum", lr=0.01,
+                    text="conformer-encoder-shaped set, 24 blocks d_model=1024 ffn=4096 conv_k=32, all weight matrices in "
+                         "S1E3M7 (11-bit) with per-variable transformation, bias/norm vectors fp32, momentum 0.9 lr=0.01 "
+                         "(fp32 momentum), grads N(0,1e-3)"),
+    "config2": dict(dims=(512, 17, 2048, 32, True), frac=None, formats=[(4, 3)], kind="sgd", lr=0.01,
+                    text="conformer-encoder-shaped set, 17 blocks d_model=512 ffn=2048 conv_k=32 + front end, all weight "
+                         "matrices in S1E4M3 (8-bit) with per-variable transformation, bias/norm vectors fp32, SGD lr=0.01, "
+                         "grads N(0,1e-3)"),
+    "config3": dict(dims=(512, 17, 2048, 32, True), frac=0.5, formats=[(4, 3), (3, 7), (5, 10)], kind="adam", lr=1e-3,
+                    text="the 17-block set with a seeded 50 % of the weight matrices quantized (S1E4M3 / S1E3M7 / S1E5M10 in "
+                         "turn) and the rest fp32 in the same arena, Adam(0.9, 0.999) lr=1e-3 with fp32 moments"),
+}
+STATE_BYTES = {"sgd": 0.0, "momentum": 8.0, "adam": 16.0}     # optimizer state read + written per element
 
 
 def warm(torch, fn, seconds=None):
@@ -122,19 +68,262 @@ def warm(torch, fn, seconds=None):
             return k
 
 
+def timed(torch, fn, iters):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(iters):
+        fn(k)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+# ------------------------------------------------------------------------------------------------
+# step configurations
+# ------------------------------------------------------------------------------------------------
+def build_step_workload(torch, omc, synth, name, blocks=None, seed=5):
+    """Variable set of one baseline configuration, values drawn on the GPU from a seeded generator and
+    compressed by the library itself."""
+    import numpy as np
+    cfg = STEP_CONFIGS[name]
+    d, nb, ffn, ck, fe = cfg["dims"]
+    nb = nb if blocks is None else blocks
+    specs = synth.conformer_varset(d, nb, ffn, ck, frontend=fe)
+    mask = synth.ppq_mask(specs, cfg["frac"], 3) if cfg["frac"] is not None else np.array([s.is_matrix for s in specs])
+    fm = [cfg["formats"][i % len(cfg["formats"])] for i in range(len(specs))]
+    gfs = [omc.fmt(*fm[i]) if mask[i] else None for i in range(len(specs))]
+    sizes = iter([omc.omc_packed_bytes(gfs[i], specs[i].n) for i in range(len(specs)) if mask[i]])
+    lay = synth.make_layout(specs, mask, lambda n: next(sizes))
+    table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gfs[i],
+                  quantized=bool(mask[i])) for i, s in enumerate(specs)]
+    plan = omc.omc_plan_build(omc.make_var_table(table))
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    vals = torch.empty(lay.aux_elems, device="cuda")
+    for i, s in enumerate(specs):
+        a = int(lay.aux_offset[i])
+        vals[a:a + s.n].normal_(0.0, 1.0 / np.sqrt(s.fan_in) if s.is_matrix else 0.02, generator=gen)
+    grads = [torch.empty(lay.aux_elems, device="cuda").normal_(0.0, 1e-3, generator=gen) for _ in range(2)]
+    arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
+    sb = torch.zeros((len(specs), 2), device="cuda")
+    ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    omc.omc_compress_set(vals, plan, arena, sb, ws)
+    torch.cuda.synchronize()
+    kind = cfg["kind"]
+    m = torch.zeros(lay.aux_elems, device="cuda") if kind != "sgd" else None
+    v = torch.zeros(lay.aux_elems, device="cuda") if kind == "adam" else None
+    okind = {"sgd": omc.OMC_SGD, "momentum": omc.OMC_MOMENTUM, "adam": omc.OMC_ADAM}[kind]
+    # launches of a step, in the library's order: one fused kernel per code width (ascending; none of these sets has
+    # ragged tails or needs a second rounding variant), the first of them also serving the fp32 variables; the finalize
+    widths = sorted({1 + sum(fm[i]) for i in range(len(specs)) if mask[i]})
+    assert all(s.n % 2048 == 0 for s, q in zip(specs, mask) if q)
+    assert plan.launches == len(widths) + 1, (plan.launches, widths)
+    st = STATE_BYTES[kind]
+    n_f = int(sum(s.n for s, q in zip(specs, mask) if not q))
+    launches = []
+    for j, B in enumerate(widths):
+        n_b = int(sum(s.n for i, s in enumerate(specs) if mask[i] and 1 + sum(fm[i]) == B))
+        alg = (2.0 * B / 8.0 + 4.0 + st) * n_b + ((12.0 + st) * n_f if j == 0 else 0.0)
+        launches.append({"kernel": f"step_kernel<{B} bit,{kind}>" + (" + fp32 variables" if j == 0 and n_f else ""),
+                         "elements": n_b + (n_f if j == 0 else 0), "algorithmic_bytes": alg})
+    n_q = int(sum(s.n for s, q in zip(specs, mask) if q))
+    packed = int(sum(omc.omc_packed_bytes(gfs[i], s.n) for i, s in enumerate(specs) if mask[i]))
+    alg_step = sum(l["algorithmic_bytes"] for l in launches) + 8.0 * int(mask.sum())
+    return dict(name=name, cfg=cfg, specs=specs, mask=mask, fm=fm, gfs=gfs, lay=lay, plan=plan, vals=vals, grads=grads,
+                arena=arena, sb=sb, ws=ws, m=m, v=v, okind=okind, launches=launches, n_q=n_q, n_f=n_f, packed=packed,
+                alg_step=alg_step, t=0)
+
+
+def step_fn(omc, wl, flags=0):
+    def step(k):
+        wl["t"] += 1
+        omc.omc_step_update_recompress(wl["arena"], wl["plan"], wl["sb"], wl["grads"][k % 2], wl["m"], wl["v"],
+                                       omc.opt(wl["okind"], wl["cfg"]["lr"], t=wl["t"], flags=flags), wl["ws"])
+    return step
+
+
+def kernel_times(torch, omc, wl, steps, flags=0, flush=None):
+    """Average duration of every launch of a step (HIP events recorded by the library on the launch stream around
+    each launch).  flush: (src, dst) of a device copy enqueued before every step, untimed, which leaves nothing of
+    the set in the caches."""
+    nl = wl["plan"].launches
+    ev = omc.HipEvents(2 * nl * steps)
+    for k in range(steps):
+        if flush is not None:
+            flush[1].copy_(flush[0])
+        wl["t"] += 1
+        omc.omc_step_update_recompress_events(wl["arena"], wl["plan"], wl["sb"], wl["grads"][k % 2], wl["m"], wl["v"],
+                                              omc.opt(wl["okind"], wl["cfg"]["lr"], t=wl["t"], flags=flags), wl["ws"], ev,
+                                              first=k * 2 * nl)
+    torch.cuda.synchronize()
+    return [sum(ev.elapsed_ms(k * 2 * nl + 2 * j, k * 2 * nl + 2 * j + 1) for k in range(steps)) / steps
+            for j in range(nl)]
+
+
+def roofline_block(wl, regimes):
+    """regimes: {"evicted": ms list, "back_to_back": ms list, "keep_codes": ms list}.  The dominant kernel is the
+    launch that takes longest in the evicted regime."""
+    ev = regimes["evicted"]
+    dom = max(range(len(wl["launches"])), key=lambda j: ev[j])
+    L = wl["launches"][dom]
+
+    def rate(ms):
+        return L["algorithmic_bytes"] / (ms * 1e-3) / 1e9
+    blk = {"bound": "hbm", "kernel": L["kernel"], "achieved": rate(ev[dom]), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": rate(ev[dom]) / HBM_PEAK_GBS, "traffic": None,
+           "regime": "caches flushed between steps (512 MiB device copy before every step, untimed): the state a "
+                     "training loop's forward and backward pass leave; default flags",
+           "kernel_ms": ev[dom], "algorithmic_bytes_per_launch": L["algorithmic_bytes"],
+           "elements_per_launch": L["elements"],
+           "back_to_back_steps": {"kernel_ms": regimes["back_to_back"][dom], "achieved": rate(regimes["back_to_back"][dom]),
+                                  "frac": rate(regimes["back_to_back"][dom]) / HBM_PEAK_GBS},
+           "back_to_back_steps_OMC_OPT_KEEP_CODES": {
+               "kernel_ms": regimes["keep_codes"][dom], "achieved": rate(regimes["keep_codes"][dom]),
+               "frac": rate(regimes["keep_codes"][dom]) / HBM_PEAK_GBS,
+               "note": "opt-in: packed codes come back from the 256 MB memory-side cache; not an HBM figure"},
+           "all_launches_ms_evicted": ev, "all_launches_ms_back_to_back": regimes["back_to_back"]}
+    # HBM bytes of the same launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, if a committed profile of exactly this
+    # kernel and workload exists: not a reading of this run, so it is labelled with its source and `traffic` stays null
+    tpath = os.path.join(ROOT, "profiles", f"step_kernel_{wl['name']}_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            tj = json.load(fh)
+        if tj.get("elements_per_launch") == L["elements"]:
+            blk["traffic_from_profile"] = {"bytes": tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"],
+                                           "fetch_bytes": tj["fetch_bytes_per_launch"],
+                                           "write_bytes": tj["write_bytes_per_launch"], "source": tj.get("source")}
+    return blk
+
+
+def measure_step_config(torch, omc, wl, steps, warmup, clock_warmup_s, flush, regimes=True):
+    """Times whole steps (back to back, default flags) and the launches of a step in three regimes."""
+    step = step_fn(omc, wl)
+    arena0, sb0 = wl["arena"].clone(), wl["sb"].clone()
+
+    def restore():
+        wl["arena"].copy_(arena0)
+        wl["sb"].copy_(sb0)
+        if wl["m"] is not None:
+            wl["m"].zero_()
+        if wl["v"] is not None:
+            wl["v"].zero_()
+        wl["t"] = 0
+    warm(torch, step, clock_warmup_s)
+    restore()
+    reg = None
+    if regimes:
+        nk = min(steps, 20)
+        reg = {"back_to_back": kernel_times(torch, omc, wl, nk)}
+        restore()
+        reg["evicted"] = kernel_times(torch, omc, wl, nk, flush=flush)
+        restore()
+        warm(torch, step_fn(omc, wl, omc.OMC_OPT_KEEP_CODES), LEG_WARMUP_S)
+        reg["keep_codes"] = kernel_times(torch, omc, wl, nk, flags=omc.OMC_OPT_KEEP_CODES)
+        restore()
+    # ---- timed region: W warm-up steps, then exactly K steps between two synchronisations --------------------
+    for k in range(warmup):
+        step(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(warmup + k)
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / steps
+    restore()
+    return ms, reg
+
+
+def describe(wl, ms):
+    return {"workload": wl["cfg"]["text"], "n_quantized_params": wl["n_q"], "n_fp32_params": wl["n_f"],
+            "n_variables": len(wl["specs"]), "packed_bytes": wl["packed"], "launches_per_step": wl["plan"].launches,
+            "algorithmic_bytes_per_step": wl["alg_step"],
+            "step_GBps_algorithmic": wl["alg_step"] / (ms * 1e-3) / 1e9,
+            "step_frac_hbm_peak": wl["alg_step"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "Gparam_per_s": (wl["n_q"] + wl["n_f"]) / (ms * 1e-3) / 1e9}
+
+
+# ------------------------------------------------------------------------------------------------
+# CPU baseline: the oracle on a bounded sample of the headline set
+# ------------------------------------------------------------------------------------------------
+def cpu_baseline(torch, omc, synth, wl, sample_blocks, iters):
+    """The oracle as it stands on the variables of the first `sample_blocks` Conformer blocks of the workload (their
+    values and gradients downloaded from the GPU), one thread and all cores, `iters` iterations each.  Returns the
+    timings and whether the GPU's first step on those variables equals the oracle's, bit for bit."""
+    import numpy as np
+    from oracle import omc_oracle as orc
+    specs, lay, mask, fm = wl["specs"], wl["lay"], wl["mask"], wl["fm"]
+    pick = [i for i, s in enumerate(specs)
+            if s.name.startswith("block") and int(s.name.split("/")[0][5:]) < sample_blocks]
+    ofs = [orc.Format(*fm[i]) if mask[i] else None for i in pick]
+    sizes = iter([orc.packed_bytes(specs[i].n, ofs[j].bits) for j, i in enumerate(pick) if mask[i]])
+    sub_mask = mask[pick]
+    sub_lay = synth.make_layout([specs[i] for i in pick], sub_mask, lambda n: next(sizes))
+    arena = np.zeros(sub_lay.arena_bytes, np.uint8)
+    sbt = np.zeros((len(pick), 2), np.float32)
+    sbt[:, 0] = 1.0
+    grads = [np.zeros(sub_lay.aux_elems, np.float32) for _ in wl["grads"]]
+    for j, i in enumerate(pick):
+        s, a, b, d = specs[i], int(lay.aux_offset[i]), int(sub_lay.aux_offset[j]), int(sub_lay.data_offset[j])
+        x = wl["vals"][a:a + s.n].cpu().numpy()
+        for g_host, g_dev in zip(grads, wl["grads"]):
+            g_host[b:b + s.n] = g_dev[a:a + s.n].cpu().numpy()
+        if sub_mask[j]:
+            p, sb = orc.compress(x, ofs[j])
+            arena[d:d + p.size] = p
+            sbt[j] = sb
+        else:
+            arena[d:d + 4 * s.n] = x.view(np.uint8)
+    table = orc.make_var_table(dict(data_offset=int(sub_lay.data_offset[j]), aux_offset=int(sub_lay.aux_offset[j]),
+                                    n=specs[i].n, fmt=ofs[j], quantized=bool(sub_mask[j])) for j, i in enumerate(pick))
+    kind = {"sgd": 0, "momentum": 1, "adam": 2}[wl["cfg"]["kind"]]
+    arena0, sbt0 = arena.copy(), sbt.copy()
+    cores = os.cpu_count() or 1
+    out = {"pick": pick, "sub_lay": sub_lay, "sub_mask": sub_mask, "cores": cores,
+           "n_elems": int(sum(specs[i].n for i in pick)),
+           "packed_bytes": int(sum(orc.packed_bytes(specs[i].n, ofs[j].bits) for j, i in enumerate(pick) if sub_mask[j]))}
+    for label, threads in (("one_thread", 1), ("all_cores", cores)):
+        arena[:] = arena0
+        sbt[:] = sbt0
+        m = np.zeros(sub_lay.aux_elems, np.float32) if kind >= 1 else None
+        v = np.zeros(sub_lay.aux_elems, np.float32) if kind == 2 else None
+        t0 = time.perf_counter()
+        for t in range(iters):
+            orc.step_varset(arena, table, sbt, grads[t % len(grads)], m, v,
+                            orc.Opt(kind=kind, lr=wl["cfg"]["lr"], t=t + 1), threads=threads)
+            if t == 0 and label == "one_thread":
+                out["first"] = (arena.copy(), sbt.copy(), None if m is None else m.copy())
+        out[label] = (time.perf_counter() - t0) / iters
+    return out
+
+
+def parity_on_sample(torch, omc, wl, cpu):
+    """One GPU step from the initial state against the oracle's first step on the sampled variables."""
+    import numpy as np
+    step_fn(omc, wl)(0)
+    torch.cuda.synchronize()
+    oa, osb, om = cpu["first"]
+    ok = True
+    for j, i in enumerate(cpu["pick"]):
+        s = wl["specs"][i]
+        d, e = int(wl["lay"].data_offset[i]), int(cpu["sub_lay"].data_offset[j])
+        a, b = int(wl["lay"].aux_offset[i]), int(cpu["sub_lay"].aux_offset[j])
+        nb = omc.omc_packed_bytes(wl["gfs"][i], s.n) if wl["mask"][i] else 4 * s.n
+        ok &= bool(np.array_equal(wl["arena"][d:d + nb].cpu().numpy(), oa[e:e + nb]))
+        if wl["mask"][i]:
+            ok &= bool(np.array_equal(wl["sb"][i].cpu().numpy().view(np.uint32), osb[j].view(np.uint32)))
+        if om is not None:
+            ok &= bool(np.array_equal(wl["m"][a:a + s.n].cpu().numpy().view(np.uint32), om[b:b + s.n].view(np.uint32)))
+    return ok
+
+
+# ------------------------------------------------------------------------------------------------
+# other legs
+# ------------------------------------------------------------------------------------------------
 def copy_ceiling(torch, n=1 << 28, iters=20):
-    """GB/s of the runtime's own device-to-device copy of 1 GiB (2 GiB moved): the practical ceiling for a
-    kernel that writes as much as it reads, measured in the same run."""
+    """GB/s of the runtime's own device-to-device copy of 1 GiB (2 GiB moved), measured in the same run."""
     src = torch.empty(n, device="cuda").normal_()
     dst = torch.empty_like(src)
     warm(torch, lambda k: dst.copy_(src))
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        dst.copy_(src)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / iters
+    ms = timed(torch, lambda k: dst.copy_(src), iters)
     return 8.0 * n / (ms * 1e-3) / 1e9
 
 
@@ -153,14 +342,9 @@ def gemm_leg(torch, omc, synth, iters=20):
         omc.omc_compress(W, K * N, gf, True, codes, sb, wsc)
         C = torch.empty((M, N), dtype=torch.float32, device="cuda")
         ws = torch.empty(omc.omc_dequant_gemm_workspace_bytes(M), dtype=torch.uint8, device="cuda")
-        warm(torch, lambda k: omc.omc_dequant_gemm(A, codes, gf, sb, C, M, N, K, ws))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            omc.omc_dequant_gemm(A, codes, gf, sb, C, M, N, K, ws)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / iters
+        f = lambda k: omc.omc_dequant_gemm(A, codes, gf, sb, C, M, N, K, ws)
+        warm(torch, f)
+        ms = timed(torch, f, iters)
         tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
         rec = {"M": M, "N": N, "K": K, "ms": ms, "TFLOPs": tf, "frac_of_bf16_mfma_peak": tf / 2500.0,
                "hbm_bytes": 2 * M * K + K * N + 4 * M * N}
@@ -169,13 +353,9 @@ def gemm_leg(torch, omc, synth, iters=20):
         codes11 = torch.zeros(omc.omc_packed_bytes(gf11, K * N), dtype=torch.uint8, device="cuda")
         sb11 = torch.zeros(2, device="cuda")
         omc.omc_compress(W, K * N, gf11, True, codes11, sb11, wsc)
-        warm(torch, lambda k: omc.omc_dequant_gemm(A, codes11, gf11, sb11, C, M, N, K, ws))
-        e0.record()
-        for _ in range(iters):
-            omc.omc_dequant_gemm(A, codes11, gf11, sb11, C, M, N, K, ws)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / iters
+        f = lambda k: omc.omc_dequant_gemm(A, codes11, gf11, sb11, C, M, N, K, ws)
+        warm(torch, f)
+        ms = timed(torch, f, iters)
         rec["S1E3M7_ms"] = ms
         rec["S1E3M7_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
         del codes11
@@ -183,26 +363,18 @@ def gemm_leg(torch, omc, synth, iters=20):
         del C
         dY = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * N, 1.0, 13)).view(np.int16)).cuda()
         dX = torch.empty((M, K), dtype=torch.float32, device="cuda")
-        warm(torch, lambda k: omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws))
-        e0.record()
-        for _ in range(iters):
-            omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / iters
+        f = lambda k: omc.omc_dequant_gemm_dx(dY, codes, gf, sb, dX, M, N, K, ws)
+        warm(torch, f)
+        ms = timed(torch, f, iters)
         rec["dx_ms"] = ms
         rec["dx_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-        # and its weight gradient dW[K, N] = X^T @ dY, consumed by the SGD update + recompression in the epilogue
+        # and its weight gradient dW[K, N] = X^T @ dY, consumed by the SGD update + recompression
         del dX
         wsd = torch.empty(omc.omc_dw_update_workspace_bytes(gf, M, N, K), dtype=torch.uint8, device="cuda")
         o = omc.opt(omc.OMC_SGD, 0.01)
-        warm(torch, lambda k: omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd))
-        e0.record()
-        for _ in range(iters):
-            omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / iters
+        f = lambda k: omc.omc_dw_update_recompress(A, dY, codes, gf, sb, True, None, None, o, None, M, N, K, wsd)
+        warm(torch, f)
+        ms = timed(torch, f, iters)
         rec["dw_update_ms"] = ms
         rec["dw_update_TFLOPs"] = 2.0 * M * N * K / (ms * 1e-3) / 1e12
         rec["dw_workspace_bytes"] = wsd.numel()   # fit partials + parked accumulators of the contraction splits
@@ -210,25 +382,20 @@ def gemm_leg(torch, omc, synth, iters=20):
     return out
 
 
-def set_conversion_leg(torch, omc, wl, n_q, n_f, iters=20):
+def set_conversion_leg(torch, omc, wl, iters=20):
     """Whole-set conversions (start / end of a round): fp32 -> packed arena and back, one call each."""
     lay, plan = wl["lay"], wl["plan"]
+    n_q, n_f = wl["n_q"], wl["n_f"]
     arena = torch.empty_like(wl["arena"])
     sb = torch.empty_like(wl["sb"])
     out = torch.empty(lay.aux_elems, device="cuda")
     ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
     res = {}
     for name, fn, nbytes in (
-            ("compress_set", lambda: omc.omc_compress_set(wl["vals_d"], plan, arena, sb, ws), 5.0 * n_q + 8.0 * n_f),
-            ("decompress_set", lambda: omc.omc_decompress_set(arena, plan, sb, out), 5.0 * n_q + 8.0 * n_f)):
-        warm(torch, lambda k: fn())
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / iters
+            ("compress_set", lambda k: omc.omc_compress_set(wl["vals"], plan, arena, sb, ws), 5.0 * n_q + 8.0 * n_f),
+            ("decompress_set", lambda k: omc.omc_decompress_set(arena, plan, sb, out), 5.0 * n_q + 8.0 * n_f)):
+        warm(torch, fn)
+        ms = timed(torch, fn, iters)
         res[name] = {"ms": ms, "algorithmic_GBps": nbytes / (ms * 1e-3) / 1e9,
                      "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     res["transport_bytes"] = plan.transport_bytes
@@ -236,10 +403,27 @@ def set_conversion_leg(torch, omc, wl, n_q, n_f, iters=20):
     return res
 
 
+def single_compress_leg(torch, omc, n=1 << 26, iters=20):
+    """omc_compress / omc_decompress of one 64 M-element variable (S1E4M3)."""
+    gf = omc.fmt(4, 3)
+    x = torch.empty(n, device="cuda").normal_(0.0, 0.05)
+    codes = torch.zeros(omc.omc_packed_bytes(gf, n), dtype=torch.uint8, device="cuda")
+    sb = torch.zeros(2, device="cuda")
+    ws = torch.empty(omc.omc_compress_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    out = torch.empty(n, device="cuda")
+    res = {"elements": n}
+    for name, fn in (("compress", lambda k: omc.omc_compress(x, n, gf, True, codes, sb, ws)),
+                     ("decompress", lambda k: omc.omc_decompress(codes, n, gf, sb, out))):
+        warm(torch, fn)
+        ms = timed(torch, fn, iters)
+        res[name] = {"ms": ms, "algorithmic_GBps": 5.0 * n / (ms * 1e-3) / 1e9,
+                     "frac_hbm_peak": 5.0 * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    return res
+
+
 def aggregate_leg(torch, omc, synth, blocks, R=8, iters=20):
     """Server side of a round: mean of R clients' copies of the set, each client with its own 90 %
     subset of the weight matrices in S1E4M3 and the rest in fp32."""
-    import numpy as np
     specs = synth.conformer_varset(512, blocks, 2048, 32, frontend=True)
     gf = omc.fmt(4, 3)
     arenas, sbs, plans = [], [], []
@@ -264,23 +448,18 @@ def aggregate_leg(torch, omc, synth, blocks, R=8, iters=20):
     alg += 4.0 * n_total
     agg = omc.omc_aggregate_plan_build(plans)
     out = torch.empty(vals_d.numel(), device="cuda")
-    warm(torch, lambda k: omc.omc_aggregate_mean(agg, arenas, sbs, out))
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(iters):
-        omc.omc_aggregate_mean(agg, arenas, sbs, out)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / iters
+    f = lambda k: omc.omc_aggregate_mean(agg, arenas, sbs, out)
+    warm(torch, f)
+    ms = timed(torch, f, iters)
     return {"clients": R, "params": n_total, "ms": ms, "algorithmic_bytes": alg,
             "algorithmic_GBps": alg / (ms * 1e-3) / 1e9, "frac_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "fp32_clients_bytes": 4.0 * n_total * (R + 1)}
 
 
-def formats_leg(torch, omc, synth, blocks, steps=20):
-    """The fused decompress + SGD + recompress kernel on the same variable set for every storage
-    format of the paper's tables (Tables 1-3: 19-, 13-, 11- and 6-bit), per-variable transformation on
-    and, for the 11-bit format, off (the ablation's switch)."""
+def formats_leg(torch, omc, synth, blocks, flush, steps=20):
+    """The fused decompress + SGD + recompress kernel on the 115 M-parameter set for every storage format of the
+    paper's tables (Tables 1-3: 19-, 13-, 11- and 6-bit), per-variable transformation on and, for the 11-bit format,
+    off (the ablation's switch); default flags, caches flushed between steps as in the roofline blocks."""
     import numpy as np
     specs = synth.conformer_varset(512, blocks, 2048, 32, frontend=True)
     mask = np.array([s.is_matrix for s in specs])
@@ -307,6 +486,7 @@ def formats_leg(torch, omc, synth, blocks, steps=20):
         ev = omc.HipEvents(2 * nl * steps)
         warm(torch, lambda k: omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], None, None, o, ws))
         for k in range(steps):
+            flush[1].copy_(flush[0])
             omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], None, None, o, ws, ev, first=k * 2 * nl)
         torch.cuda.synchronize()
         ms = sum(ev.elapsed_ms(k * 2 * nl, k * 2 * nl + 1) for k in range(steps)) / steps
@@ -317,89 +497,29 @@ def formats_leg(torch, omc, synth, blocks, steps=20):
     return res
 
 
-def other_configs_leg(torch, omc, synth, steps=10):
-    """The other step configurations of the baseline at full size (they are parity-test cases first; timed here
-    for reference): config 3 = the benchmark set with half of the matrices quantized in three formats (8, 11,
-    16 bit) and Adam; config 4 = a 604 M-parameter set (24 blocks, d_model 1024, ffn 4096) in S1E3M7 with momentum."""
-    import numpy as np
-    res = []
-    for name, dims, frac, choices, kind, lr in (
-            ("config3: 17 blocks d=512, 50% of matrices quantized (S1E4M3 / S1E3M7 / S1E5M10), Adam",
-             (512, 17, 2048, 32, True), 0.5, [(4, 3), (3, 7), (5, 10)], omc.OMC_ADAM, 1e-3),
-            ("config4: 24 blocks d=1024 ffn=4096, all matrices S1E3M7, momentum 0.9",
-             (1024, 24, 4096, 32, False), None, [(3, 7)], omc.OMC_MOMENTUM, 0.01)):
-        specs = synth.conformer_varset(dims[0], dims[1], dims[2], dims[3], frontend=dims[4])
-        mask = synth.ppq_mask(specs, frac, 3) if frac is not None else np.array([s.is_matrix for s in specs])
-        fm = [choices[i % len(choices)] for i in range(len(specs))]
-        gfs = [omc.fmt(*fm[i]) if mask[i] else None for i in range(len(specs))]
-        sizes = iter([omc.omc_packed_bytes(gfs[i], specs[i].n) for i in range(len(specs)) if mask[i]])
-        lay = synth.make_layout(specs, mask, lambda n: next(sizes))
-        table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gfs[i],
-                      quantized=bool(mask[i])) for i, s in enumerate(specs)]
-        plan = omc.omc_plan_build(omc.make_var_table(table))
-        gen = torch.Generator(device="cuda").manual_seed(5)
-        vals = torch.empty(lay.aux_elems, device="cuda")
-        for i, s in enumerate(specs):
-            a = int(lay.aux_offset[i])
-            vals[a:a + s.n].normal_(0.0, 1.0 / np.sqrt(s.fan_in) if s.is_matrix else 0.02, generator=gen)
-        grads = [torch.empty(lay.aux_elems, device="cuda").normal_(0.0, 1e-3, generator=gen) for _ in range(2)]
-        arena = torch.zeros(lay.arena_bytes, dtype=torch.uint8, device="cuda")
-        sb = torch.zeros((len(specs), 2), device="cuda")
-        ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
-        omc.omc_compress_set(vals, plan, arena, sb, ws)
-        del vals
-        m = torch.zeros(lay.aux_elems, device="cuda")
-        v = torch.zeros(lay.aux_elems, device="cuda") if kind == omc.OMC_ADAM else None
-        state = 8.0 if kind == omc.OMC_MOMENTUM else 16.0
-        alg = sum((2.0 * (1 + sum(fm[i])) / 8.0 + 4.0 + state) * s.n if mask[i] else (12.0 + state) * s.n
-                  for i, s in enumerate(specs))
-        packed = sum(omc.omc_packed_bytes(gfs[i], s.n) for i, s in enumerate(specs) if mask[i])
-        t = warm(torch, lambda k: omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=k + 1), ws))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for k in range(steps):
-            omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=t + k + 1), ws)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
-        nl = plan.launches
-        ev = omc.HipEvents(2 * nl * steps)
-        for k in range(steps):
-            omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], m, v, omc.opt(kind, lr, t=t + steps + k + 1), ws, ev,
-                                                  first=k * 2 * nl)
-        torch.cuda.synchronize()
-        kms = [sum(ev.elapsed_ms(k * 2 * nl + 2 * j, k * 2 * nl + 2 * j + 1) for k in range(steps)) / steps for j in range(nl)]
-        res.append({"workload": name, "params": int(sum(s.n for s in specs)), "launches_per_step": plan.launches,
-                    "ms_per_step": ms, "kernel_ms": kms, "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
-                    "frac_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                    "compressed_param_GBps": packed / (ms * 1e-3) / 1e9})
-        del arena, sb, ws, m, v, grads, plan
-        torch.cuda.empty_cache()
-    return res
-
-
 def main():
     global LEG_WARMUP_S
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--blocks", type=int, default=17, help="Conformer blocks (17 = the benchmark workload)")
-    ap.add_argument("--cpu-sample-blocks", type=int, default=4)
-    ap.add_argument("--cpu-iters", type=int, default=6)
+    ap.add_argument("--config", default="config4", choices=sorted(STEP_CONFIGS),
+                    help="step configuration timed as the headline (default: the largest, config4)")
+    ap.add_argument("--blocks", type=int, default=None, help="override the number of Conformer blocks (smaller runs)")
+    ap.add_argument("--cpu-sample-blocks", type=int, default=1)
+    ap.add_argument("--cpu-iters", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
-    ap.add_argument("--leg-warmup-s", type=float, default=LEG_WARMUP_S, help="untimed wall time before each extra leg's measurement (profiler runs shorten it)")
-    ap.add_argument("--step-only", action="store_true", help="skip the extra legs (set conversions, aggregation, formats, "
-                                                             "other configurations, matrix-core kernels); for profiler runs")
-    ap.add_argument("--eager", action="store_true", help="(default) one library call per step")
+    ap.add_argument("--leg-warmup-s", type=float, default=LEG_WARMUP_S,
+                    help="untimed wall time before each extra leg's measurement")
+    ap.add_argument("--step-only", action="store_true",
+                    help="only the headline configuration: no other configurations, no extra legs (for profiler runs)")
+    ap.add_argument("--flush-between-steps", action="store_true",
+                    help="with --step-only: run the timed steps with the cache-flushing copy before each of them "
+                         "(for profiler runs of the evicted regime; the reported ms_per_step then includes the copies)")
     ap.add_argument("--clock-warmup-s", type=float, default=0.5,
                     help="seconds of untimed steps before any measurement, so that the GPU clocks have ramped up")
-    ap.add_argument("--graph", action="store_true",
-                    help="time HIP graph replays of two captured steps instead (checked against eager launches first); "
-                         "measured: no faster than eager launches on this machine")
-    ap.add_argument("--gemm-only", action="store_true", help="only the forward GEMM leg (for profiler runs)")
+    ap.add_argument("--gemm-only", action="store_true", help="only the matrix-core leg (for profiler runs)")
     ap.add_argument("--aggregate-only", action="store_true", help="only the server aggregation leg")
-    ap.add_argument("--configs-only", action="store_true", help="only the leg over the baseline's other step configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device-to-device copy of known size (1 GiB read + 1 GiB written "
                          "per launch) to calibrate profiler byte counters and show the copy ceiling")
@@ -409,7 +529,6 @@ def main():
         sys.exit("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
                  "(no collectives or sharding exist in this library)")
 
-    import numpy as np
     import torch
     from paper_2205_03494_amd import omc, synth
 
@@ -422,179 +541,49 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(20):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 20
+        ms = timed(torch, lambda k: dst.copy_(src), 20)
         print(json.dumps({"copy_kernel": "torch Tensor.copy_ fp32", "bytes_read": 4 * n, "bytes_written": 4 * n,
                           "ms": ms, "GBps": 8 * n / (ms * 1e-3) / 1e9}))
         return
     if args.gemm_only:
-        print(json.dumps({"gemm": gemm_leg(torch, omc, synth)}))
-        return
-    if args.configs_only:
-        print(json.dumps({"other_step_configs": other_configs_leg(torch, omc, synth)}))
+        print(json.dumps({"forward_gemm": gemm_leg(torch, omc, synth)}))
         return
     if args.aggregate_only:
-        print(json.dumps({"server_aggregation": aggregate_leg(torch, omc, synth, args.blocks)}))
+        print(json.dumps({"server_aggregation": aggregate_leg(torch, omc, synth, 17)}))
         return
-    wl = build_workload(torch, omc, synth, args.blocks, 512, 2048)
-    specs, mask, lay, plan = wl["specs"], wl["mask"], wl["lay"], wl["plan"]
-    # a ring of two pre-generated gradient sets, resident in HBM
-    wl["grads_host"] = [synth.gradients(lay, 1e-3, 1000 + k) for k in range(2)]
-    grads = [torch.from_numpy(g).cuda() for g in wl["grads_host"]]
-    ws = torch.empty(max(plan.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
-    o = omc.opt(omc.OMC_SGD, 0.01)
-    arena, sb = wl["arena"], wl["sb"]
-    arena0, sb0 = arena.clone(), sb.clone()
 
-    n_q = int(sum(s.n for s, q in zip(specs, mask) if q))
-    n_f = int(sum(s.n for s, q in zip(specs, mask) if not q))
-    packed_bytes = int(sum(omc.omc_packed_bytes(omc.fmt(4, 3), s.n) for s, q in zip(specs, mask) if q))
-    alg_bytes_q = 6.0 * n_q            # per element: 1 B code in + 4 B gradient in + 1 B code out
-    alg_bytes_step = alg_bytes_q + 12.0 * n_f + 8.0 * int(mask.sum())
+    flush = (torch.empty(1 << 27, device="cuda"), torch.empty(1 << 27, device="cuda"))    # 512 MiB each
+    wl = build_step_workload(torch, omc, synth, args.config, blocks=args.blocks)
 
-    def step(k):
-        omc.omc_step_update_recompress(arena, plan, sb, grads[k % 2], None, None, o, ws)
-
-    # ---- parity spot check + CPU baseline (oracle) on a bounded sample ------------------------
-    cpu = None
-    parity = None
+    # ---- CPU baseline (oracle) on a bounded sample + parity of the GPU's first step on that sample --------------
+    cpu = parity = None
     if not args.no_cpu:
-        threads = min(16, os.cpu_count() or 1)
-        cpu = cpu_baseline(wl, synth, min(args.cpu_sample_blocks, args.blocks), args.cpu_iters, threads)
-        step(0)
-        torch.cuda.synchronize()
-        ga, gs = arena.cpu().numpy(), sb.cpu().numpy()
-        oa, osb = cpu["first"]
-        parity = True
-        for j, i in enumerate(cpu["pick"]):
-            d, e = int(lay.data_offset[i]), int(cpu["sub_lay"].data_offset[j])
-            nb = omc.omc_packed_bytes(omc.fmt(4, 3), specs[i].n) if mask[i] else 4 * specs[i].n
-            parity &= bool(np.array_equal(ga[d:d + nb], oa[e:e + nb]))
-            if mask[i]:
-                parity &= bool(np.array_equal(gs[i], osb[j]))
-        arena.copy_(arena0)
-        sb.copy_(sb0)
+        cpu = cpu_baseline(torch, omc, synth, wl, args.cpu_sample_blocks, args.cpu_iters)
+        arena0, sb0 = wl["arena"].clone(), wl["sb"].clone()
+        parity = parity_on_sample(torch, omc, wl, cpu)
+        wl["arena"].copy_(arena0)
+        wl["sb"].copy_(sb0)
+        if wl["m"] is not None:
+            wl["m"].zero_()
+        wl["t"] = 0
+        del arena0, sb0
 
-    # ---- the step as a HIP graph: two steps (one per gradient buffer) captured once, replayed ----------
-    # The library only enqueues kernels on the caller's stream, so a caller can capture it; replaying
-    # removes the launch gaps between the fused kernel and the finalize.  Checked here against eager
-    # launches on the same state, over several replays, before it is used for the timed region.
-    graph = None
-    if args.graph:
-        cap = torch.cuda.Stream()
-        cap.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=cap):
-            omc.omc_step_update_recompress(arena, plan, sb, grads[0], None, None, o, ws, stream=cap)
-            omc.omc_step_update_recompress(arena, plan, sb, grads[1], None, None, o, ws, stream=cap)
+    if args.step_only and args.flush_between_steps:
+        step = step_fn(omc, wl)
+        warm(torch, step, args.clock_warmup_s)
         torch.cuda.synchronize()
-        arena.copy_(arena0)
-        sb.copy_(sb0)
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
-        ga, gs = arena.clone(), sb.clone()
-        arena.copy_(arena0)
-        sb.copy_(sb0)
-        for k in range(6):
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            flush[1].copy_(flush[0])
             step(k)
         torch.cuda.synchronize()
-        assert torch.equal(ga, arena) and torch.equal(gs.view(torch.int32), sb.view(torch.int32)), \
-            "graph replay and eager launches disagree"
-        arena.copy_(arena0)
-        sb.copy_(sb0)
-
-    def run_steps(n, first=0):
-        k = first
-        if graph is not None:
-            if k % 2 == 1 and n > 0:
-                step(k); k += 1; n -= 1
-            for _ in range(n // 2):
-                graph.replay()
-            k += 2 * (n // 2)
-            if n % 2:
-                step(k)
-        else:
-            for j in range(n):
-                step(k + j)
-
-    # ---- bring the GPU to its steady clocks: after idling (host-side set-up, the oracle leg) the first tens of
-    # milliseconds of kernels run at reduced clocks (measured: the same kernel 232 us -> 109 us), which
-    # W = 5 warm-up steps of 0.1 ms do not cover.  Untimed; the state is restored afterwards.
-    t_warm = time.perf_counter()
-    k = 0
-    while time.perf_counter() - t_warm < args.clock_warmup_s:
-        for _ in range(50):
-            step(k)
-            k += 1
-        torch.cuda.synchronize()
-    arena.copy_(arena0)
-    sb.copy_(sb0)
-
-    # ---- per-kernel durations: the steps with an event pair around every launch ------
-    nl = plan.launches
-    ev = omc.HipEvents(2 * nl * args.steps)
-    for k in range(args.steps):
-        omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], None, None, o, ws, ev,
-                                              first=k * 2 * nl)
-    torch.cuda.synchronize()
-    kern_ms = [0.0] * nl
-    for k in range(args.steps):
-        for j in range(nl):
-            kern_ms[j] += ev.elapsed_ms(k * 2 * nl + 2 * j, k * 2 * nl + 2 * j + 1)
-    kern_ms = [x / args.steps for x in kern_ms]
-    arena.copy_(arena0)
-    sb.copy_(sb0)
-    # ---- the same kernel when the packed codes do not come back from the memory-side cache: between two
-    # steps of a training loop lies a forward and a backward pass, which leaves nothing of the codes in the
-    # 256 MB Infinity Cache, while back-to-back steps find all 115 MB of them there.  A 512 MiB device copy
-    # between the steps (1 GiB of traffic) stands in for that pass; only the step kernel is timed.
-    cold_ms = None
-    if not args.step_only:
-        nc = min(args.steps, 30)
-        fl_src = torch.empty(1 << 27, device="cuda")
-        fl_dst = torch.empty_like(fl_src)
-        cold_ms = {}
-        for name, flags in (("default", 0), ("OMC_OPT_STREAM_CODES", omc.OMC_OPT_STREAM_CODES)):
-            oc = omc.opt(omc.OMC_SGD, 0.01, flags=flags)
-            ev2 = omc.HipEvents(2 * nl * nc)
-            for k in range(nc):
-                fl_dst.copy_(fl_src)
-                omc.omc_step_update_recompress_events(arena, plan, sb, grads[k % 2], None, None, oc, ws, ev2, first=k * 2 * nl)
-            torch.cuda.synchronize()
-            cold_ms[name] = sum(ev2.elapsed_ms(k * 2 * nl, k * 2 * nl + 1) for k in range(nc)) / nc
-            arena.copy_(arena0)
-            sb.copy_(sb0)
-        del fl_src, fl_dst
-    # ---- timed region: whole steps ---------------------------------------------------------------
-    run_steps(args.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(args.steps, first=args.warmup)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = 1e3 * dt / args.steps
-
-    dom_ms = kern_ms[0]                                     # launch 0: the 8-bit fused step kernel
-    achieved = alg_bytes_q / (dom_ms * 1e-3) / 1e9
-    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same command and
-    # scaled by a plain copy's reading (summary and commands: profiles/step_kernel_sgd8_conformer115m.md)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "step_kernel_sgd8_traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as fh:
-            tj = json.load(fh)
-        if tj.get("n_quantized_params") == n_q:
-            traffic = tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"]
-
+        ms_per_step, reg = 1e3 * (time.perf_counter() - t0) / args.steps, None
+    else:
+        ms_per_step, reg = measure_step_config(torch, omc, wl, args.steps, args.warmup, args.clock_warmup_s, flush,
+                                               regimes=True)
     out = {
         "metric": "compressed-param GB/s per decompress+update+recompress step; % HBM peak",
-        "value": packed_bytes / (ms_per_step * 1e-3) / 1e9,
+        "value": wl["packed"] / (ms_per_step * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -605,53 +594,46 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"conformer-encoder-shaped set, {args.blocks} blocks d_model=512 ffn=2048 conv_k=32 "
-                               f"+ front end, {n_q} weight-matrix params in S1E4M3 (8-bit) with per-variable "
-                               f"transformation, {n_f} fp32 bias/norm params, SGD lr=0.01, grads N(0,1e-3)",
-                   "n_quantized_params": n_q, "n_fp32_params": n_f, "n_variables": len(specs),
-                   "packed_bytes": packed_bytes, "algorithmic_bytes_per_step": alg_bytes_step,
-                   "step_GBps_algorithmic": alg_bytes_step / (ms_per_step * 1e-3) / 1e9,
-                   "Gparam_per_s": (n_q + n_f) / (ms_per_step * 1e-3) / 1e9,
-                   "launch": "one library call per step" if graph is None else
-                             "HIP graph of two steps (one per gradient buffer), replayed; checked against eager launches",
-
-                   "kernel_ms": {"step_kernel<8,sgd> (fp32 variables ride along)": kern_ms[0],
-                                 "tail_kernel": kern_ms[1] if nl > 2 else None,
-                                 "finalize_plan_kernel": kern_ms[-1]},
-                   "parity_vs_oracle_on_sample": parity},
-        "roofline": {"bound": "hbm", "kernel": "step_kernel<8,sgd>", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "algorithmic_bytes_per_launch": alg_bytes_q, "traffic": traffic},
+        "config": dict(describe(wl, ms_per_step), config=args.config, launch="one library call per step, default flags",
+                       parity_vs_oracle_on_sample=parity),
     }
-    if cold_ms is not None:     # the dominant kernel with the codes evicted from the memory-side cache between steps
-        out["roofline"]["codes_evicted_between_steps"] = {
-            "how": "a 512 MiB device-to-device copy between steps; only the step kernel is timed",
-            **{name: {"kernel_ms": ms, "achieved": alg_bytes_q / (ms * 1e-3) / 1e9,
-                      "frac": alg_bytes_q / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS} for name, ms in cold_ms.items()}}
-    del grads, arena0
-    torch.cuda.empty_cache()
-    if not args.step_only:
-        ceil = copy_ceiling(torch)
-        out["roofline"]["copy_kernel_GBps"] = ceil        # device-to-device copy of 1 GiB in this run
-        out["roofline"]["frac_of_copy_kernel"] = out["roofline"]["achieved"] / ceil
-        out["set_conversions"] = set_conversion_leg(torch, omc, wl, n_q, n_f)
-        del wl
-        torch.cuda.empty_cache()
-        out["server_aggregation"] = aggregate_leg(torch, omc, synth, args.blocks)
-        torch.cuda.empty_cache()
-        out["paper_formats_sgd"] = formats_leg(torch, omc, synth, args.blocks)
-        torch.cuda.empty_cache()
-        out["other_step_configs"] = other_configs_leg(torch, omc, synth)
-        out["forward_gemm"] = gemm_leg(torch, omc, synth)
+    if reg is not None:
+        out["roofline"] = roofline_block(wl, reg)
     if cpu is not None:
         out["cpu_baseline"] = {
-            "value": cpu["packed_bytes"] / cpu["sec_per_iter"] / 1e9, "unit": "GB/s",
-            "cores": min(16, os.cpu_count() or 1), "kind": "oracle",
-            "sample": f"first {min(args.cpu_sample_blocks, args.blocks)} Conformer blocks of the same set "
-                      f"({cpu['n_elems']} params), {args.cpu_iters} iterations, "
-                      f"{1e3 * cpu['sec_per_iter']:.0f} ms per iteration on {min(16, os.cpu_count() or 1)} threads "
-                      f"({args.cpu_iters * cpu['sec_per_iter'] * min(16, os.cpu_count() or 1):.0f} core-seconds)",
+            "value": cpu["packed_bytes"] / cpu["all_cores"] / 1e9, "unit": "GB/s", "cores": cpu["cores"], "kind": "oracle",
+            "one_thread_value": cpu["packed_bytes"] / cpu["one_thread"] / 1e9,
+            "sample": f"variables of the first {args.cpu_sample_blocks} Conformer block(s) of the same set "
+                      f"({cpu['n_elems']} params, {cpu['packed_bytes']} packed bytes), {args.cpu_iters} iterations each: "
+                      f"{1e3 * cpu['one_thread']:.0f} ms per iteration on one thread, {1e3 * cpu['all_cores']:.0f} ms on "
+                      f"{cpu['cores']} threads (os.cpu_count(); OpenMP over variables)",
         }
+    del wl
+    torch.cuda.empty_cache()
+    if not args.step_only:
+        others = []
+        for name in sorted(STEP_CONFIGS):
+            if name == args.config:
+                continue
+            w2 = build_step_workload(torch, omc, synth, name, blocks=args.blocks)
+            ms2, reg2 = measure_step_config(torch, omc, w2, min(args.steps, 50), args.warmup, LEG_WARMUP_S, flush)
+            rec = dict(describe(w2, ms2), config=name, ms_per_step=ms2,
+                       compressed_param_GBps=w2["packed"] / (ms2 * 1e-3) / 1e9, roofline=roofline_block(w2, reg2))
+            if name == "config2":
+                rec["set_conversions"] = set_conversion_leg(torch, omc, w2)
+            others.append(rec)
+            del w2
+            torch.cuda.empty_cache()
+        out["other_step_configs"] = others
+        out["copy_kernel_GBps"] = copy_ceiling(torch)          # the runtime's device-to-device copy of 1 GiB, same run
+        out["single_variable_64M"] = single_compress_leg(torch, omc)
+        torch.cuda.empty_cache()
+        blocks = 17 if args.blocks is None else min(args.blocks, 17)
+        out["server_aggregation"] = aggregate_leg(torch, omc, synth, blocks)
+        torch.cuda.empty_cache()
+        out["paper_formats_sgd"] = formats_leg(torch, omc, synth, blocks, flush)
+        torch.cuda.empty_cache()
+        out["forward_gemm"] = gemm_leg(torch, omc, synth)
     print(json.dumps(out))
 
 

@@ -110,13 +110,22 @@ typedef struct {
  *                                                                         state0 = m, state1 = v
  * one_minus_beta* = fp32(1 - beta*) and bias_corr* = fp32(1 - beta*^t) are computed by the caller
  * in fp64 and rounded once.
- * flags: OMC_OPT_STREAM_CODES tells the step that other work runs on the GPU between two steps (the
- * forward and backward pass of a training loop), so that nothing of the packed codes is left in the
- * memory-side cache when the next step starts: all code accesses then carry the non-temporal hint
- * instead of the first 224 MiB staying cached (see omc_step_update_recompress_events).  It changes
- * memory traffic only, never a value.  Unknown bits are OMC_ERR_OPT. */
+ * flags choose the cache policy of the packed codes, which every step reads and rewrites in place; they
+ * change memory traffic only, never a value.
+ *   default (0)           a training loop runs a forward and a backward pass between two update steps
+ *                         (Sec. 2.1), so nothing of the codes is left in the GPU's 256 MB memory-side
+ *                         cache when the next step starts: all code accesses carry the non-temporal hint
+ *                         and stream past the caches, like gradients and optimizer state always do.
+ *   OMC_OPT_STREAM_CODES  names the default explicitly (accepted, no effect).
+ *   OMC_OPT_KEEP_CODES    for callers that run steps back to back with nothing in between (benchmarks,
+ *                         several optimizer steps per gradient): the first 224 MiB of codes (all of them
+ *                         up to 264 MiB) are accessed with ordinary cached loads and stores, so that they
+ *                         come back from the memory-side cache at the next step
+ *                         (see omc_step_update_recompress_events).
+ * Both bits together, or unknown bits, are OMC_ERR_OPT. */
 typedef enum { OMC_SGD = 0, OMC_MOMENTUM = 1, OMC_ADAM = 2 } omc_opt_kind;
 #define OMC_OPT_STREAM_CODES 1u
+#define OMC_OPT_KEEP_CODES 2u
 typedef struct {
     int32_t kind; /* omc_opt_kind */
     float lr;
@@ -237,8 +246,8 @@ uint64_t omc_plan_transport_bytes(const void *plan_host);
  * full-tile kernel ran, one kernel for the fp32 variables; then the per-variable
  * finalize, if any variable is quantized.  omc_plan_launches gives the count; nevents must be at
  * least twice that (OMC_ERR_SIZE otherwise).  Results are identical to the plain call.
- * A full-tile kernel may be enqueued as two launches, one event pair around both: packed codes are
- * read and rewritten in place by every step, so when a set holds more than 264 MiB of them, the
+ * Under OMC_OPT_KEEP_CODES a full-tile kernel may be enqueued as two launches, one event pair around
+ * both: packed codes are read and rewritten in place by every step, so when a set holds more than 264 MiB of them, the
  * work items holding the first 224 MiB (in launch order) access their codes with ordinary cached
  * loads and stores, which lets them come back from the GPU's 256 MB memory-side cache at the
  * next step, and the work items after that limit access theirs with the non-temporal hint so that

@@ -182,6 +182,11 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
     return OMC_OK;
 }
 
+static bool opt_flags_ok(uint32_t flags) {
+    if (flags & ~(OMC_OPT_STREAM_CODES | OMC_OPT_KEEP_CODES)) return false;
+    return flags != (OMC_OPT_STREAM_CODES | OMC_OPT_KEEP_CODES);   // the two policies exclude each other
+}
+
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace omc
@@ -390,7 +395,7 @@ omc_status omc_step_update_recompress_events(void *arena, size_t arena_bytes, co
     const PlanHeader *ph = plan_check(plan_host);
     if (!ph) return OMC_ERR_PLAN;
     if (opt->kind != OMC_SGD && opt->kind != OMC_MOMENTUM && opt->kind != OMC_ADAM) return OMC_ERR_OPT;
-    if (opt->flags & ~OMC_OPT_STREAM_CODES) return OMC_ERR_OPT;
+    if (!opt_flags_ok(opt->flags)) return OMC_ERR_OPT;
     if (opt->kind >= OMC_MOMENTUM && !state0) return OMC_ERR_OPT;
     if (opt->kind == OMC_ADAM && !state1) return OMC_ERR_OPT;
     if (arena_bytes < ph->arena_bytes || aux_elems < ph->aux_elems) return OMC_ERR_SIZE;
@@ -686,7 +691,7 @@ omc_status omc_dw_update_recompress(const uint16_t *X, const uint16_t *dY, void 
     if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
     if (M == 0 || N == 0 || K == 0 || M % 32 != 0 || K % 256 != 0 || N % 128 != 0) return OMC_ERR_SIZE;
     if (opt->kind != OMC_SGD && opt->kind != OMC_MOMENTUM && opt->kind != OMC_ADAM) return OMC_ERR_OPT;
-    if (opt->flags & ~OMC_OPT_STREAM_CODES) return OMC_ERR_OPT;
+    if (!opt_flags_ok(opt->flags)) return OMC_ERR_OPT;
     if (opt->kind >= OMC_MOMENTUM && !state0) return OMC_ERR_OPT;
     if (opt->kind == OMC_ADAM && !state1) return OMC_ERR_OPT;
     if (!aligned16(X) || !aligned16(dY) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return OMC_ERR_ALIGN;

@@ -81,14 +81,16 @@ int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *
     }
     fuse = fuse && fp32_group != nullptr;
     bool fused_done = false;
-    // Packed codes are read and rewritten by every step and come back from the memory-side cache at the
-    // next step if they still sit there; gradients are new every step and never do.  Work items get to keep
+    // Packed codes are read and rewritten by every step.  In a training loop a forward and a backward pass lie
+    // between two steps and nothing survives in the caches, so by default every code access carries the
+    // non-temporal hint.  A caller that runs steps back to back asks for OMC_OPT_KEEP_CODES: the codes then
+    // come back from the memory-side cache at the next step if they still sit there.  Work items get to keep
     // their codes cached, in launch order, up to a budget below that cache's 256 MB; the codes of all other
     // items carry the non-temporal hint and pass it by.  A group whose items fall on both sides of the limit
     // is launched in two parts.
     uint64_t keep_budget = 0;                              // bytes of packed codes that stay cached
     uint32_t fp32_keep_items = 0;                          // fp32 work items whose values stay cached
-    if (!(opt.flags & OMC_OPT_STREAM_CODES)) {             // (set: the caller runs other work between steps, nothing would survive)
+    if (opt.flags & OMC_OPT_KEEP_CODES) {                  // (default: other work runs between two steps, nothing would survive)
         const uint64_t cache = static_cast<uint64_t>(OMC_TUNE_KEEP_BUDGET_MIB) << 20;
         uint64_t all_codes = 0;
         for (uint32_t gi = 0; gi < ph->ngroups; ++gi)

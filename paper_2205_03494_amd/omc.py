@@ -30,6 +30,7 @@ OMC_VAR_QUANTIZED = 1
 OMC_VAR_NO_PVT = 2
 OMC_SGD, OMC_MOMENTUM, OMC_ADAM = 0, 1, 2
 OMC_OPT_STREAM_CODES = 1
+OMC_OPT_KEEP_CODES = 2
 OMC_BIAS_DEFAULT = -1
 
 

@@ -176,7 +176,8 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert call(arena=None) == 1
     assert call(s1=None) == 6
     assert call(o=omc.opt(7, 1e-3)) == 6
-    assert call(o=omc.opt(omc.OMC_ADAM, 1e-3, flags=2)) == 6          # unknown flag bit
+    assert call(o=omc.opt(omc.OMC_ADAM, 1e-3, flags=4)) == 6          # unknown flag bit
+    assert call(o=omc.opt(omc.OMC_ADAM, 1e-3, flags=3)) == 6          # both cache policies at once
     assert call(ab=100) == 3
     assert call(aux=10) == 3
     assert call(wsb=8) == 5

@@ -33,7 +33,7 @@ def pick_samples(specs, mask, k_extra=3):
     return sorted(idx)
 
 
-def run_fullsize(specs, mask, fmts, kind, lr, steps, seed, max_sample_elems=14_000_000, first_samples=()):
+def run_fullsize(specs, mask, fmts, kind, lr, steps, seed, max_sample_elems=14_000_000, first_samples=(), flags=0):
     gfs = [omc.fmt(*fmts[i]) if mask[i] else None for i in range(len(specs))]
     sizes = iter([omc.omc_packed_bytes(gfs[i], specs[i].n) for i in range(len(specs)) if mask[i]])
     lay = synth.make_layout(specs, mask, lambda n: next(sizes))
@@ -82,7 +82,7 @@ def run_fullsize(specs, mask, fmts, kind, lr, steps, seed, max_sample_elems=14_0
         else:
             ost[i] = dict(w=x.copy(), m=np.zeros(s.n, np.float32), v=np.zeros(s.n, np.float32))
     for t in range(1, steps + 1):
-        omc.omc_step_update_recompress(arena, plan, sb, grads[t % 2], m, v, omc.opt(kind, lr, t=t), ws2)
+        omc.omc_step_update_recompress(arena, plan, sb, grads[t % 2], m, v, omc.opt(kind, lr, t=t, flags=flags), ws2)
         torch.cuda.synchronize()
         for i in samples:
             s = specs[i]
@@ -124,8 +124,9 @@ def test_config3_full_size_partial_quantization_three_formats_adam():
 
 
 def test_config3_set_under_sgd_fp32_values_on_both_sides_of_the_cache_budget():
-    """Same set as configuration 3 under plain SGD: 78 MB of codes stay cached and the 249 MB of fp32 matrices get
-    what is left of the budget, so their work items fall on both sides of that limit within one launch."""
+    """Same set as configuration 3 under plain SGD with OMC_OPT_KEEP_CODES: 78 MB of codes stay cached and the
+    249 MB of fp32 matrices get what is left of the budget, so their work items fall on both sides of that limit
+    within one launch."""
     specs = synth.conformer_varset(512, 17, 2048, 32, frontend=True)
     mask = synth.ppq_mask(specs, 0.5, 3)
     choices = [(4, 3), (3, 7), (5, 10)]
@@ -139,17 +140,19 @@ def test_config3_set_under_sgd_fp32_values_on_both_sides_of_the_cache_budget():
             break
     assert cut
     ns, total = run_fullsize(specs, mask, fmts, kind=0, lr=0.01, steps=2, seed=7, max_sample_elems=14_000_000,
-                             first_samples=cut + [f32[0], f32[-1]])
+                             first_samples=cut + [f32[0], f32[-1]], flags=omc.OMC_OPT_KEEP_CODES)
     assert ns >= 6
 
 
-def test_config4_full_size_momentum_11bit():
+@pytest.mark.parametrize("flags", [0, omc.OMC_OPT_KEEP_CODES])
+def test_config4_full_size_momentum_11bit(flags):
     specs = synth.conformer_varset(1024, 24, 4096, 32, frontend=False)
     mask = np.array([s.is_matrix for s in specs])
     assert 5.9e8 < sum(s.n for s in specs if s.is_matrix) < 6.2e8
     fmts = [(3, 7)] * len(specs)
-    # 832 MB of packed codes: the step keeps the first 224 MiB of them cached and streams the rest, as two
-    # launches of the fused kernel; the variable that the limit cuts through and its neighbours are checked first
+    # 832 MB of packed codes: by default all of them stream; with OMC_OPT_KEEP_CODES the step keeps the first 224 MiB
+    # cached and streams the rest, as two launches of the fused kernel.  The variable that this limit cuts through
+    # and its neighbours are checked first
     done, cut = 0, None
     for i, s in enumerate(specs):
         if mask[i]:
@@ -160,13 +163,13 @@ def test_config4_full_size_momentum_11bit():
     assert cut is not None
     near = [i for i in range(cut - 3, cut + 4) if 0 <= i < len(specs) and mask[i]][:3]
     ns, total = run_fullsize(specs, mask, fmts, kind=1, lr=0.01, steps=2, seed=4, max_sample_elems=16_000_000,
-                             first_samples=near)
+                             first_samples=near, flags=flags)
     assert ns >= 6
 
 
 def test_large_mixed_set_adam_launches_on_both_sides_of_the_cache_budget():
     """604 M-parameter set, 90 % of the matrices quantized in three widths, Adam: 0.79 GB of packed codes.  The
-    step keeps the first 224 MiB of codes cached: all of the 8-bit group's launch and a part of the 11-bit
+    step (with OMC_OPT_KEEP_CODES) keeps the first 224 MiB of codes cached: all of the 8-bit group's launch and a part of the 11-bit
     group's, which is launched in two parts, while the 16-bit group streams as a whole; the fp32 matrices ride
     along with the first launch.  Sampled: the variables around the cut, and the usual first / last / largest."""
     specs = synth.conformer_varset(1024, 24, 4096, 32, frontend=False)
@@ -185,7 +188,7 @@ def test_large_mixed_set_adam_launches_on_both_sides_of_the_cache_budget():
     assert near
     first = near + [by_width[8][-1], by_width[16][0]]
     ns, total = run_fullsize(specs, mask, fmts, kind=2, lr=1e-3, steps=2, seed=6, max_sample_elems=24_000_000,
-                             first_samples=first)
+                             first_samples=first, flags=omc.OMC_OPT_KEEP_CODES)
     assert ns >= 8
 
 

@@ -164,9 +164,10 @@ def test_varset_mixed_arena(kind, lr):
     assert mism == 0
 
 
+@pytest.mark.parametrize("flags", [omc.OMC_OPT_STREAM_CODES, omc.OMC_OPT_KEEP_CODES])
 @pytest.mark.parametrize("kind,lr", [(0, 0.05), (2, 1e-3)])
-def test_stream_codes_flag_changes_no_value(kind, lr):
-    """OMC_OPT_STREAM_CODES only changes cache hints: same set, same steps, same bits."""
+def test_cache_policy_flags_change_no_value(kind, lr, flags):
+    """OMC_OPT_KEEP_CODES / OMC_OPT_STREAM_CODES only change cache hints: same set, same steps, same bits."""
     specs = synth.conformer_varset(96, 3, 384, 8, frontend=True)
     mask = synth.ppq_mask(specs, 0.5, 11)
     choices = [(4, 3), (3, 7), (2, 3), (4, 14)]
@@ -176,7 +177,7 @@ def test_stream_codes_flag_changes_no_value(kind, lr):
     for t in range(1, 4):
         g = synth.gradients(vs.lay, 0.02, 80 + t)
         vs.step_oracle(g, kind, lr, t)
-        vs.step_gpu(to_dev(g), kind, lr, t, flags=omc.OMC_OPT_STREAM_CODES)
+        vs.step_gpu(to_dev(g), kind, lr, t, flags=flags)
         mism += vs.compare(kind, f"t={t}")
     assert mism == 0
 
