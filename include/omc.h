@@ -18,8 +18,8 @@
  * Conventions that hold for every entry point
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
  *     process memory.  The library allocates nothing, frees nothing and keeps no pointer after
- *     a call returns.  There is no global state; calls on different streams may overlap as long
- *     as their buffers do not.
+ *     a call returns.  There is no global state (with the one exception stated at
+ *     omc_compress_noalloc); calls on different streams may overlap as long as their buffers do not.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
  *     on it and the call returns without synchronising.
  *   - Arguments are validated on the host before anything is enqueued: every status other than
@@ -167,6 +167,22 @@ size_t omc_compress_workspace_bytes(uint64_t n);
  * v and codes must not overlap. */
 omc_status omc_compress(const float *v, uint64_t n, omc_format f, int use_pvt, void *codes,
                         float *sb, void *ws, size_t ws_bytes, void *stream);
+
+/* omc_compress for callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc -- and so cannot bring a workspace: the partial sums of
+ * the fit go to a 2 MiB device array that is part of the library image (each GPU the library runs on
+ * holds its own copy until the process ends).  Same arguments, same results bit for bit as omc_compress;
+ * v, codes and sb are still the caller's.  The call allocates and frees nothing (its first use on a
+ * device looks the array's address up once).
+ *   n        at most omc_compress_noalloc_max_elems() (107 368 448), OMC_ERR_SIZE beyond
+ * This is the one piece of state the library keeps: all calls on one GPU share that GPU's array, so two
+ * such calls must not overlap in time on the same GPU (different streams, different threads): they would
+ * race on the partial sums.  Calls on one stream, one after the other, are fine; nothing is carried over
+ * from one call to the next.  The array belongs to the device that is current when the call is made,
+ * which must be the device of `stream` and of the buffers. */
+uint64_t omc_compress_noalloc_max_elems(void);
+omc_status omc_compress_noalloc(const float *v, uint64_t n, omc_format f, int use_pvt, void *codes,
+                                float *sb, void *stream);
 
 /* Decompress n elements: out_k = fl32(fl32(s*Vtilde_k) + b)  (Sec. 2.1, 2.3).
  *   codes    device, omc_packed_bytes(f, n) bytes, read only

@@ -247,6 +247,31 @@ omc_status omc_compress(const float *v, uint64_t n, omc_format f, int use_pvt, v
     return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
 }
 
+uint64_t omc_compress_noalloc_max_elems(void) {
+    // largest n whose partial sums fit the static array: one partial per kMinTilesPerChunk full tiles, one for the tail
+    const uint64_t parts = kStaticScratchBytes / sizeof(Partial);
+    return (parts - 1) * kMinTilesPerChunk * kTileElems;
+}
+
+omc_status omc_compress_noalloc(const float *v, uint64_t n, omc_format f, int use_pvt, void *codes, float *sb,
+                                void *stream) {
+    if (!v || !codes || !sb) return OMC_ERR_NULL;
+    FmtParams fp;
+    if (!make_fmt_params(f, &fp)) return OMC_ERR_FORMAT;
+    if (n == 0 || n > omc_compress_noalloc_max_elems()) return OMC_ERR_SIZE;
+    if (omc_compress_workspace_bytes(n) > kStaticScratchBytes) return OMC_ERR_SIZE;
+    if (!aligned16(v) || !aligned16(codes) || (reinterpret_cast<uintptr_t>(sb) & 3u)) return OMC_ERR_ALIGN;
+    const size_t pb = packed_bytes_u(fp.bits, n);
+    const uintptr_t v0 = reinterpret_cast<uintptr_t>(v), c0 = reinterpret_cast<uintptr_t>(codes);
+    if (v0 < c0 + pb && c0 < v0 + 4 * n) return OMC_ERR_SIZE;  // input and output overlap
+    void *ws = nullptr;
+    if (static_scratch(&ws) != 0) return OMC_ERR_DEVICE;
+    // every partial the finalize reads is written by this call's kernels first: nothing has to start at zero
+    VarArgs va{n, pb / 4, fp};
+    const int rc = launch_compress(v, va, use_pvt, codes, sb, static_cast<Partial *>(ws), stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
 omc_status omc_decompress(const void *codes, uint64_t n, omc_format f, const float *sb, float *out,
                           void *stream) {
     if (!codes || !out) return OMC_ERR_NULL;

@@ -1,4 +1,6 @@
 // omc_compress / omc_compress_set: fp32 values -> packed codes + partial sums of the fit, then (s, b).
+#include <mutex>
+
 #include "omc_codec_impl.h"
 
 namespace omc {
@@ -84,6 +86,38 @@ int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes,
     else
         finalize_single_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
     return static_cast<int>(hipGetLastError());
+}
+
+// ---- a workspace that nobody has to allocate ------------------------------------------------------
+// omc_compress_noalloc serves callers that cannot allocate device memory (code under HIP graph
+// capture, tight serving loops, harnesses that forbid it): the partial sums of the fit go to this
+// file-scope device array instead of a caller's workspace.  Every GPU the library runs on holds its
+// own copy of the array, at its own address, until the process ends.  In host code the array's name
+// is only a handle for the runtime's symbol lookup, not a device address: the address is asked for
+// once per device (that device current) and all host-side uses go through the pointer kept here.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices] = {nullptr};    // per device: address of that device's copy of `scratch`
+}  // namespace
+
+int static_scratch(void **ptr_out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return static_cast<int>(e);
+    if (dev < 0 || dev >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return static_cast<int>(e);
+        if (!p) return static_cast<int>(hipErrorInvalidSymbol);
+        scratch_ptr[dev] = p;
+    }
+    *ptr_out = scratch_ptr[dev];
+    return 0;
 }
 
 int launch_compress_set(const float *values, const PlanHeader *ph, const void *plan_dev, void *arena,

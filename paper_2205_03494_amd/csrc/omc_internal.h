@@ -148,6 +148,10 @@ struct VarArgs {
 
 int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb,
                     Partial *ws, void *stream);
+// Size of the library's own device scratch array (omc_compress_noalloc) and the address of the current
+// device's copy of it (looked up once per device); returns a hipError_t as int.
+constexpr size_t kStaticScratchBytes = 2u << 20;
+int static_scratch(void **ptr_out);
 int launch_decompress(const void *codes, const VarArgs &va, const float *sb, float *out, void *stream);
 int launch_compress_set(const float *values, const PlanHeader *ph, const void *plan_dev, void *arena,
                         float *sb_table, Partial *ws, void *stream);

@@ -65,6 +65,8 @@ _format_max = _sig("omc_format_max", C.c_float, omc_format)
 _packed_bytes = _sig("omc_packed_bytes", C.c_size_t, omc_format, C.c_uint64)
 _compress_ws = _sig("omc_compress_workspace_bytes", C.c_size_t, C.c_uint64)
 _compress = _sig("omc_compress", C.c_int, _vp, C.c_uint64, omc_format, C.c_int, _vp, _vp, _vp, C.c_size_t, _vp)
+_compress_noalloc = _sig("omc_compress_noalloc", C.c_int, _vp, C.c_uint64, omc_format, C.c_int, _vp, _vp, _vp)
+_compress_noalloc_max = _sig("omc_compress_noalloc_max_elems", C.c_uint64)
 _decompress = _sig("omc_decompress", C.c_int, _vp, C.c_uint64, omc_format, _vp, _vp, _vp)
 _plan_bytes = _sig("omc_plan_bytes", C.c_size_t, _vp, C.c_uint32)
 _plan_build = _sig("omc_plan_build", C.c_int, _vp, C.c_uint32, _vp, C.c_size_t)
@@ -94,6 +96,7 @@ _gemm_dx = _sig("omc_dequant_gemm_dx", C.c_int, _vp, _vp, omc_format, _vp, _vp, 
 
 EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_format_max",
             "omc_packed_bytes", "omc_compress_workspace_bytes", "omc_compress", "omc_decompress",
+            "omc_compress_noalloc", "omc_compress_noalloc_max_elems",
             "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_workspace_bytes", "omc_plan_arena_bytes",
             "omc_plan_aux_elems", "omc_plan_launches", "omc_step_update_recompress",
             "omc_step_update_recompress_events", "omc_compress_set", "omc_decompress_set",
@@ -168,6 +171,16 @@ def omc_compress(v: torch.Tensor, n: int, f: omc_format, use_pvt: bool, codes: t
                  sb: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
     _check(_compress(_ptr(v), n, f, int(use_pvt), _ptr(codes), _ptr(sb), _ptr(ws),
                      ws.numel() * ws.element_size(), _stream(stream)), "omc_compress")
+
+
+def omc_compress_noalloc_max_elems() -> int:
+    return _compress_noalloc_max()
+
+
+def omc_compress_noalloc(v: torch.Tensor, n: int, f: omc_format, use_pvt: bool, codes: torch.Tensor,
+                         sb: torch.Tensor, stream=None) -> None:
+    _check(_compress_noalloc(_ptr(v), n, f, int(use_pvt), _ptr(codes), _ptr(sb), _stream(stream)),
+           "omc_compress_noalloc")
 
 
 def omc_decompress(codes: torch.Tensor, n: int, f: omc_format, sb: Optional[torch.Tensor],
