@@ -403,6 +403,48 @@ def set_conversion_leg(torch, omc, wl, iters=20):
     return res
 
 
+def round_boundary_leg(torch, omc, synth, blocks, iters=20):
+    """What happens between two rounds on the 115 M-parameter set with the paper's 90 % partial quantization (S1E3M7):
+    omc_reselect to another seeded 90 % subset (only the switched matrices are converted, the rest move as bytes), and
+    omc_transport_pack of the set into one message."""
+    specs = synth.conformer_varset(512, blocks, 2048, 32, frontend=True)
+    gf = omc.fmt(3, 7)
+    plans, lays = [], []
+    for seed in (1, 2):
+        mask = synth.ppq_mask(specs, 0.9, seed)
+        lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(gf, n))
+        table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gf,
+                      quantized=bool(mask[i])) for i, s in enumerate(specs)]
+        plans.append(omc.omc_plan_build(omc.make_var_table(table)))
+        lays.append(lay)
+    vals = torch.empty(lays[0].aux_elems, device="cuda").normal_(0.0, 0.03)
+    arena_a = torch.zeros(lays[0].arena_bytes, dtype=torch.uint8, device="cuda")
+    sb_a = torch.zeros((len(specs), 2), device="cuda")
+    ws = torch.empty(max(plans[0].workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    omc.omc_compress_set(vals, plans[0], arena_a, sb_a, ws)
+    del vals
+    rs = omc.omc_reselect_plan_build(plans[0], plans[1])
+    arena_b = torch.zeros(lays[1].arena_bytes, dtype=torch.uint8, device="cuda")
+    sb_b = torch.zeros_like(sb_a)
+    ws2 = torch.empty(max(rs.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    f = lambda k: omc.omc_reselect(rs, arena_a, sb_a, arena_b, sb_b, ws2)
+    warm(torch, f)
+    ms = timed(torch, f, iters)
+    alg = float(rs.algorithmic_bytes)
+    res = {"reselect": {"ms": ms, "algorithmic_bytes": alg, "algorithmic_GBps": alg / (ms * 1e-3) / 1e9,
+                        "frac_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                        "fp32_copy_of_the_model_bytes": 4.0 * sum(s.n for s in specs)}}
+    nbytes = omc.omc_transport_bytes(plans[1])
+    msg = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    f = lambda k: omc.omc_transport_pack(plans[1], arena_b, sb_b, msg)
+    warm(torch, f)
+    ms = timed(torch, f, iters)
+    res["transport_pack"] = {"ms": ms, "message_bytes": nbytes, "algorithmic_GBps": 2.0 * nbytes / (ms * 1e-3) / 1e9,
+                             "frac_hbm_peak": 2.0 * nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "message_over_fp32": nbytes / (4.0 * sum(s.n for s in specs))}
+    return res
+
+
 def single_compress_leg(torch, omc, n=1 << 26, iters=20):
     """omc_compress / omc_decompress of one 64 M-element variable (S1E4M3)."""
     gf = omc.fmt(4, 3)
@@ -629,6 +671,8 @@ def main():
         out["single_variable_64M"] = single_compress_leg(torch, omc)
         torch.cuda.empty_cache()
         blocks = 17 if args.blocks is None else min(args.blocks, 17)
+        out["round_boundary"] = round_boundary_leg(torch, omc, synth, blocks)
+        torch.cuda.empty_cache()
         out["server_aggregation"] = aggregate_leg(torch, omc, synth, blocks)
         torch.cuda.empty_cache()
         out["paper_formats_sgd"] = formats_leg(torch, omc, synth, blocks, flush)

@@ -14,6 +14,8 @@
  *   omc_dequant_gemm_dx          dX = dY * decompress(W)^T                                (Sec. 2.1, backward path)
  *   omc_dw_update_recompress     dW = X^T dY consumed by the update in the GEMM's epilogue  (Sec. 2.1, backward path)
  *   omc_aggregate_mean           server: mean of R clients' mixed-precision copies        (Sec. 1, 2.5)
+ *   omc_reselect                 a new round's quantized subset without a full-precision copy (Sec. 2.5)
+ *   omc_transport_pack / _open   the packed set as one self-describing message / checkpoint  (Sec. 1)
  *
  * Conventions that hold for every entry point
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
@@ -250,6 +252,63 @@ omc_status omc_compress_set(const float *values, uint64_t aux_elems, const void 
 omc_status omc_decompress_set(const void *arena, size_t arena_bytes, const void *plan_host, const void *plan_dev,
                               const float *sb_table, float *out, uint64_t aux_elems, void *stream);
 uint64_t omc_plan_transport_bytes(const void *plan_host);
+
+/* ---- a new round with another quantized subset (Sec. 2.5) ----------------------------------------
+ * Partial parameter quantization picks the variables to quantize anew for every round and every client.
+ * omc_reselect converts a set from the old selection (plan_old, its arena and (s, b) table) to the new one
+ * (plan_new, another arena and table) in one pass and without a full-precision copy of the model:
+ *   - a variable that becomes quantized is compressed straight from its fp32 values in the old arena
+ *     into the new arena (Sec. 2.2, 2.3: codes and a fresh (s, b));
+ *   - a variable that becomes fp32 is decompressed straight from its codes into the new arena;
+ *   - every other variable is moved as bytes (its codes and (s, b), or its fp32 values), untouched.
+ * Results are bit-identical to omc_decompress / omc_compress applied to the switched variables alone.
+ * The two plans must list the same variables (count and sizes); a variable quantized in both must keep
+ * its format (OMC_ERR_FORMAT otherwise: changing the format of codes is a decompress + compress).
+ *
+ * omc_reselect_plan_bytes / _build: host only; derive the conversion's own blob from the two host plans
+ *   (position independent; the caller copies it to the device, 16-byte aligned).
+ * omc_reselect_workspace_bytes, omc_reselect_algorithmic_bytes: device workspace of the call, and the bytes
+ *   the conversion has to move (2 x size of every moved variable, 4n + packed size of every converted one).
+ * omc_reselect:
+ *   arena_old, sb_old   device: the set under plan_old (read only)
+ *   arena_new, sb_new   device: receive the set under plan_new; must not overlap the old ones
+ *   ws                  device workspace of omc_reselect_workspace_bytes(rs_host) bytes */
+size_t omc_reselect_plan_bytes(const void *plan_old_host, const void *plan_new_host);
+omc_status omc_reselect_plan_build(const void *plan_old_host, const void *plan_new_host, void *rs_host,
+                                   size_t rs_bytes);
+size_t omc_reselect_workspace_bytes(const void *rs_host);
+uint64_t omc_reselect_algorithmic_bytes(const void *rs_host);
+omc_status omc_reselect(const void *rs_host, const void *rs_dev, const void *arena_old, size_t arena_old_bytes,
+                        const float *sb_old, void *arena_new, size_t arena_new_bytes, float *sb_new, void *ws,
+                        size_t ws_bytes, void *stream);
+
+/* ---- transport / checkpoint message (Sec. 1) ------------------------------------------------------
+ * The paper keeps and transports parameters in compressed form: what a client sends back, what the server
+ * sends out and what a checkpoint holds is the packed set itself.  omc_transport_pack serialises a set into
+ * one self-describing buffer
+ *     [ header | variable table | (s, b) table, 2 floats per variable | payload ]
+ * whose payload holds every variable's packed stream (or fp32 values) back to back at 16-byte aligned
+ * offsets, in table order.  Its size, omc_transport_bytes(plan), is omc_plan_transport_bytes(plan) plus the
+ * header and table, 8 bytes per fp32 variable (the (s, b) table has an entry for every variable) and
+ * alignment padding.  The message needs no unpacking: omc_transport_open validates the header and table
+ * (magic, version, sizes, dense payload, checksum; OMC_ERR_PLAN otherwise) and returns an omc_var table
+ * whose data offsets are relative to the payload, so that the receiver builds a plan from it and uses the
+ * message body in place as arena (msg + arena_offset) and (s, b) table (msg + sb_offset).
+ *   omc_transport_meta_bytes   size of header + variable table: the prefix of the message that
+ *                              omc_transport_open needs in host memory
+ *   omc_transport_pack         device to device; msg_dev 16-byte aligned, at least omc_transport_bytes long,
+ *                              not overlapping the arena
+ *   omc_transport_open         host only.  vars_out == NULL: only *nvars_out and the offsets are returned
+ *                              (prefix of at least 64 bytes); otherwise the prefix must hold the whole table and
+ *                              vars_cap >= nvars (OMC_ERR_SIZE).  Optimizer state is not part of the message: it
+ *                              is the caller's own fp32 arrays. */
+size_t omc_transport_meta_bytes(uint32_t nvars);
+uint64_t omc_transport_bytes(const void *plan_host);
+omc_status omc_transport_pack(const void *plan_host, const void *plan_dev, const void *arena, size_t arena_bytes,
+                              const float *sb_table, void *msg_dev, size_t msg_bytes, void *stream);
+omc_status omc_transport_open(const void *msg_prefix_host, size_t prefix_bytes, uint64_t msg_bytes,
+                              omc_var *vars_out, uint32_t vars_cap, uint32_t *nvars_out, uint64_t *sb_offset,
+                              uint64_t *arena_offset, uint64_t *arena_bytes, uint64_t *aux_elems);
 
 /* Measurement aid.  Same work as omc_step_update_recompress; additionally records caller-owned HIP
  * events (hipEvent_t passed as void*) on the stream around every kernel launch, so that a

@@ -182,6 +182,88 @@ static omc_status plan_layout(const omc_var *vars, uint32_t nvars, PlanLayout *p
     return OMC_OK;
 }
 
+// Validates the table and writes the plan blob.  sb_index: entry of the (s, b) table per variable, or
+// nullptr for the identity (a plan built from a caller's table).
+static omc_status build_plan(const omc_var *vars_host, const uint32_t *sb_index, uint32_t nvars, void *plan_host,
+                             size_t plan_bytes) {
+    if (!plan_host) return OMC_ERR_NULL;
+    PlanLayout pl;
+    const omc_status st = plan_layout(vars_host, nvars, &pl);
+    if (st != OMC_OK) return st;
+    if (plan_bytes < pl.total) return OMC_ERR_SIZE;
+    uint8_t *base = static_cast<uint8_t *>(plan_host);
+    std::memset(base, 0, pl.total);
+    PlanHeader *ph = reinterpret_cast<PlanHeader *>(base);
+    PlanVar *pv = reinterpret_cast<PlanVar *>(base + pl.var_off);
+    PlanItem *items = reinterpret_cast<PlanItem *>(base + pl.item_off);
+    PlanGroup *groups = reinterpret_cast<PlanGroup *>(base + pl.group_off);
+    uint64_t arena_bytes = 0, aux_elems = 0;
+    for (uint32_t i = 0; i < nvars; ++i) {
+        const omc_var &v = vars_host[i];
+        PlanVar &d = pv[i];
+        d.data_offset = v.data_offset;
+        d.aux_offset = v.aux_offset;
+        d.n = v.n;
+        d.flags = v.flags;
+        uint64_t bytes;
+        if (v.flags & OMC_VAR_QUANTIZED) {
+            make_fmt_params(v.fmt, &d.fp);
+            bytes = packed_bytes_u(d.fp.bits, v.n);
+            d.total_dwords = bytes / 4;
+        } else {
+            bytes = 4 * v.n;
+        }
+        d.sb_index = sb_index ? sb_index[i] : i;
+        d.first_item = kNoItem;
+        d.nitems = 0;
+        d.tail_item = kNoItem;
+        arena_bytes = std::max(arena_bytes, v.data_offset + bytes);
+        aux_elems = std::max(aux_elems, v.aux_offset + v.n);
+    }
+    uint32_t next = 0;
+    for (uint32_t gi = 0; gi < pl.ngroups; ++gi) {
+        PlanGroup g = pl.groups[gi];
+        g.first_item = next;
+        for (uint32_t i = 0; i < nvars; ++i) {
+            const omc_var &v = vars_host[i];
+            const bool q = (v.flags & OMC_VAR_QUANTIZED) != 0;
+            if (g.kind == kGroupFull) {
+                if (!q || pv[i].fp.bits != g.bits || pv[i].fp.variant != g.wide || v.n < kTileElems) continue;
+                pv[i].first_item = next;
+                pv[i].nitems = static_cast<uint32_t>((v.n / kTileElems + tiles_per_chunk(g.bits) - 1) / tiles_per_chunk(g.bits));
+                for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
+            } else if (g.kind == kGroupTail) {
+                if (!q || pv[i].fp.wide != g.wide || v.n % kTileElems == 0) continue;
+                pv[i].tail_item = next;
+                items[next++] = PlanItem{i, 0};
+            } else {
+                if (q) continue;
+                pv[i].first_item = next;
+                pv[i].nitems = static_cast<uint32_t>((v.n + kChunkElems - 1) / kChunkElems);
+                for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
+            }
+        }
+        g.nitems = next - g.first_item;
+        groups[gi] = g;
+    }
+    ph->magic = kPlanMagic;
+    ph->version = kPlanVersion;
+    ph->nvars = nvars;
+    ph->nitems = pl.nitems;
+    ph->ngroups = pl.ngroups;
+    ph->nquant = pl.nquant;
+    ph->total_bytes = pl.total;
+    ph->var_off = pl.var_off;
+    ph->item_off = pl.item_off;
+    ph->group_off = pl.group_off;
+    ph->arena_bytes = arena_bytes;
+    ph->aux_elems = aux_elems;
+    ph->ws_bytes = std::max<uint64_t>(16, static_cast<uint64_t>(pl.nitems) * sizeof(Partial));
+    ph->checksum = body_checksum(base + sizeof(PlanHeader), pl.total - sizeof(PlanHeader));
+    return OMC_OK;
+}
+
+
 static bool opt_flags_ok(uint32_t flags) {
     if (flags & ~(OMC_OPT_STREAM_CODES | OMC_OPT_KEEP_CODES)) return false;
     return flags != (OMC_OPT_STREAM_CODES | OMC_OPT_KEEP_CODES);   // the two policies exclude each other
@@ -294,80 +376,7 @@ size_t omc_plan_bytes(const omc_var *vars_host, uint32_t nvars) {
 }
 
 omc_status omc_plan_build(const omc_var *vars_host, uint32_t nvars, void *plan_host, size_t plan_bytes) {
-    if (!plan_host) return OMC_ERR_NULL;
-    PlanLayout pl;
-    const omc_status st = plan_layout(vars_host, nvars, &pl);
-    if (st != OMC_OK) return st;
-    if (plan_bytes < pl.total) return OMC_ERR_SIZE;
-    uint8_t *base = static_cast<uint8_t *>(plan_host);
-    std::memset(base, 0, pl.total);
-    PlanHeader *ph = reinterpret_cast<PlanHeader *>(base);
-    PlanVar *pv = reinterpret_cast<PlanVar *>(base + pl.var_off);
-    PlanItem *items = reinterpret_cast<PlanItem *>(base + pl.item_off);
-    PlanGroup *groups = reinterpret_cast<PlanGroup *>(base + pl.group_off);
-    uint64_t arena_bytes = 0, aux_elems = 0;
-    for (uint32_t i = 0; i < nvars; ++i) {
-        const omc_var &v = vars_host[i];
-        PlanVar &d = pv[i];
-        d.data_offset = v.data_offset;
-        d.aux_offset = v.aux_offset;
-        d.n = v.n;
-        d.flags = v.flags;
-        uint64_t bytes;
-        if (v.flags & OMC_VAR_QUANTIZED) {
-            make_fmt_params(v.fmt, &d.fp);
-            bytes = packed_bytes_u(d.fp.bits, v.n);
-            d.total_dwords = bytes / 4;
-        } else {
-            bytes = 4 * v.n;
-        }
-        d.first_item = kNoItem;
-        d.nitems = 0;
-        d.tail_item = kNoItem;
-        arena_bytes = std::max(arena_bytes, v.data_offset + bytes);
-        aux_elems = std::max(aux_elems, v.aux_offset + v.n);
-    }
-    uint32_t next = 0;
-    for (uint32_t gi = 0; gi < pl.ngroups; ++gi) {
-        PlanGroup g = pl.groups[gi];
-        g.first_item = next;
-        for (uint32_t i = 0; i < nvars; ++i) {
-            const omc_var &v = vars_host[i];
-            const bool q = (v.flags & OMC_VAR_QUANTIZED) != 0;
-            if (g.kind == kGroupFull) {
-                if (!q || pv[i].fp.bits != g.bits || pv[i].fp.variant != g.wide || v.n < kTileElems) continue;
-                pv[i].first_item = next;
-                pv[i].nitems = static_cast<uint32_t>((v.n / kTileElems + tiles_per_chunk(g.bits) - 1) / tiles_per_chunk(g.bits));
-                for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
-            } else if (g.kind == kGroupTail) {
-                if (!q || pv[i].fp.wide != g.wide || v.n % kTileElems == 0) continue;
-                pv[i].tail_item = next;
-                items[next++] = PlanItem{i, 0};
-            } else {
-                if (q) continue;
-                pv[i].first_item = next;
-                pv[i].nitems = static_cast<uint32_t>((v.n + kChunkElems - 1) / kChunkElems);
-                for (uint32_t c = 0; c < pv[i].nitems; ++c) items[next++] = PlanItem{i, c};
-            }
-        }
-        g.nitems = next - g.first_item;
-        groups[gi] = g;
-    }
-    ph->magic = kPlanMagic;
-    ph->version = kPlanVersion;
-    ph->nvars = nvars;
-    ph->nitems = pl.nitems;
-    ph->ngroups = pl.ngroups;
-    ph->nquant = pl.nquant;
-    ph->total_bytes = pl.total;
-    ph->var_off = pl.var_off;
-    ph->item_off = pl.item_off;
-    ph->group_off = pl.group_off;
-    ph->arena_bytes = arena_bytes;
-    ph->aux_elems = aux_elems;
-    ph->ws_bytes = std::max<uint64_t>(16, static_cast<uint64_t>(pl.nitems) * sizeof(Partial));
-    ph->checksum = body_checksum(base + sizeof(PlanHeader), pl.total - sizeof(PlanHeader));
-    return OMC_OK;
+    return build_plan(vars_host, nullptr, nvars, plan_host, plan_bytes);
 }
 
 size_t omc_workspace_bytes(const omc_var *vars_host, uint32_t nvars) {
@@ -744,6 +753,313 @@ omc_status omc_dequant_gemm_dx(const uint16_t *dY, const void *codes, omc_format
     // output columns = K (the weights' rows), contraction over N
     const int rc = launch_dequant_gemm(dY, codes, fp, sb, dX, M, K, N, static_cast<float *>(ws), 1, stream);
     return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+}  // extern "C"
+
+// ---- change of the quantized subset between rounds (Sec. 2.5) ---------------------------------------
+namespace omc {
+struct ReselectLayout {
+    std::vector<uint32_t> actions;
+    std::vector<omc_var> c_vars, d_vars;       // derived tables
+    std::vector<uint32_t> c_index, d_index;    // their entries of the (s, b) table
+    uint64_t action_off, plan_c_off, plan_c_bytes, plan_d_off, plan_d_bytes, total;
+    uint64_t alg_bytes;
+};
+
+static omc_format format_of(const FmtParams &fp) {
+    omc_format f;
+    f.exp_bits = static_cast<uint8_t>(fp.exp_bits);
+    f.man_bits = static_cast<uint8_t>(fp.man_bits);
+    f.exp_bias = static_cast<int16_t>(fp.bias);
+    return f;
+}
+
+static const PlanVar *plan_vars(const PlanHeader *ph) {
+    return reinterpret_cast<const PlanVar *>(reinterpret_cast<const uint8_t *>(ph) + ph->var_off);
+}
+
+// Both plans must describe the same variable list (count, sizes); a variable that is quantized in both
+// must keep its format.  Every variable gets one action; the two derived tables address the old arena
+// as the "values" of a compress-set (offsets in floats) and the new arena as the output of a decompress-set.
+static omc_status reselect_layout(const void *old_host, const void *new_host, ReselectLayout *rl) {
+    const PlanHeader *po = plan_check(old_host), *pn = plan_check(new_host);
+    if (!po || !pn) return OMC_ERR_PLAN;
+    if (po->nvars != pn->nvars) return OMC_ERR_SIZE;
+    const PlanVar *vo = plan_vars(po), *vn = plan_vars(pn);
+    const uint32_t nvars = po->nvars;
+    rl->actions.assign(nvars, 0);
+    rl->c_vars.clear(); rl->d_vars.clear(); rl->c_index.clear(); rl->d_index.clear();
+    rl->alg_bytes = 0;
+    for (uint32_t i = 0; i < nvars; ++i) {
+        if (vo[i].n != vn[i].n) return OMC_ERR_SIZE;
+        const bool qo = (vo[i].flags & OMC_VAR_QUANTIZED) != 0, qn = (vn[i].flags & OMC_VAR_QUANTIZED) != 0;
+        omc_var v{};
+        if (qo == qn) {                                   // unchanged: its bytes move as a run of floats
+            if (qo && !(vo[i].fp.exp_bits == vn[i].fp.exp_bits && vo[i].fp.man_bits == vn[i].fp.man_bits &&
+                        vo[i].fp.bias == vn[i].fp.bias))
+                return OMC_ERR_FORMAT;
+            const uint64_t bytes = qo ? vo[i].total_dwords * 4 : 4 * vo[i].n;
+            rl->actions[i] = qo ? kRsCopyQuantized : kRsCopyFp32;
+            v.data_offset = vn[i].data_offset;
+            v.aux_offset = vo[i].data_offset / 4;
+            v.n = bytes / 4;
+            v.flags = 0;
+            rl->c_vars.push_back(v);
+            rl->c_index.push_back(i);
+            rl->alg_bytes += 2 * bytes;
+        } else if (qn) {                                  // fp32 -> codes: compressed straight from the old arena
+            rl->actions[i] = kRsToQuantized;
+            v.data_offset = vn[i].data_offset;
+            v.aux_offset = vo[i].data_offset / 4;
+            v.n = vn[i].n;
+            v.fmt = format_of(vn[i].fp);
+            v.flags = vn[i].flags;
+            rl->c_vars.push_back(v);
+            rl->c_index.push_back(i);
+            rl->alg_bytes += 4 * vn[i].n + vn[i].total_dwords * 4 + 8;
+        } else {                                          // codes -> fp32: decompressed straight into the new arena
+            rl->actions[i] = kRsToFp32;
+            v.data_offset = vo[i].data_offset;
+            v.aux_offset = vn[i].data_offset / 4;
+            v.n = vo[i].n;
+            v.fmt = format_of(vo[i].fp);
+            v.flags = vo[i].flags;
+            rl->d_vars.push_back(v);
+            rl->d_index.push_back(i);
+            rl->alg_bytes += 4 * vo[i].n + vo[i].total_dwords * 4 + 8;
+        }
+    }
+    rl->action_off = sizeof(ReselectHeader);
+    uint64_t off = align_up(rl->action_off + 4ull * nvars, 16);
+    rl->plan_c_off = rl->plan_c_bytes = rl->plan_d_off = rl->plan_d_bytes = 0;
+    if (!rl->c_vars.empty()) {
+        PlanLayout pl;
+        const omc_status st = plan_layout(rl->c_vars.data(), static_cast<uint32_t>(rl->c_vars.size()), &pl);
+        if (st != OMC_OK) return st;
+        rl->plan_c_off = off;
+        rl->plan_c_bytes = pl.total;
+        off = align_up(off + pl.total, 16);
+    }
+    if (!rl->d_vars.empty()) {
+        PlanLayout pl;
+        const omc_status st = plan_layout(rl->d_vars.data(), static_cast<uint32_t>(rl->d_vars.size()), &pl);
+        if (st != OMC_OK) return st;
+        rl->plan_d_off = off;
+        rl->plan_d_bytes = pl.total;
+        off = align_up(off + pl.total, 16);
+    }
+    rl->total = off;
+    return OMC_OK;
+}
+
+static const ReselectHeader *reselect_check(const void *rs_host) {
+    if (!rs_host) return nullptr;
+    const ReselectHeader *rh = static_cast<const ReselectHeader *>(rs_host);
+    if (rh->magic != kReselectMagic || rh->version != kReselectVersion || rh->nvars == 0) return nullptr;
+    if (rh->action_off != sizeof(ReselectHeader) || rh->total_bytes < rh->action_off + 4ull * rh->nvars) return nullptr;
+    const uint8_t *base = static_cast<const uint8_t *>(rs_host);
+    if (rh->checksum != body_checksum(base + sizeof(ReselectHeader), rh->total_bytes - sizeof(ReselectHeader))) return nullptr;
+    if (rh->plan_c_bytes && (rh->plan_c_off % 16 || rh->plan_c_off + rh->plan_c_bytes > rh->total_bytes)) return nullptr;
+    if (rh->plan_d_bytes && (rh->plan_d_off % 16 || rh->plan_d_off + rh->plan_d_bytes > rh->total_bytes)) return nullptr;
+    if (rh->plan_c_bytes && !plan_check(base + rh->plan_c_off)) return nullptr;
+    if (rh->plan_d_bytes && !plan_check(base + rh->plan_d_off)) return nullptr;
+    return rh;
+}
+
+static const TransportHeader *transport_check(const void *prefix, size_t prefix_bytes, uint64_t msg_bytes) {
+    if (!prefix || prefix_bytes < sizeof(TransportHeader)) return nullptr;
+    const TransportHeader *th = static_cast<const TransportHeader *>(prefix);
+    if (th->magic != kTransportMagic || th->version != kTransportVersion || th->nvars == 0) return nullptr;
+    if (th->nquant > th->nvars) return nullptr;
+    const uint64_t meta = align_up(sizeof(TransportHeader) + static_cast<uint64_t>(th->nvars) * sizeof(TransportVar), kTransportAlign);
+    if (th->sb_off != meta) return nullptr;
+    if (th->payload_off != align_up(th->sb_off + 8ull * th->nvars, kTransportAlign)) return nullptr;
+    if (th->total_bytes != th->payload_off + th->payload_bytes || th->payload_bytes % 16) return nullptr;
+    if (msg_bytes < th->total_bytes) return nullptr;
+    return th;
+}
+}  // namespace omc
+
+extern "C" {
+
+size_t omc_reselect_plan_bytes(const void *plan_old_host, const void *plan_new_host) {
+    ReselectLayout rl;
+    if (reselect_layout(plan_old_host, plan_new_host, &rl) != OMC_OK) return 0;
+    return static_cast<size_t>(rl.total);
+}
+
+omc_status omc_reselect_plan_build(const void *plan_old_host, const void *plan_new_host, void *rs_host, size_t rs_bytes) {
+    if (!rs_host) return OMC_ERR_NULL;
+    ReselectLayout rl;
+    const omc_status st = reselect_layout(plan_old_host, plan_new_host, &rl);
+    if (st != OMC_OK) return st;
+    if (rs_bytes < rl.total) return OMC_ERR_SIZE;
+    uint8_t *base = static_cast<uint8_t *>(rs_host);
+    std::memset(base, 0, rl.total);
+    ReselectHeader *rh = reinterpret_cast<ReselectHeader *>(base);
+    const PlanHeader *po = plan_check(plan_old_host), *pn = plan_check(plan_new_host);
+    std::memcpy(base + rl.action_off, rl.actions.data(), 4ull * rl.actions.size());
+    uint64_t ws = 16;
+    if (rl.plan_c_bytes) {
+        const omc_status sc = build_plan(rl.c_vars.data(), rl.c_index.data(), static_cast<uint32_t>(rl.c_vars.size()),
+                                         base + rl.plan_c_off, rl.plan_c_bytes);
+        if (sc != OMC_OK) return sc;
+        ws = std::max<uint64_t>(ws, reinterpret_cast<const PlanHeader *>(base + rl.plan_c_off)->ws_bytes);
+    }
+    if (rl.plan_d_bytes) {
+        const omc_status sd = build_plan(rl.d_vars.data(), rl.d_index.data(), static_cast<uint32_t>(rl.d_vars.size()),
+                                         base + rl.plan_d_off, rl.plan_d_bytes);
+        if (sd != OMC_OK) return sd;
+    }
+    rh->magic = kReselectMagic;
+    rh->version = kReselectVersion;
+    rh->nvars = po->nvars;
+    rh->total_bytes = rl.total;
+    rh->action_off = rl.action_off;
+    rh->plan_c_off = rl.plan_c_off; rh->plan_c_bytes = rl.plan_c_bytes;
+    rh->plan_d_off = rl.plan_d_off; rh->plan_d_bytes = rl.plan_d_bytes;
+    rh->arena_old_bytes = po->arena_bytes;
+    rh->arena_new_bytes = pn->arena_bytes;
+    rh->ws_bytes = ws;
+    rh->algorithmic_bytes = rl.alg_bytes;
+    rh->checksum = body_checksum(base + sizeof(ReselectHeader), rl.total - sizeof(ReselectHeader));
+    return OMC_OK;
+}
+
+size_t omc_reselect_workspace_bytes(const void *rs_host) {
+    const ReselectHeader *rh = reselect_check(rs_host);
+    return rh ? static_cast<size_t>(rh->ws_bytes) : 0;
+}
+
+uint64_t omc_reselect_algorithmic_bytes(const void *rs_host) {
+    const ReselectHeader *rh = reselect_check(rs_host);
+    return rh ? rh->algorithmic_bytes : 0;
+}
+
+omc_status omc_reselect(const void *rs_host, const void *rs_dev, const void *arena_old, size_t arena_old_bytes,
+                        const float *sb_old, void *arena_new, size_t arena_new_bytes, float *sb_new, void *ws,
+                        size_t ws_bytes, void *stream) {
+    if (!rs_host || !rs_dev || !arena_old || !sb_old || !arena_new || !sb_new) return OMC_ERR_NULL;
+    const ReselectHeader *rh = reselect_check(rs_host);
+    if (!rh) return OMC_ERR_PLAN;
+    if (arena_old_bytes < rh->arena_old_bytes || arena_new_bytes < rh->arena_new_bytes) return OMC_ERR_SIZE;
+    if (!aligned16(rs_dev) || !aligned16(arena_old) || !aligned16(arena_new) ||
+        (reinterpret_cast<uintptr_t>(sb_old) & 7u) || (reinterpret_cast<uintptr_t>(sb_new) & 7u))
+        return OMC_ERR_ALIGN;
+    if (!ws || ws_bytes < rh->ws_bytes) return OMC_ERR_WORKSPACE;
+    if (!aligned16(ws)) return OMC_ERR_ALIGN;
+    const uintptr_t o0 = reinterpret_cast<uintptr_t>(arena_old), n0 = reinterpret_cast<uintptr_t>(arena_new);
+    if (o0 < n0 + rh->arena_new_bytes && n0 < o0 + rh->arena_old_bytes) return OMC_ERR_SIZE;   // the arenas overlap
+    if (sb_old == sb_new) return OMC_ERR_SIZE;
+    const uint8_t *hb = static_cast<const uint8_t *>(rs_host);
+    const uint8_t *db = static_cast<const uint8_t *>(rs_dev);
+    int rc = 0;
+    if (rh->plan_c_bytes)
+        rc = launch_compress_set(static_cast<const float *>(arena_old), reinterpret_cast<const PlanHeader *>(hb + rh->plan_c_off),
+                                 db + rh->plan_c_off, arena_new, sb_new, static_cast<Partial *>(ws), stream);
+    if (rc == 0 && rh->plan_d_bytes)
+        rc = launch_decompress_set(arena_old, reinterpret_cast<const PlanHeader *>(hb + rh->plan_d_off), db + rh->plan_d_off,
+                                   sb_old, static_cast<float *>(arena_new), stream);
+    if (rc == 0)
+        rc = launch_reselect_sb(reinterpret_cast<const uint32_t *>(db + rh->action_off), rh->nvars, sb_old, sb_new, stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+// ---- transport / checkpoint message -------------------------------------------------------------------
+
+size_t omc_transport_meta_bytes(uint32_t nvars) {
+    if (nvars == 0) return 0;
+    return static_cast<size_t>(align_up(sizeof(TransportHeader) + static_cast<uint64_t>(nvars) * sizeof(TransportVar), kTransportAlign));
+}
+
+static bool transport_header_for(const PlanHeader *ph, TransportHeader *th) {
+    const PlanVar *pv = plan_vars(ph);
+    uint64_t payload = 0;
+    for (uint32_t i = 0; i < ph->nvars; ++i)
+        payload += align_up((pv[i].flags & OMC_VAR_QUANTIZED) ? pv[i].total_dwords * 4 : 4 * pv[i].n, 16);
+    std::memset(th, 0, sizeof *th);
+    th->magic = kTransportMagic;
+    th->version = kTransportVersion;
+    th->nvars = ph->nvars;
+    th->nquant = ph->nquant;
+    th->sb_off = omc_transport_meta_bytes(ph->nvars);
+    th->payload_off = align_up(th->sb_off + 8ull * ph->nvars, kTransportAlign);
+    th->payload_bytes = payload;
+    th->total_bytes = th->payload_off + payload;
+    th->aux_elems = ph->aux_elems;
+    return true;
+}
+
+uint64_t omc_transport_bytes(const void *plan_host) {
+    const PlanHeader *ph = plan_check(plan_host);
+    if (!ph) return 0;
+    TransportHeader th;
+    transport_header_for(ph, &th);
+    return th.total_bytes;
+}
+
+omc_status omc_transport_pack(const void *plan_host, const void *plan_dev, const void *arena, size_t arena_bytes,
+                              const float *sb_table, void *msg_dev, size_t msg_bytes, void *stream) {
+    if (!plan_host || !plan_dev || !arena || !sb_table || !msg_dev) return OMC_ERR_NULL;
+    const PlanHeader *ph = plan_check(plan_host);
+    if (!ph) return OMC_ERR_PLAN;
+    if (arena_bytes < ph->arena_bytes) return OMC_ERR_SIZE;
+    TransportHeader th;
+    transport_header_for(ph, &th);
+    if (msg_bytes < th.total_bytes) return OMC_ERR_SIZE;
+    if (!aligned16(plan_dev) || !aligned16(arena) || !aligned16(msg_dev) || (reinterpret_cast<uintptr_t>(sb_table) & 7u))
+        return OMC_ERR_ALIGN;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(arena), m0 = reinterpret_cast<uintptr_t>(msg_dev);
+    if (a0 < m0 + th.total_bytes && m0 < a0 + ph->arena_bytes) return OMC_ERR_SIZE;            // message overlaps the arena
+    const int rc = launch_transport_pack(ph, plan_dev, arena, sb_table, msg_dev, th, stream);
+    return rc == 0 ? OMC_OK : OMC_ERR_DEVICE;
+}
+
+omc_status omc_transport_open(const void *msg_prefix_host, size_t prefix_bytes, uint64_t msg_bytes, omc_var *vars_out,
+                              uint32_t vars_cap, uint32_t *nvars_out, uint64_t *sb_offset, uint64_t *arena_offset,
+                              uint64_t *arena_bytes, uint64_t *aux_elems) {
+    if (!msg_prefix_host || !nvars_out) return OMC_ERR_NULL;
+    const TransportHeader *th = transport_check(msg_prefix_host, prefix_bytes, msg_bytes);
+    if (!th) return OMC_ERR_PLAN;
+    *nvars_out = th->nvars;
+    if (sb_offset) *sb_offset = th->sb_off;
+    if (arena_offset) *arena_offset = th->payload_off;
+    if (arena_bytes) *arena_bytes = th->payload_bytes;
+    if (aux_elems) *aux_elems = th->aux_elems;
+    if (!vars_out) return OMC_OK;                           // size query
+    if (prefix_bytes < th->sb_off || vars_cap < th->nvars) return OMC_ERR_SIZE;
+    const TransportVar *tv = reinterpret_cast<const TransportVar *>(static_cast<const uint8_t *>(msg_prefix_host) + sizeof(TransportHeader));
+    uint64_t sum = 0, next = 0;
+    uint32_t nq = 0;
+    for (uint32_t i = 0; i < th->nvars; ++i) {
+        sum += transport_var_hash(i, tv[i]);
+        omc_var v{};
+        v.data_offset = tv[i].payload_offset;
+        v.aux_offset = tv[i].aux_offset;
+        v.n = tv[i].n;
+        v.fmt.exp_bits = tv[i].exp_bits;
+        v.fmt.man_bits = tv[i].man_bits;
+        v.fmt.exp_bias = tv[i].exp_bias;
+        v.flags = tv[i].flags;
+        if (v.flags & ~(OMC_VAR_QUANTIZED | OMC_VAR_NO_PVT)) return OMC_ERR_PLAN;
+        uint64_t bytes;
+        if (v.flags & OMC_VAR_QUANTIZED) {
+            if (!format_ok(v.fmt)) return OMC_ERR_PLAN;
+            ++nq;
+            if (v.n == 0 || v.n > kMaxElems) return OMC_ERR_PLAN;
+            bytes = packed_bytes_u(1u + v.fmt.exp_bits + v.fmt.man_bits, v.n);
+        } else {
+            if (v.n == 0 || v.n > kMaxElems) return OMC_ERR_PLAN;
+            bytes = align_up(4 * v.n, 16);
+        }
+        if (v.data_offset != next) return OMC_ERR_PLAN;         // the payload is dense, in table order
+        next += bytes;
+        vars_out[i] = v;
+    }
+    if (next != th->payload_bytes || nq != th->nquant) return OMC_ERR_PLAN;
+    if (transport_header_hash(*th, sum) != th->checksum) return OMC_ERR_PLAN;
+    return OMC_OK;
 }
 
 }  // extern "C"

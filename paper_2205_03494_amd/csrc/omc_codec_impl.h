@@ -84,9 +84,9 @@ __global__ __launch_bounds__(64, (Tuning<MODE, B>::waves)) void codec_kernel(Cod
         const PlanVar *vars = reinterpret_cast<const PlanVar *>(ca.plan + ca.var_off);
         item = ca.first_item + blockIdx.x;
         const PlanItem it = to_scalar_regs(items[item]);
-        var = it.var;
         chunk = it.chunk;
         pv = to_scalar_regs(vars[it.var]);
+        var = pv.sb_index;
     }
     TileArgs a{};
     codec_tile_args<MODE>(ca, pv, var, a);
@@ -103,8 +103,8 @@ __global__ __launch_bounds__(64) void codec_tail_kernel(CodecArgs ca) {
         const PlanVar *vars = reinterpret_cast<const PlanVar *>(ca.plan + ca.var_off);
         item = ca.first_item + blockIdx.x;
         const PlanItem it = to_scalar_regs(items[item]);
-        var = it.var;
         pv = to_scalar_regs(vars[it.var]);
+        var = pv.sb_index;
     }
     TileArgs a{};
     codec_tile_args<MODE>(ca, pv, var, a);

@@ -64,7 +64,7 @@ static_assert(sizeof(Partial) == 80, "Partial layout");
 
 // ---- plan blob ---------------------------------------------------------------------------
 constexpr uint32_t kPlanMagic = 0x434d4f50u;  // "POMC"
-constexpr uint32_t kPlanVersion = 5;
+constexpr uint32_t kPlanVersion = 6;
 
 struct PlanHeader {
     uint32_t magic, version;
@@ -85,7 +85,10 @@ struct PlanVar {
     uint32_t nitems;         // number of those (0 when n < 2048)
     uint32_t tail_item;      // index of the ragged-tail item / partial, kNoItem if n % 2048 == 0
     FmtParams fp;
+    uint32_t sb_index;       // entry of the (s, b) table that belongs to this variable (its own index in a plan
+                             // built from a caller's table; the index in the original set for derived plans)
 };
+static_assert(sizeof(PlanVar) == 112, "PlanVar layout");
 
 struct PlanItem {
     uint32_t var;
@@ -134,6 +137,77 @@ struct AggSrc {              // one per (variable, client), variable-major
 // groups reuse PlanGroup: kGroupFull (bits) = full tiles of variables quantized somewhere,
 // kGroupTail = their ragged tails, kGroupFp32 = variables that are fp32 at every client
 
+// ---- reselection blob (Sec. 2.5: the set of quantized variables changes from round to round) ----
+// Two derived plans over (old arena -> new arena): one whose "values" are the old arena (variables that
+// become quantized are compressed from there, unchanged variables are copied as runs of floats), one
+// whose "output" is the new arena (variables that become fp32 are decompressed into it).
+constexpr uint32_t kReselectMagic = 0x53524d4fu;  // "OMRS"
+constexpr uint32_t kReselectVersion = 1;
+enum ReselectAction : uint32_t { kRsCopyQuantized = 0, kRsCopyFp32 = 1, kRsToQuantized = 2, kRsToFp32 = 3 };
+struct ReselectHeader {
+    uint32_t magic, version;
+    uint32_t nvars, pad;
+    uint64_t total_bytes;
+    uint64_t action_off;                    // nvars x uint32 ReselectAction
+    uint64_t plan_c_off, plan_c_bytes;      // derived plan run through the compress-set kernels (0: none)
+    uint64_t plan_d_off, plan_d_bytes;      // derived plan run through the decompress-set kernels (0: none)
+    uint64_t arena_old_bytes, arena_new_bytes;
+    uint64_t ws_bytes;
+    uint64_t algorithmic_bytes;             // bytes the conversion must move
+    uint64_t checksum;                      // over everything after the header
+};
+
+// ---- transport message (Sec. 1: parameters are kept and transported in compressed form) ----------
+// [TransportHeader | nvars x TransportVar | pad to 256 | (s, b) table: nvars x 2 floats | pad to 256 | payload]
+// The payload holds every variable's packed stream or fp32 values back to back at 16-byte aligned
+// offsets, so the message body is itself an arena + (s, b) table for the plan built from its table.
+constexpr uint32_t kTransportMagic = 0x54584d4fu;  // "OMXT"
+constexpr uint32_t kTransportVersion = 1;
+struct TransportHeader {
+    uint32_t magic, version;
+    uint32_t nvars, nquant;
+    uint64_t total_bytes;                   // whole message
+    uint64_t sb_off, payload_off, payload_bytes;
+    uint64_t aux_elems;
+    uint64_t checksum;                      // over the header fields above and the variable table
+};
+static_assert(sizeof(TransportHeader) == 64, "TransportHeader layout");
+struct TransportVar {
+    uint64_t payload_offset;                // bytes from payload_off, multiple of 16
+    uint64_t aux_offset;
+    uint64_t n;
+    uint8_t exp_bits, man_bits;
+    int16_t exp_bias;                       // resolved bias
+    uint32_t flags;                         // OMC_VAR_*
+};
+static_assert(sizeof(TransportVar) == 32, "TransportVar layout");
+__host__ __device__ inline uint64_t transport_mix(uint64_t h, uint64_t w) {
+    h = (h ^ w) * 0x100000001b3ull;
+    return (h << 29) | (h >> 35);
+}
+// order-independent part of the checksum: one term per variable, summed (wrapping)
+__host__ __device__ inline uint64_t transport_var_hash(uint32_t index, const TransportVar &v) {
+    uint64_t h = 0x9e3779b97f4a7c15ull + index;
+    h = transport_mix(h, v.payload_offset);
+    h = transport_mix(h, v.aux_offset);
+    h = transport_mix(h, v.n);
+    h = transport_mix(h, static_cast<uint64_t>(v.exp_bits) | (static_cast<uint64_t>(v.man_bits) << 8) |
+                             (static_cast<uint64_t>(static_cast<uint16_t>(v.exp_bias)) << 16) |
+                             (static_cast<uint64_t>(v.flags) << 32));
+    return h;
+}
+__host__ __device__ inline uint64_t transport_header_hash(const TransportHeader &h, uint64_t var_sum) {
+    uint64_t x = 0xc2b2ae3d27d4eb4full;
+    x = transport_mix(x, static_cast<uint64_t>(h.nvars) | (static_cast<uint64_t>(h.nquant) << 32));
+    x = transport_mix(x, h.total_bytes);
+    x = transport_mix(x, h.sb_off);
+    x = transport_mix(x, h.payload_off);
+    x = transport_mix(x, h.payload_bytes);
+    x = transport_mix(x, h.aux_elems);
+    return transport_mix(x, var_sum);
+}
+constexpr uint64_t kTransportAlign = 256;
+
 // ---- host helpers (omc_host.cpp) -----------------------------------------------------------
 bool make_fmt_params(omc_format f, FmtParams *out);
 const PlanHeader *plan_check(const void *plan_host);
@@ -160,6 +234,9 @@ int launch_decompress_set(const void *arena, const PlanHeader *ph, const void *p
 int launch_step(void *arena, const PlanHeader *ph, const void *plan_dev, float *sb_table,
                 const float *grads, float *state0, float *state1, const omc_opt &opt, Partial *ws,
                 void *stream, void *const *events);
+int launch_reselect_sb(const uint32_t *actions_dev, uint32_t nvars, const float *sb_old, float *sb_new, void *stream);
+int launch_transport_pack(const PlanHeader *ph, const void *plan_dev, const void *arena, const float *sb_table,
+                          void *msg_dev, const TransportHeader &th, void *stream);
 struct DwConfig {
     uint32_t rows;     // weight rows per tile: 256 or 128
     uint32_t nsplit;   // workgroups per tile along the contraction

@@ -36,8 +36,8 @@ __global__ __launch_bounds__(64) void step_tail_kernel(StepArgs sa) {
     a.st0 = sa.st0 ? sa.st0 + pv.aux_offset : nullptr;
     a.st1 = sa.st1 ? sa.st1 + pv.aux_offset : nullptr;
     a.n = pv.n;
-    a.s = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var)]);
-    a.b = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var) + 1]);
+    a.s = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(pv.sb_index)]);
+    a.b = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(pv.sb_index) + 1]);
     const FmtParams fp = pv.fp;
     do_tail<MODE, WIDE>(a, fp, sa.oc, sa.ws + item);
 }

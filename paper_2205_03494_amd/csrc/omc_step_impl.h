@@ -140,8 +140,8 @@ __global__ __launch_bounds__(64, (VARIANT == 3 ? OMC_TUNE_WAVES_FP6 : Tuning<MOD
     a.st0 = sa.st0 ? sa.st0 + pv.aux_offset : nullptr;
     a.st1 = sa.st1 ? sa.st1 + pv.aux_offset : nullptr;
     a.n = pv.n;
-    a.s = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var)]);
-    a.b = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(it.var) + 1]);
+    a.s = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(pv.sb_index)]);
+    a.b = to_scalar_regs(sa.sb_table[2 * static_cast<uint64_t>(pv.sb_index) + 1]);
     const FmtParams fp = pv.fp;
     do_chunk<B, MODE, VARIANT, KEEP>(a, fp, sa.oc, it.chunk, lds, sa.ws + item);
 }

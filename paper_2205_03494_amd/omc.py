@@ -82,6 +82,16 @@ _step_ev = _sig("omc_step_update_recompress_events", C.c_int, _vp, C.c_size_t, _
 _compress_set = _sig("omc_compress_set", C.c_int, _vp, C.c_uint64, _vp, _vp, _vp, C.c_size_t, _vp, _vp, C.c_size_t, _vp)
 _decompress_set = _sig("omc_decompress_set", C.c_int, _vp, C.c_size_t, _vp, _vp, _vp, _vp, C.c_uint64, _vp)
 _plan_transport = _sig("omc_plan_transport_bytes", C.c_uint64, _vp)
+_rs_bytes = _sig("omc_reselect_plan_bytes", C.c_size_t, _vp, _vp)
+_rs_build = _sig("omc_reselect_plan_build", C.c_int, _vp, _vp, _vp, C.c_size_t)
+_rs_ws = _sig("omc_reselect_workspace_bytes", C.c_size_t, _vp)
+_rs_alg = _sig("omc_reselect_algorithmic_bytes", C.c_uint64, _vp)
+_reselect = _sig("omc_reselect", C.c_int, _vp, _vp, _vp, C.c_size_t, _vp, _vp, C.c_size_t, _vp, _vp, C.c_size_t, _vp)
+_tr_meta = _sig("omc_transport_meta_bytes", C.c_size_t, C.c_uint32)
+_tr_bytes = _sig("omc_transport_bytes", C.c_uint64, _vp)
+_tr_pack = _sig("omc_transport_pack", C.c_int, _vp, _vp, _vp, C.c_size_t, _vp, _vp, C.c_size_t, _vp)
+_tr_open = _sig("omc_transport_open", C.c_int, _vp, C.c_size_t, C.c_uint64, _vp, C.c_uint32, C.POINTER(C.c_uint32),
+                C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64))
 _agg_bytes = _sig("omc_aggregate_plan_bytes", C.c_size_t, _vp, C.c_uint32)
 _agg_build = _sig("omc_aggregate_plan_build", C.c_int, _vp, C.c_uint32, _vp, C.c_size_t)
 _agg_mean = _sig("omc_aggregate_mean", C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.c_uint64, _vp)
@@ -100,7 +110,10 @@ EXPORTED = ["omc_status_string", "omc_format_validate", "omc_format_bits", "omc_
             "omc_plan_bytes", "omc_plan_build", "omc_plan_workspace_bytes", "omc_workspace_bytes", "omc_plan_arena_bytes",
             "omc_plan_aux_elems", "omc_plan_launches", "omc_step_update_recompress",
             "omc_step_update_recompress_events", "omc_compress_set", "omc_decompress_set",
-            "omc_plan_transport_bytes", "omc_aggregate_plan_bytes", "omc_aggregate_plan_build",
+            "omc_plan_transport_bytes", "omc_reselect_plan_bytes", "omc_reselect_plan_build",
+            "omc_reselect_workspace_bytes", "omc_reselect_algorithmic_bytes", "omc_reselect",
+            "omc_transport_meta_bytes", "omc_transport_bytes", "omc_transport_pack", "omc_transport_open",
+            "omc_aggregate_plan_bytes", "omc_aggregate_plan_build",
             "omc_aggregate_mean", "omc_dequant_gemm_workspace_bytes",
             "omc_dequant_gemm", "omc_dequant_gemm_dx", "omc_dw_update_workspace_bytes",
             "omc_dw_update_recompress"]
@@ -261,6 +274,65 @@ def omc_decompress_set(arena: torch.Tensor, plan: Plan, sb_table: torch.Tensor, 
     _check(_decompress_set(_ptr(arena), arena.numel() * arena.element_size(), plan.host.ctypes.data,
                            _ptr(plan.dev), _ptr(sb_table), _ptr(out), out.numel(), _stream(stream)),
            "omc_decompress_set")
+
+
+# ------------------------------------------------------------------ a new round's quantized subset
+@dataclass
+class ReselectPlan:
+    host: np.ndarray
+    dev: torch.Tensor
+
+    @property
+    def workspace_bytes(self) -> int:
+        return _rs_ws(self.host.ctypes.data)
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        return _rs_alg(self.host.ctypes.data)
+
+
+def omc_reselect_plan_build(plan_old: Plan, plan_new: Plan) -> ReselectPlan:
+    size = _rs_bytes(plan_old.host.ctypes.data, plan_new.host.ctypes.data)
+    buf = np.zeros(max(size, 16), dtype=np.uint8)
+    _check(_rs_build(plan_old.host.ctypes.data, plan_new.host.ctypes.data, buf.ctypes.data, size),
+           "omc_reselect_plan_build")
+    return ReselectPlan(buf, torch.from_numpy(buf).cuda())
+
+
+def omc_reselect(rs: ReselectPlan, arena_old: torch.Tensor, sb_old: torch.Tensor, arena_new: torch.Tensor,
+                 sb_new: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    _check(_reselect(rs.host.ctypes.data, _ptr(rs.dev), _ptr(arena_old), arena_old.numel() * arena_old.element_size(),
+                     _ptr(sb_old), _ptr(arena_new), arena_new.numel() * arena_new.element_size(), _ptr(sb_new),
+                     _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "omc_reselect")
+
+
+# ------------------------------------------------------------------ transport / checkpoint message
+def omc_transport_meta_bytes(nvars: int) -> int:
+    return _tr_meta(nvars)
+
+
+def omc_transport_bytes(plan: Plan) -> int:
+    return _tr_bytes(plan.host.ctypes.data)
+
+
+def omc_transport_pack(plan: Plan, arena: torch.Tensor, sb_table: torch.Tensor, msg: torch.Tensor, stream=None) -> None:
+    _check(_tr_pack(plan.host.ctypes.data, _ptr(plan.dev), _ptr(arena), arena.numel() * arena.element_size(),
+                    _ptr(sb_table), _ptr(msg), msg.numel() * msg.element_size(), _stream(stream)), "omc_transport_pack")
+
+
+def omc_transport_open(prefix: np.ndarray, msg_bytes: int):
+    """prefix: the first bytes of a message in host memory (uint8).  Returns (omc_var table or None when the
+    prefix is shorter than header + table, nvars, sb_offset, arena_offset, arena_bytes, aux_elems)."""
+    prefix = np.ascontiguousarray(prefix, dtype=np.uint8)
+    nv, so, ao, ab, ae = C.c_uint32(), C.c_uint64(), C.c_uint64(), C.c_uint64(), C.c_uint64()
+    _check(_tr_open(prefix.ctypes.data, prefix.size, msg_bytes, None, 0, C.byref(nv), C.byref(so), C.byref(ao),
+                    C.byref(ab), C.byref(ae)), "omc_transport_open")
+    table = None
+    if prefix.size >= _tr_meta(nv.value):
+        table = (omc_var * nv.value)()
+        _check(_tr_open(prefix.ctypes.data, prefix.size, msg_bytes, C.cast(table, _vp), nv.value, C.byref(nv),
+                        C.byref(so), C.byref(ao), C.byref(ab), C.byref(ae)), "omc_transport_open")
+    return table, nv.value, so.value, ao.value, ab.value, ae.value
 
 
 class HipEvents:

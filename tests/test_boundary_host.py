@@ -289,3 +289,108 @@ def test_dw_update_rejects_bad_arguments():
     assert call(opt=omc.opt(omc.OMC_ADAM, 0.1), st0=A) == 6
     assert call(codes=A + 4) == 4
     assert call(wsb=16) == 5
+
+
+# ---- transport message: the wire format written out by hand --------------------------------------------------
+M64 = (1 << 64) - 1
+
+
+def _mix(h, w):
+    h = ((h ^ w) * 0x100000001b3) & M64
+    return ((h << 29) | (h >> 35)) & M64
+
+
+def _message_prefix(entries, aux_elems):
+    """entries: (n, aux_offset, E, M, bias, flags) per variable.  Header (64 bytes: magic 'OMXT', version, nvars,
+    nquant, total bytes, offsets of the (s, b) table and the payload, payload bytes, aux elements, checksum) and one
+    32-byte record per variable (payload offset, aux offset, n, E, M, bias, flags); sections padded to 256 bytes."""
+    import struct
+    nvars = len(entries)
+    recs, off, var_sum, nq = b"", 0, 0, 0
+    for i, (n, aux, E, M, bias, flags) in enumerate(entries):
+        q = flags & 1
+        nq += q
+        size = ((n * (1 + E + M) + 7) // 8 + 15) // 16 * 16 if q else (4 * n + 15) // 16 * 16
+        recs += struct.pack("<QQQBBhI", off, aux, n, E, M, bias, flags)
+        h = (0x9e3779b97f4a7c15 + i) & M64
+        for w in (off, aux, n, E | (M << 8) | ((bias & 0xffff) << 16) | (flags << 32)):
+            h = _mix(h, w)
+        var_sum = (var_sum + h) & M64
+        off += size
+    sb_off = (64 + 32 * nvars + 255) // 256 * 256
+    payload_off = (sb_off + 8 * nvars + 255) // 256 * 256
+    total = payload_off + off
+    x = 0xc2b2ae3d27d4eb4f
+    for w in (nvars | (nq << 32), total, sb_off, payload_off, off, aux_elems, var_sum):
+        x = _mix(x, w)
+    head = struct.pack("<IIIIQQQQQQ", 0x54584d4f, 1, nvars, nq, total, sb_off, payload_off, off, aux_elems, x)
+    buf = head + recs
+    return np.frombuffer(buf + b"\0" * (sb_off - len(buf)), np.uint8).copy(), total, sb_off, payload_off, off
+
+
+def test_transport_message_format_as_documented():
+    entries = [(5000, 0, 3, 7, 3, 1), (100, 5000, 8, 23, 127, 0), (2048, 5100, 4, 3, 7, 3), (7, 7148, 8, 23, 127, 0)]
+    prefix, total, sb_off, payload_off, payload = _message_prefix(entries, 7156)
+    assert omc.omc_transport_meta_bytes(len(entries)) == prefix.size == 256
+    table, nvars, so, ao, ab, ae = omc.omc_transport_open(prefix, total)
+    assert (nvars, so, ao, ab, ae) == (4, sb_off, payload_off, payload, 7156)
+    assert [int(t.n) for t in table] == [5000, 100, 2048, 7]
+    assert [int(t.data_offset) for t in table] == [0, 6880, 7280, 9328]
+    assert [int(t.flags) for t in table] == [1, 0, 3, 0]
+    assert (table[0].fmt.exp_bits, table[0].fmt.man_bits, table[0].fmt.exp_bias) == (3, 7, 3)
+    # the table is a valid variable table: a plan over the payload can be built from it
+    size = omc._plan_bytes(C.cast(table, C.c_void_p), nvars)
+    assert size > 0
+    buf = np.zeros(size, np.uint8)
+    assert omc._plan_build(C.cast(table, C.c_void_p), nvars, buf.ctypes.data, size) == 0
+    assert omc._plan_arena(buf.ctypes.data) <= payload
+    # and the size of a message that the library writes for this set follows the same arithmetic
+    assert omc._tr_bytes(buf.ctypes.data) == total
+    # damaged prefixes are refused
+    for pos in (0, 4, 8, 12, 16, 24, 32, 40, 48, 56, 64, 72, 80, 88, 89, 90, 92, 64 + 32 * 3 + 5):
+        bad = prefix.copy()
+        bad[pos] ^= 2
+        with pytest.raises(omc.OmcError):
+            omc.omc_transport_open(bad, total)
+    with pytest.raises(omc.OmcError):
+        omc.omc_transport_open(prefix, total - 1)
+    with pytest.raises(omc.OmcError):
+        omc.omc_transport_open(prefix[:32], total)
+
+
+def test_reselect_plan_and_transport_reject_bad_arguments():
+    f = omc.fmt(3, 7)
+    A = 0x100000
+    old = [dict(data_offset=0, aux_offset=0, n=5000, fmt=f, quantized=True), dict(data_offset=6880, aux_offset=5000, n=100, quantized=False)]
+    new = [dict(data_offset=0, aux_offset=0, n=5000, quantized=False), dict(data_offset=20000, aux_offset=5000, n=100, fmt=f, quantized=True)]
+    _, st, po = _plan_status(old)
+    _, st2, pn = _plan_status(new)
+    assert st == 0 and st2 == 0
+    size = omc._rs_bytes(po.ctypes.data, pn.ctypes.data)
+    assert size > 0
+    rs = np.zeros(size, np.uint8)
+    assert omc._rs_build(po.ctypes.data, pn.ctypes.data, rs.ctypes.data, size - 16) == 3
+    assert omc._rs_build(po.ctypes.data, pn.ctypes.data, rs.ctypes.data, size) == 0
+    assert omc._rs_ws(rs.ctypes.data) == 80                 # one partial: the ragged tail of the newly quantized variable
+    assert omc._rs_alg(rs.ctypes.data) == (4 * 5000 + 6880 + 8) + (4 * 100 + 144 + 8)
+    call = lambda **kw: omc._reselect(*[dict(dict(rs=rs.ctypes.data, rd=A, ao=A, aob=1 << 16, so=A, an=0x200000, anb=1 << 16,
+                                                  sn=A + 4096, ws=A, wsb=4096), **kw)[k]
+                                        for k in ("rs", "rd", "ao", "aob", "so", "an", "anb", "sn", "ws", "wsb")], None)
+    assert call(ao=None) == 1
+    assert call(aob=16) == 3 and call(anb=16) == 3
+    assert call(an=A + 256) == 3                          # the arenas overlap
+    assert call(sn=A) == 3                                # one (s, b) table for both
+    assert call(wsb=8) == 5
+    assert call(ao=A + 8) == 4
+    bad = rs.copy(); bad[-20] ^= 1
+    assert call(rs=bad.ctypes.data) == 8
+    assert omc._rs_ws(bad.ctypes.data) == 0
+    # transport_pack
+    pk = lambda **kw: omc._tr_pack(*[dict(dict(ph=po.ctypes.data, pd=A, ar=A, ab=1 << 16, sb=A, msg=0x200000, mb=1 << 20), **kw)[k]
+                                     for k in ("ph", "pd", "ar", "ab", "sb", "msg", "mb")], None)
+    assert pk(msg=None) == 1
+    assert pk(mb=100) == 3 and pk(ab=100) == 3
+    assert pk(msg=A + 512) == 3                            # the message overlaps the arena
+    assert pk(msg=0x200008) == 4
+    bad = po.copy(); bad[200] ^= 1
+    assert pk(ph=bad.ctypes.data) == 8
