@@ -13,6 +13,8 @@ struct CodecArgs {
     uint32_t first_item, nitems;
     uint32_t fp32_first, fp32_nitems;   // set calls: copies of fp32 variables appended to the grid
     PlanVar single;
+    uint32_t single_tiles;       // single variable: full tiles per work item
+    uint32_t single_tail;        // single variable: 1 = one more workgroup of the full-tile launch serves the ragged tail
     const float *sb_in;          // decompress: (s, b) table / pair, nullptr = (1, 0)
     const float *vin;            // compress: fp32 values, indexed by aux_offset
     float *vout;                 // decompress: fp32 output, indexed by aux_offset
@@ -79,6 +81,17 @@ __global__ __launch_bounds__(64, (Tuning<MODE, B>::waves)) void codec_kernel(Cod
     }
     uint32_t item = blockIdx.x, var = 0, chunk = blockIdx.x;
     PlanVar pv = ca.single;
+    uint32_t tiles = tiles_per_chunk(B);
+    if (!ca.plan) {
+        tiles = ca.single_tiles;
+        if (ca.single_tail && blockIdx.x == ca.nitems - 1) {       // the last workgroup: the variable's ragged tail
+            TileArgs a{};
+            codec_tile_args<MODE>(ca, pv, 0, a);
+            OptConst oc{};
+            do_tail<MODE, variant_wide(VARIANT)>(a, pv.fp, oc, ca.ws + item);   // (a format's rounding kind follows its variant)
+            return;
+        }
+    }
     if (ca.plan) {
         const PlanItem *items = reinterpret_cast<const PlanItem *>(ca.plan + ca.item_off);
         const PlanVar *vars = reinterpret_cast<const PlanVar *>(ca.plan + ca.var_off);
@@ -91,7 +104,7 @@ __global__ __launch_bounds__(64, (Tuning<MODE, B>::waves)) void codec_kernel(Cod
     TileArgs a{};
     codec_tile_args<MODE>(ca, pv, var, a);
     OptConst oc{};
-    do_chunk<B, MODE, VARIANT>(a, pv.fp, oc, chunk, lds, ca.ws + item);
+    do_chunk<B, MODE, VARIANT>(a, pv.fp, oc, chunk, lds, ca.ws + item, tiles);
 }
 
 template <int MODE, bool WIDE>

@@ -54,37 +54,44 @@ static int launch_tail(bool wide, uint32_t grid, const CodecArgs &ca, hipStream_
     return static_cast<int>(hipGetLastError());
 }
 
+// Full tiles per work item of a single variable: the plan's figure, doubled until at most kMaxSingleItems work
+// items are left (a 64 M-element variable: 2048 items of 16 tiles), so that all of them are resident at once and the
+// finalize adds a few thousand partial sums at most.  Depends on the size alone.
+uint32_t single_tiles_per_item(uint32_t bits, uint64_t n) {
+#ifndef OMC_TUNE_SINGLE_ITEMS
+#define OMC_TUNE_SINGLE_ITEMS 2048
+#endif
+    constexpr uint64_t kMaxSingleItems = OMC_TUNE_SINGLE_ITEMS;
+    const uint64_t full_tiles = n / kTileElems;
+    uint64_t tiles = tiles_per_chunk(bits);
+    if ((full_tiles + tiles - 1) / tiles > kMaxSingleItems) tiles = (full_tiles + kMaxSingleItems - 1) / kMaxSingleItems;
+    return static_cast<uint32_t>(tiles);
+}
+
 int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb, Partial *ws,
                     void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const uint32_t tpc = tiles_per_chunk(va.fp.bits);
-    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + tpc - 1) / tpc);
+    const uint32_t tiles = single_tiles_per_item(va.fp.bits, va.n);
+    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + tiles - 1) / tiles);
     const bool has_tail = (va.n % kTileElems) != 0;
     CodecArgs ca{};
     ca.arena = static_cast<uint8_t *>(codes);
     ca.single.n = va.n;
     ca.single.total_dwords = va.total_dwords;
     ca.single.fp = va.fp;
+    ca.single_tiles = tiles;
+    ca.single_tail = has_tail ? 1u : 0u;
     ca.vin = v;
     ca.ws = ws;
-    ca.nitems = nchunks;
-    if (nchunks > 0) {
-        const int rc = launch_full(va.fp.bits, va.fp.variant, nchunks, ca, st);
-        if (rc != 0) return rc;
-    }
-    if (has_tail) {
-        ca.first_item = nchunks;                       // the tail's partial slot
-        const int rc = launch_tail(va.fp.wide != 0, 1, ca, st);
-        if (rc != 0) return rc;
-    }
+    ca.nitems = nchunks + (has_tail ? 1u : 0u);            // the ragged tail is the launch's last workgroup
+    int rc = launch_full(va.fp.bits, va.fp.variant, ca.nitems, ca, st);
+    if (rc != 0) return rc;
     // the width of the reduction depends on the size alone, so results do not depend on the run
     const int exact = variant_exact(va.fp.variant) ? 1 : 0;
     if (nchunks <= 256)
         finalize_single_kernel<1><<<dim3(1), dim3(64), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
-    else if (nchunks <= 2048)
-        finalize_single_kernel<4><<<dim3(1), dim3(256), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
     else
-        finalize_single_kernel<16><<<dim3(1), dim3(1024), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
+        finalize_single_kernel<4><<<dim3(1), dim3(256), 0, st>>>(ws, nchunks, has_tail ? 1 : 0, va.n, use_pvt, exact, sb);
     return static_cast<int>(hipGetLastError());
 }
 

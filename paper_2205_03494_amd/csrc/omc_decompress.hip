@@ -19,25 +19,20 @@ static int launch_full(uint32_t bits, uint32_t grid, const CodecArgs &ca, hipStr
 
 int launch_decompress(const void *codes, const VarArgs &va, const float *sb, float *out, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const uint32_t tpc = tiles_per_chunk(va.fp.bits);
-    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + tpc - 1) / tpc);
+    const uint32_t tiles = single_tiles_per_item(va.fp.bits, va.n);
+    const uint32_t nchunks = static_cast<uint32_t>((va.n / kTileElems + tiles - 1) / tiles);
+    const bool has_tail = (va.n % kTileElems) != 0;
     CodecArgs ca{};
     ca.arena = static_cast<uint8_t *>(const_cast<void *>(codes));   // never written in this mode
     ca.single.n = va.n;
     ca.single.total_dwords = va.total_dwords;
     ca.single.fp = va.fp;
+    ca.single_tiles = tiles;
+    ca.single_tail = has_tail ? 1u : 0u;
     ca.sb_in = sb;
     ca.vout = out;
-    ca.nitems = nchunks;
-    if (nchunks > 0) {
-        const int rc = launch_full(va.fp.bits, nchunks, ca, st);
-        if (rc != 0) return rc;
-    }
-    if (va.n % kTileElems) {
-        codec_tail_kernel<kDecompress, false><<<dim3(1), dim3(64), 0, st>>>(ca);
-        return static_cast<int>(hipGetLastError());
-    }
-    return 0;
+    ca.nitems = nchunks + (has_tail ? 1u : 0u);            // the ragged tail is the launch's last workgroup
+    return launch_full(va.fp.bits, ca.nitems, ca, st);
 }
 
 int launch_decompress_set(const void *arena, const PlanHeader *ph, const void *plan_dev, const float *sb_table,

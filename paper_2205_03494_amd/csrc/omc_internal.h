@@ -220,6 +220,7 @@ struct VarArgs {
     FmtParams fp;
 };
 
+uint32_t single_tiles_per_item(uint32_t bits, uint64_t n);
 int launch_compress(const float *v, const VarArgs &va, int use_pvt, void *codes, float *sb,
                     Partial *ws, void *stream);
 // Size of the library's own device scratch array (omc_compress_noalloc) and the address of the current

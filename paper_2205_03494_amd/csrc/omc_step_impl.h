@@ -10,8 +10,8 @@ namespace omc {
 #ifndef OMC_TUNE_OCP_MAXMODE
 #define OMC_TUNE_OCP_MAXMODE 2      // kStepSgd: the hardware FP8 variant serves plain SGD only
 #endif
-#ifndef OMC_TUNE_LDS_PAD_DWORDS
-#define OMC_TUNE_LDS_PAD_DWORDS 2900   // 20 KB per workgroup: 8 workgroups per compute unit
+#ifndef OMC_TUNE_SGD8_MAX_WAVES
+#define OMC_TUNE_SGD8_MAX_WAVES 2      // waves per SIMD of the 8-bit SGD kernel with hardware conversion (0: no cap)
 #endif
 #ifndef OMC_TUNE_FP6_MAXMODE
 #define OMC_TUNE_FP6_MAXMODE 2      // kStepSgd: the hardware 6-bit variant serves plain SGD only
@@ -116,14 +116,24 @@ __device__ __forceinline__ void do_fp32_item(const StepArgs &sa, uint32_t item) 
 
 // KEEP: the launch's work items keep their packed codes cached from step to step; without it the code
 // loads and stores carry the non-temporal hint.
+// Occupancy: the register budget follows Tuning<>::waves (waves per SIMD the compiler must make room for).  The
+// 8-bit SGD kernel with hardware conversion needs few registers and would run four waves per SIMD; it is held
+// at two (8 workgroups per compute unit), because fewer streams open at once suit the memory system better when
+// the traffic really comes from HBM (codes streamed, caches flushed between steps: 120 -> 113 us; caps of 10
+// workgroups measure like 8, 6 and 4 are slower).  The kernels with more arithmetic per element lose 7-10 %
+// under the same cap and are left alone.
+template <int B, int MODE, int VARIANT>
+struct StepOccupancy {
+    static constexpr int min_waves = (VARIANT == 3) ? OMC_TUNE_WAVES_FP6 : Tuning<MODE, B>::waves;
+    static constexpr bool capped = (VARIANT == 2 && MODE == kStepSgd && OMC_TUNE_SGD8_MAX_WAVES > 0);
+    static constexpr int lo = capped ? (min_waves < OMC_TUNE_SGD8_MAX_WAVES ? min_waves : OMC_TUNE_SGD8_MAX_WAVES) : min_waves;
+    static constexpr int hi = capped ? OMC_TUNE_SGD8_MAX_WAVES : 8;
+};
 template <int B, int MODE, int VARIANT, bool KEEP>
-__global__ __launch_bounds__(64, (VARIANT == 3 ? OMC_TUNE_WAVES_FP6 : Tuning<MODE, B>::waves)) void step_kernel(StepArgs sa) {
-    // The 8-bit SGD kernel with hardware conversion needs few registers and would run 16 workgroups per compute
-    // unit; capped at 8 through its LDS footprint it keeps fewer streams open at once, which the memory system
-    // rewards (warm 105.6 -> 105.1 us; with the codes streamed from HBM 120 -> 113 us).  The kernels with more
-    // arithmetic per element lose 7-10 % under the same cap and are left alone.
-    constexpr int kLdsPad = (VARIANT == 2 && MODE == kStepSgd) ? OMC_TUNE_LDS_PAD_DWORDS : 0;
-    __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords + kLdsPad];
+__global__ __attribute__((amdgpu_flat_work_group_size(64, 64)))
+__attribute__((amdgpu_waves_per_eu(StepOccupancy<B, MODE, VARIANT>::lo, StepOccupancy<B, MODE, VARIANT>::hi)))
+void step_kernel(StepArgs sa) {
+    __shared__ __attribute__((aligned(16))) uint32_t lds[kLdsDwords];
     if (blockIdx.x >= sa.nitems) {                       // the workgroups past the end serve fp32 variables
         do_fp32_item<MODE>(sa, sa.fp32_first + (blockIdx.x - sa.nitems));
         return;

@@ -854,18 +854,20 @@ __device__ __forceinline__ void finish_tile(const TileArgs &a, const FmtParams &
     store_code_pieces<B, StreamHints<MODE, KEEP>::nt_codes>(a.codes + (e0 >> 5) * B, lane, cout);
 }
 
-// One work item of the full-tile kernels: tiles [chunk*tiles_per_chunk(B), ...) of one variable, as far
-// as full tiles go, reduced into one Partial.  The caller guarantees at least one full tile.
+// One work item of the full-tile kernels: tiles [chunk * tiles, (chunk + 1) * tiles) of one variable, as far
+// as full tiles go, reduced into one Partial.  The caller guarantees at least one full tile.  `tiles` is
+// tiles_per_chunk(B) for the work items of a plan; the single-variable calls pass a larger number for huge
+// variables, so that the finalize has at most a few thousand partial sums to add.
 template <int B, int MODE, int VARIANT, bool KEEP = true>
 __device__ __forceinline__ void do_chunk(const TileArgs &a, const FmtParams &fp, const OptConst &oc,
-                                         uint32_t chunk, uint32_t *lds, Partial *partial_out) {
+                                         uint32_t chunk, uint32_t *lds, Partial *partial_out,
+                                         uint32_t tiles = tiles_per_chunk(B)) {
     const uint32_t lane = threadIdx.x;
     FitAcc acc;
     acc.clear();
-    constexpr uint32_t kTiles = tiles_per_chunk(B);
-    const uint64_t first_tile = static_cast<uint64_t>(chunk) * kTiles;
+    const uint64_t first_tile = static_cast<uint64_t>(chunk) * tiles;
     const uint64_t full_tiles = a.n / kTileElems;
-    const uint32_t ntiles = static_cast<uint32_t>((full_tiles - first_tile < kTiles) ? full_tiles - first_tile : kTiles);
+    const uint32_t ntiles = static_cast<uint32_t>((full_tiles - first_tile < tiles) ? full_tiles - first_tile : tiles);
     const uint64_t begin = first_tile * kTileElems;
     Stage<B, MODE> st;
     issue_loads<B, MODE, KEEP>(a, begin, lane, st);

@@ -69,9 +69,9 @@ __global__ __launch_bounds__(kMetaThreads) void transport_meta_kernel(const uint
     }
 }
 
-// Workgroup (i, y) copies the 16-byte pieces y * 256 + t, + 256 * gridDim.y, ... of variable i from the arena to
+// Workgroup (i, y) copies runs of 1024 16-byte pieces, y, y + gridDim.y, ..., of variable i from the arena to
 // the place the meta kernel gave it (read back from the message's own table).
-constexpr uint32_t kPackSlices = 32;
+constexpr uint32_t kPackSlices = 64;
 __global__ __launch_bounds__(256) void transport_pack_kernel(const uint8_t *__restrict__ plan, uint64_t var_off,
                                                              const uint8_t *__restrict__ arena, uint8_t *__restrict__ msg,
                                                              uint64_t payload_off) {
@@ -85,8 +85,21 @@ __global__ __launch_bounds__(256) void transport_pack_kernel(const uint8_t *__re
     const uint64_t full = bytes / 16;
     const u32x4 *src = reinterpret_cast<const u32x4 *>(arena + pv.data_offset);
     u32x4 *dst = reinterpret_cast<u32x4 *>(msg + payload_off + dst_off);
-    for (uint64_t p = static_cast<uint64_t>(blockIdx.y) * 256 + threadIdx.x; p < full; p += 256ull * gridDim.y)
-        __builtin_nontemporal_store(__builtin_nontemporal_load(src + p), dst + p);
+    // four pieces per thread in flight; a slice's run of 4 * 256 pieces is contiguous
+    constexpr uint32_t kBatch = 4;
+    for (uint64_t p0 = static_cast<uint64_t>(blockIdx.y) * (256 * kBatch); p0 < full; p0 += 256ull * kBatch * gridDim.y) {
+        u32x4 x[kBatch];
+#pragma unroll
+        for (uint32_t u = 0; u < kBatch; ++u) {
+            const uint64_t p = p0 + u * 256 + threadIdx.x;
+            if (p < full) x[u] = __builtin_nontemporal_load(src + p);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < kBatch; ++u) {
+            const uint64_t p = p0 + u * 256 + threadIdx.x;
+            if (p < full) __builtin_nontemporal_store(x[u], dst + p);
+        }
+    }
     if (blockIdx.y == 0 && threadIdx.x == 0 && bytes % 16) {      // an fp32 variable whose size is no multiple of four
         const uint32_t *s = reinterpret_cast<const uint32_t *>(src + full);
         uint32_t *d = reinterpret_cast<uint32_t *>(dst + full);
