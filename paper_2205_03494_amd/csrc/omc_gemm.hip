@@ -399,6 +399,214 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
     }
 }
 
+// ---- S1E4M3 forward kernel ---------------------------------------------------------------------------
+// The forward product on hardware-convertible byte codes (S1E4M3, bias 7, no top code: see the pre-pass) takes a
+// kernel of its own, built on three facts that were measured on this part.  (1) In the 4 x 1 wave layout the 64 rows
+// of A that a wave multiplies belong to it alone, so staging A in LDS buys no reuse and only costs LDS bandwidth (the
+// tile kernel above moves 80 KB through LDS per K step, more than the matrix instructions leave time for): here every
+// lane loads its A fragments (8 consecutive k of its row, 16 bytes) straight from global memory into registers, two K
+// steps ahead in three register sets.  (2) gfx950 converts two FP8 codes into a packed pair of bfloat16 in one
+// instruction (v_cvt_scalef32_pk_bf16_fp8, scale 1), so a thread's 16 codes become 32 bytes of bf16 with eight
+// conversions and no byte shuffles, stored row-major [k][n] as loaded.  (3) The transposing LDS read
+// (ds_read_b64_tr_b16) then delivers the B fragments: within a block of 16 lanes, lane 4 q + e receives element e of
+// the 8-byte chunks that lanes q, q + 4, q + 8, q + 12 point at, so four lanes pointing at four consecutive k rows of
+// the same four columns hand each of 16 lanes one column's four k values.  Rows are 320 bytes apart (16 banks), which
+// keeps the four rows of a read on different banks.  About 30 vector instructions per K step and wave instead of
+// about 100, and 48 KB instead of 80 KB through LDS.  W of step j + 1 is decoded and stored during step j; the
+// fragments of the first half of step j + 1 are read under the second half of step j; one barrier per K step.
+constexpr int kF8RowBytes = kBN * 2 + 64;
+constexpr int kF8WBytes = kBK * kF8RowBytes;               // 10 KB per stage, two stages
+
+__device__ __forceinline__ void dequant_gemm_fp8_body(const uint16_t *__restrict__ A, const uint8_t *__restrict__ codes,
+                                                      const float *__restrict__ sb, float *__restrict__ C, uint32_t N,
+                                                      uint32_t K, uint8_t *sW0, uint8_t *sW1, float *rowsum_lds) {
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    constexpr int BM = 256;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t m0 = blockIdx.x * BM, n0 = blockIdx.y * kBN;
+    const uint32_t nk = K / kBK;                              // >= 2
+    const uint32_t f_row = lane & 31u, f_half = lane >> 5;
+
+    // A: lane (row, half) takes 8 consecutive k of its row per fragment
+    const uint8_t *a_base = reinterpret_cast<const uint8_t *>(A) + static_cast<uint64_t>(m0) * K * 2;
+    uint32_t a_off[2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) a_off[mi] = (64 * wave + 32 * mi + f_row) * K * 2 + f_half * 16;
+    struct ASet {
+        u32x4 f[2][2];                                        // [half of the K step][mi]
+    };
+    auto load_a = [&](uint32_t step, ASet &r) {
+        const uint8_t *p = a_base + step * (kBK * 2);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) r.f[ks][mi] = *reinterpret_cast<const u32x4 *>(p + a_off[mi] + 32 * ks);
+    };
+    // W: thread = (k row, 16 consecutive codes)
+    const uint32_t w_row = tid >> 3, w_piece = tid & 7u;
+    const uint8_t *w_base = codes + n0;
+    const uint32_t w_off = w_row * N + 16 * w_piece;
+    auto load_w = [&](uint32_t step) {
+        return *reinterpret_cast<const u32x4 *>(w_base + static_cast<uint64_t>(step) * kBK * N + w_off);
+    };
+    auto store_w = [&](const u32x4 &c, uint8_t *sW) {
+        uint32_t o[8];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            o[2 * d] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[d], 1.0f, false));
+            o[2 * d + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[d], 1.0f, true));
+        }
+        uint8_t *dst = sW + w_row * kF8RowBytes + w_piece * 32;
+        *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<u32x4 *>(dst + 16) = u32x4{o[4], o[5], o[6], o[7]};
+    };
+    // transposing read: block b = lane >> 4 (b & 1: which 16 of the 32 columns, b >> 1: which 8 of the 16 k),
+    // source lane L = lane & 15: L & 3 = group of four columns, L >> 2 = k row
+    const uint32_t tb = lane >> 4, tL = lane & 15u;
+    const uint32_t fb_base = (8 * (tb >> 1) + (tL >> 2)) * kF8RowBytes + (16 * (tb & 1u) + 4 * (tL & 3u)) * 2;
+    struct BSet {
+        bf16x8 b[4];
+    };
+    auto read_b = [&](const uint8_t *sW, int ks, BSet &f) {
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+            const uint8_t *p = sW + fb_base + (16 * ks) * kF8RowBytes + 64 * ni;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(p + 4 * kF8RowBytes));
+            const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            f.b[ni] = __builtin_bit_cast(bf16x8, both);
+        }
+    };
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+    float rsum[2] = {0.0f, 0.0f};
+    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+    const bool want_rs = sb != nullptr;
+    auto multiply = [&](const ASet &a, int ks, const BSet &f) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a.f[ks][mi]), f.b[ni], acc[mi][ni], 0, 0, 0);
+        if (want_rs) {                                       // row sums of A for the b * rowsum(A) term, on the way
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t x = a.f[ks][mi][i];
+                    rsum[mi] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x), ones, rsum[mi], false);
+                }
+        }
+    };
+
+    ASet a0, a1, a2;
+    u32x4 wq0, wq1;
+    BSet f0, f1;
+    load_a(0, a0); wq0 = load_w(0);
+    load_a(1, a1); wq1 = load_w(1);
+    store_w(wq0, sW0);
+    __syncthreads();
+    read_b(sW0, 0, f0);
+    // one K step J whose step J + 2 still exists: A of step J in Ac, loads of J + 2 into Af / WQ_FAR, W of J + 1 from WQ_NXT
+#define OMC_F8_STEADY(J, Ac, Af, sWc, sWn, WQ_FAR, WQ_NXT) \
+    do {                                                    \
+        read_b(sWc, 1, f1);                                 \
+        load_a((J) + 2, Af);                                \
+        WQ_FAR = load_w((J) + 2);                           \
+        multiply(Ac, 0, f0);                                \
+        store_w(WQ_NXT, sWn);                               \
+        __syncthreads();                                    \
+        read_b(sWn, 0, f0);                                 \
+        multiply(Ac, 1, f1);                                \
+    } while (0)
+    // the same with every part conditional: the last steps
+#define OMC_F8_TAIL(J, Ac, Af, sWc, sWn, WQ_FAR, WQ_NXT)   \
+    if ((J) < nk) {                                         \
+        read_b(sWc, 1, f1);                                 \
+        if ((J) + 2 < nk) {                                 \
+            load_a((J) + 2, Af);                            \
+            WQ_FAR = load_w((J) + 2);                       \
+        }                                                   \
+        multiply(Ac, 0, f0);                                \
+        if ((J) + 1 < nk) {                                 \
+            store_w(WQ_NXT, sWn);                           \
+            __syncthreads();                                \
+            read_b(sWn, 0, f0);                             \
+        }                                                   \
+        multiply(Ac, 1, f1);                                \
+    }
+    // three A sets and two W buffers rotate with a period of six steps, written out so that every index is static
+    uint32_t j = 0;
+    for (; j + 8 <= nk; j += 6) {
+        OMC_F8_STEADY(j + 0, a0, a2, sW0, sW1, wq0, wq1);
+        OMC_F8_STEADY(j + 1, a1, a0, sW1, sW0, wq1, wq0);
+        OMC_F8_STEADY(j + 2, a2, a1, sW0, sW1, wq0, wq1);
+        OMC_F8_STEADY(j + 3, a0, a2, sW1, sW0, wq1, wq0);
+        OMC_F8_STEADY(j + 4, a1, a0, sW0, sW1, wq0, wq1);
+        OMC_F8_STEADY(j + 5, a2, a1, sW1, sW0, wq1, wq0);
+    }
+    OMC_F8_TAIL(j + 0, a0, a2, sW0, sW1, wq0, wq1)
+    OMC_F8_TAIL(j + 1, a1, a0, sW1, sW0, wq1, wq0)
+    OMC_F8_TAIL(j + 2, a2, a1, sW0, sW1, wq0, wq1)
+    OMC_F8_TAIL(j + 3, a0, a2, sW1, sW0, wq1, wq0)
+    OMC_F8_TAIL(j + 4, a1, a0, sW0, sW1, wq0, wq1)
+    OMC_F8_TAIL(j + 5, a2, a1, sW1, sW0, wq1, wq0)
+    OMC_F8_TAIL(j + 6, a0, a2, sW0, sW1, wq0, wq1)
+#undef OMC_F8_STEADY
+#undef OMC_F8_TAIL
+
+    // epilogue: C = s * acc + b * rowsum(A).  A lane's accumulators are one column of each of the four 32-column
+    // blocks: a wave's store instruction writes two rows of 128 contiguous bytes
+    const float s = sb ? sb[0] : 1.0f;
+    const float b = sb ? sb[1] : 0.0f;
+    if (want_rs) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+            float t = rsum[mi];
+            t += __shfl_xor(t, 32);
+            if (f_half == 0) rowsum_lds[64 * wave + 32 * mi + f_row] = t;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const uint32_t trow = 64 * wave + 32 * mi + 8 * (v >> 2) + 4 * f_half + (v & 3);
+            const float add = want_rs ? b * rowsum_lds[trow] : 0.0f;
+            float *crow = C + static_cast<uint64_t>(m0 + trow) * N + n0 + f_row;
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) __builtin_nontemporal_store(s * acc[mi][ni][v] + add, crow + 32 * ni);
+        }
+    }
+}
+
+// S1E4M3 / bias 7, forward, 256-row tiles, K >= 64: the kernel above unless the pre-pass found a top code, in which
+// case the tile kernel's generic byte decode runs (same results).
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void dequant_gemm_fp8_kernel(const uint16_t *__restrict__ A, const uint32_t *__restrict__ codes, uint64_t total_dwords,
+                             FmtParams fp, const float *__restrict__ sb, float *__restrict__ C, uint32_t M, uint32_t N,
+                             uint32_t K, const uint32_t *__restrict__ flags) {
+    __shared__ __attribute__((aligned(1024))) uint8_t sW0[kF8WBytes], sW1[kF8WBytes];
+    __shared__ float rowsum_lds[256];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_generic[2 * (4 * 256 * 16 + 4 * kWChunkBytes)];
+    (void)M;
+    const bool top = __any(flags[threadIdx.x & 63u] != 0);
+    if (!top) {
+        dequant_gemm_fp8_body(A, reinterpret_cast<const uint8_t *>(codes), sb, C, N, K, sW0, sW1, rowsum_lds);
+        return;
+    }
+    dequant_gemm_body<256, 1, false, false>(A, codes, total_dwords, fp, sb, C, N, K, lds_generic);
+}
+
 // ---- wave-specialised variant --------------------------------------------------------------------
 // One workgroup of 16 waves per compute unit and 256 x 128 tile.  Waves 0-7 only multiply (64 x 64 each:
 // 2 x 2 MFMA tiles, 64 accumulator registers), waves 8-11 only stage A (global -> LDS, row sums on the
@@ -697,6 +905,13 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
             dequant_gemm_kernel<BM, DEC, false><<<dim3(M / BM, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, \
                                                                                              C, M, N, K, flags);    \
     } while (0)
+    // S1E4M3 forward: the kernel built on the hardware FP8 -> bf16 conversion and transposing LDS reads (measured on
+    // the two benchmark shapes: 871 against 806 TFLOP/s for 8192 x 4096 x 1024 with the tile kernel, 921 against 873 for
+    // 8192 x 1024 x 4096 with the wave-specialised one); smaller grids take it too
+    if (dec == 2 && !trans && K >= 2 * kBK) {
+        dequant_gemm_fp8_kernel<<<dim3(M / 256, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, C, M, N, K, flags);
+        return static_cast<int>(hipGetLastError());
+    }
     // At most one 256-row tile per compute unit and a long contraction: the wave-specialised kernel (its
     // prologue and C stores are not covered by another workgroup, so it needs the long K loop to pay off).
 #ifndef OMC_GEMM_WS_MIN_K
