@@ -526,6 +526,14 @@ static const AggHeader *agg_check(const void *agg_host) {
     if (ah->group_off != ah->item_off + static_cast<uint64_t>(ah->nitems) * sizeof(PlanItem)) return nullptr;
     if (ah->total_bytes != align_up(ah->group_off + static_cast<uint64_t>(ah->ngroups) * sizeof(PlanGroup), 16))
         return nullptr;
+    if (ah->checksum != body_checksum(static_cast<const uint8_t *>(agg_host) + sizeof(AggHeader), ah->total_bytes - sizeof(AggHeader)))
+        return nullptr;
+    const PlanGroup *groups = reinterpret_cast<const PlanGroup *>(static_cast<const uint8_t *>(agg_host) + ah->group_off);
+    for (uint32_t g = 0; g < ah->ngroups; ++g) {          // what the host reads from the body: the launch groups
+        if (groups[g].kind > kGroupFp32) return nullptr;
+        if (static_cast<uint64_t>(groups[g].first_item) + groups[g].nitems > ah->nitems) return nullptr;
+        if (groups[g].kind == kGroupFull && (groups[g].bits < 2 || groups[g].bits > 32)) return nullptr;
+    }
     return ah;
 }
 
@@ -666,6 +674,7 @@ omc_status omc_aggregate_plan_build(const void *const *plans_host, uint32_t nrep
     ah->item_off = al.item_off;
     ah->group_off = al.group_off;
     ah->aux_elems = p0->aux_elems;
+    ah->checksum = body_checksum(base + sizeof(AggHeader), al.total - sizeof(AggHeader));
     return OMC_OK;
 }
 

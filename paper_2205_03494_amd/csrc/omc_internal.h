@@ -110,7 +110,7 @@ struct PlanGroup {
 
 // ---- aggregation plan blob (server side: R clients' copies of one variable set) ---------------
 constexpr uint32_t kAggMagic = 0x47414d4fu;  // "OMAG"
-constexpr uint32_t kAggVersion = 1;
+constexpr uint32_t kAggVersion = 2;
 constexpr uint32_t kMaxReplicas = 16;
 
 struct AggHeader {
@@ -120,6 +120,8 @@ struct AggHeader {
     uint64_t var_off, src_off, item_off, group_off;
     uint64_t aux_elems;
     uint64_t arena_bytes[kMaxReplicas];     // extent each client's arena must have
+    uint64_t checksum;                      // over everything after the header
+    uint64_t pad;
 };
 
 struct AggVar {

@@ -271,6 +271,8 @@ def test_aggregate_plan_checks_that_the_clients_plans_fit_together():
     assert omc._agg_mean(buf.ctypes.data, A, arenas, sizes, sbs, out + 4, 1 << 20, None) == 4
     broken = buf.copy(); broken[4] ^= 1
     assert omc._agg_mean(broken.ctypes.data, A, arenas, sizes, sbs, out, 1 << 20, None) == 8
+    broken = buf.copy(); broken[-20] ^= 1                 # a bit of the body: the checksum notices
+    assert omc._agg_mean(broken.ctypes.data, A, arenas, sizes, sbs, out, 1 << 20, None) == 8
 
 
 def test_dw_update_rejects_bad_arguments():

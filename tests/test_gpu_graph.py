@@ -30,13 +30,26 @@ def test_captured_round_replays_like_eager_launches():
     wsb = torch.tensor([0.5, 0.125], device="cuda")
     C = torch.zeros((M, N), device="cuda")
     gws = torch.empty(omc.omc_dequant_gemm_workspace_bytes(M), dtype=torch.uint8, device="cuda")
-    K2 = 2048                                        # a long contraction on a small grid: the sixteen-wave kernel
+    K2 = 2048                                        # a long contraction on a small grid (dX: the sixteen-wave kernel)
     A2 = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * K2, 1.0, 6)).view(np.int16)).cuda()
     wcodes2 = torch.randint(0, 120, (K2 * N,), dtype=torch.uint8, device="cuda")
     C2 = torch.zeros((M, N), device="cuda")
     dX2 = torch.zeros((M, K), device="cuda")
     dY2 = torch.from_numpy(synth.to_bf16_bits(synth.normal_f32(M * K2, 1.0, 7)).view(np.int16)).cuda()   # [M x 2048]
     wcodes3 = torch.randint(0, 120, (K * K2,), dtype=torch.uint8, device="cuda")                          # W [K x 2048]
+
+    # the round's end: another quantized subset for the next round, and the set as one message
+    mask2 = synth.ppq_mask(specs, 0.8, 4)
+    lay2, plan2 = build(specs, mask2, fmts)
+    rs = omc.omc_reselect_plan_build(plan, plan2)
+    arena2 = torch.zeros(lay2.arena_bytes, dtype=torch.uint8, device="cuda")
+    sb2 = torch.zeros((len(specs), 2), device="cuda")
+    rws = torch.empty(max(rs.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    msg = torch.zeros(omc.omc_transport_bytes(plan2), dtype=torch.uint8, device="cuda")
+    n1 = 50000 + 77
+    one = torch.from_numpy(synth.normal_f32(n1, 0.05, 9)).cuda()
+    one_codes = torch.zeros(omc.omc_packed_bytes(omc.fmt(3, 7), n1), dtype=torch.uint8, device="cuda")
+    one_sb = torch.zeros(2, device="cuda")
 
     def one_round(stream=None):
         # a client's round in miniature: compress the set, two training steps, a forward GEMM, decompress
@@ -47,10 +60,13 @@ def test_captured_round_replays_like_eager_launches():
         omc.omc_dequant_gemm(A2, wcodes2, omc.fmt(4, 3), wsb, C2, M, N, K2, gws, stream=stream)
         omc.omc_dequant_gemm_dx(dY2, wcodes3, omc.fmt(4, 3), wsb, dX2, M, K2, K, gws, stream=stream)
         omc.omc_decompress_set(arena, plan, sb, out, stream=stream)
+        omc.omc_reselect(rs, arena, sb, arena2, sb2, rws, stream=stream)
+        omc.omc_transport_pack(plan2, arena2, sb2, msg, stream=stream)
+        omc.omc_compress_noalloc(one, n1, omc.fmt(3, 7), True, one_codes, one_sb, stream=stream)   # allocates nothing: capturable
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (arena, sb, mom, out, C, C2, dX2)]
+        return [t.clone() for t in (arena, sb, mom, out, C, C2, dX2, arena2, sb2, msg, one_codes, one_sb)]
 
     mom.zero_()
     one_round()
@@ -65,6 +81,7 @@ def test_captured_round_replays_like_eager_launches():
     for rep in range(4):
         mom.zero_()                                  # eager work between the replays
         arena.zero_(); out.zero_(); C.zero_(); C2.zero_(); dX2.zero_(); sb.zero_()
+        arena2.zero_(); sb2.zero_(); msg.zero_(); one_codes.zero_(); one_sb.zero_()
         torch.cuda.synchronize()
         g.replay()
         got = snapshot()
