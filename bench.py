@@ -549,7 +549,7 @@ def main():
                     help="step configuration timed as the headline (default: the largest, config4)")
     ap.add_argument("--blocks", type=int, default=None, help="override the number of Conformer blocks (smaller runs)")
     ap.add_argument("--cpu-sample-blocks", type=int, default=1)
-    ap.add_argument("--cpu-iters", type=int, default=2)
+    ap.add_argument("--cpu-iters", type=int, default=4)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle leg (for profiler runs)")
     ap.add_argument("--leg-warmup-s", type=float, default=LEG_WARMUP_S,
                     help="untimed wall time before each extra leg's measurement")
