@@ -417,6 +417,10 @@ __device__ __forceinline__ void dequant_gemm_body(const uint16_t *__restrict__ A
 constexpr int kF8RowBytes = kBN * 2 + 64;
 constexpr int kF8WBytes = kBK * kF8RowBytes;               // 10 KB per stage, two stages
 
+// TRANS (dX = dY * Wbar^T; the packed variable is [N x K]): the contraction runs along the codes' contiguous direction, so
+// a thread's 16 codes are 16 consecutive k of one output column and need no transposition at all: they are stored as two
+// 16-byte k-chunks in the [k-chunk][column][16 B] layout of the tile kernel and read back with plain 16-byte loads.
+template <bool TRANS>
 __device__ __forceinline__ void dequant_gemm_fp8_body(const uint16_t *__restrict__ A, const uint8_t *__restrict__ codes,
                                                       const float *__restrict__ sb, float *__restrict__ C, uint32_t N,
                                                       uint32_t K, uint8_t *sW0, uint8_t *sW1, float *rowsum_lds) {
@@ -444,12 +448,13 @@ __device__ __forceinline__ void dequant_gemm_fp8_body(const uint16_t *__restrict
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi) r.f[ks][mi] = *reinterpret_cast<const u32x4 *>(p + a_off[mi] + 32 * ks);
     };
-    // W: thread = (k row, 16 consecutive codes)
-    const uint32_t w_row = tid >> 3, w_piece = tid & 7u;
-    const uint8_t *w_base = codes + n0;
-    const uint32_t w_off = w_row * N + 16 * w_piece;
+    // W: thread = (k row, 16 consecutive codes); TRANS: thread = (output column, which 16 of the step's 32 k)
+    const uint32_t w_row = TRANS ? (tid >> 1) : (tid >> 3), w_piece = TRANS ? (tid & 1u) : (tid & 7u);
+    const uint8_t *w_base = TRANS ? codes + static_cast<uint64_t>(n0) * K : codes + n0;
+    const uint32_t w_off = TRANS ? w_row * K + 16 * w_piece : w_row * N + 16 * w_piece;
     auto load_w = [&](uint32_t step) {
-        return *reinterpret_cast<const u32x4 *>(w_base + static_cast<uint64_t>(step) * kBK * N + w_off);
+        return *reinterpret_cast<const u32x4 *>(w_base + (TRANS ? static_cast<uint64_t>(step) * kBK
+                                                                : static_cast<uint64_t>(step) * kBK * N) + w_off);
     };
     auto store_w = [&](const u32x4 &c, uint8_t *sW) {
         uint32_t o[8];
@@ -457,6 +462,13 @@ __device__ __forceinline__ void dequant_gemm_fp8_body(const uint16_t *__restrict
         for (int d = 0; d < 4; ++d) {
             o[2 * d] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[d], 1.0f, false));
             o[2 * d + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(c[d], 1.0f, true));
+        }
+        if (TRANS) {      // k-chunks 2 piece and 2 piece + 1 of column w_row; the column slot is XORed with 8 piece so that
+                          // the two threads of a column, whose chunks lie 4 KB apart, hit different banks
+            uint8_t *dst = sW + (2 * w_piece) * kWChunkBytes + ((w_row ^ (8u * w_piece)) << 4);
+            *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};
+            *reinterpret_cast<u32x4 *>(dst + kWChunkBytes) = u32x4{o[4], o[5], o[6], o[7]};
+            return;
         }
         uint8_t *dst = sW + w_row * kF8RowBytes + w_piece * 32;
         *reinterpret_cast<u32x4 *>(dst) = u32x4{o[0], o[1], o[2], o[3]};
@@ -470,6 +482,12 @@ __device__ __forceinline__ void dequant_gemm_fp8_body(const uint16_t *__restrict
         bf16x8 b[4];
     };
     auto read_b = [&](const uint8_t *sW, int ks, BSet &f) {
+        if (TRANS) {
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni)
+                f.b[ni] = *reinterpret_cast<const bf16x8 *>(sW + (2 * ks + f_half) * kWChunkBytes + (((32u * ni + f_row) ^ (8u * ks)) << 4));
+            return;
+        }
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni) {
             const uint8_t *p = sW + fb_base + (16 * ks) * kF8RowBytes + 64 * ni;
@@ -591,6 +609,7 @@ __device__ __forceinline__ void dequant_gemm_fp8_body(const uint16_t *__restrict
 
 // S1E4M3 / bias 7, forward, 256-row tiles, K >= 64: the kernel above unless the pre-pass found a top code, in which
 // case the tile kernel's generic byte decode runs (same results).
+template <bool TRANS>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void dequant_gemm_fp8_kernel(const uint16_t *__restrict__ A, const uint32_t *__restrict__ codes, uint64_t total_dwords,
                              FmtParams fp, const float *__restrict__ sb, float *__restrict__ C, uint32_t M, uint32_t N,
@@ -601,10 +620,10 @@ void dequant_gemm_fp8_kernel(const uint16_t *__restrict__ A, const uint32_t *__r
     (void)M;
     const bool top = __any(flags[threadIdx.x & 63u] != 0);
     if (!top) {
-        dequant_gemm_fp8_body(A, reinterpret_cast<const uint8_t *>(codes), sb, C, N, K, sW0, sW1, rowsum_lds);
+        dequant_gemm_fp8_body<TRANS>(A, reinterpret_cast<const uint8_t *>(codes), sb, C, N, K, sW0, sW1, rowsum_lds);
         return;
     }
-    dequant_gemm_body<256, 1, false, false>(A, codes, total_dwords, fp, sb, C, N, K, lds_generic);
+    dequant_gemm_body<256, 1, false, TRANS>(A, codes, total_dwords, fp, sb, C, N, K, lds_generic);
 }
 
 // ---- wave-specialised variant --------------------------------------------------------------------
@@ -892,6 +911,9 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
         if (e != hipSuccess) return static_cast<int>(e);
     }
     // 256-row tiles unless they would leave fewer than two workgroups per compute unit
+#ifndef OMC_GEMM_FP8_TRANS
+#define OMC_GEMM_FP8_TRANS 1
+#endif
 #ifndef OMC_GEMM_SMALL_LIMIT
 #define OMC_GEMM_SMALL_LIMIT 512
 #endif
@@ -908,8 +930,9 @@ int launch_dequant_gemm(const uint16_t *A, const void *codes, const FmtParams &f
     // S1E4M3 forward: the kernel built on the hardware FP8 -> bf16 conversion and transposing LDS reads (measured on
     // the two benchmark shapes: 871 against 806 TFLOP/s for 8192 x 4096 x 1024 with the tile kernel, 921 against 873 for
     // 8192 x 1024 x 4096 with the wave-specialised one); smaller grids take it too
-    if (dec == 2 && !trans && K >= 2 * kBK) {
-        dequant_gemm_fp8_kernel<<<dim3(M / 256, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, C, M, N, K, flags);
+    if (dec == 2 && K >= 2 * kBK && (!trans || OMC_GEMM_FP8_TRANS)) {
+        if (trans) dequant_gemm_fp8_kernel<true><<<dim3(M / 256, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, C, M, N, K, flags);
+        else dequant_gemm_fp8_kernel<false><<<dim3(M / 256, N / kBN), dim3(256), 0, st>>>(A, c, total_dwords, fp, sb, C, M, N, K, flags);
         return static_cast<int>(hipGetLastError());
     }
     // At most one 256-row tile per compute unit and a long contraction: the wave-specialised kernel (its

@@ -14,7 +14,7 @@ from test_gpu_sets import build, ragged_specs
 pytestmark = pytest.mark.gpu
 
 
-def expected_after_reselect(specs, fmts, mask_a, lay_a, arena_a, sb_a, mask_b, lay_b):
+def expected_after_reselect(specs, fmts, mask_a, lay_a, arena_a, sb_a, mask_b, lay_b, use_pvt=True):
     """Oracle: unchanged variables keep their bytes and (s, b); a newly quantized one is the oracle's compress of
     its fp32 values; a variable that becomes fp32 is the oracle's decompress of its codes."""
     arena = np.zeros(lay_b.arena_bytes, np.uint8)
@@ -30,7 +30,7 @@ def expected_after_reselect(specs, fmts, mask_a, lay_a, arena_a, sb_a, mask_b, l
         elif not mask_a[i] and not mask_b[i]:
             arena[db:db + 4 * s.n] = arena_a[da:da + 4 * s.n]
         elif mask_b[i]:
-            p, fit = orc.compress(arena_a[da:da + 4 * s.n].view(np.float32).copy(), of)
+            p, fit = orc.compress(arena_a[da:da + 4 * s.n].view(np.float32).copy(), of, use_pvt)
             arena[db:db + nb] = p
             sb[i] = fit
         else:
@@ -39,14 +39,14 @@ def expected_after_reselect(specs, fmts, mask_a, lay_a, arena_a, sb_a, mask_b, l
     return arena, sb
 
 
-def run_reselect(specs, fmts, mask_a, mask_b, steps=2, kind=1, lr=0.05):
-    vs = VarSet(specs, mask_a, fmts, seed=11)
+def run_reselect(specs, fmts, mask_a, mask_b, steps=2, kind=1, lr=0.05, use_pvt=True):
+    vs = VarSet(specs, mask_a, fmts, seed=11, use_pvt=use_pvt)
     for t in range(1, steps + 1):                          # a state that training has touched, not a fresh compress
         g = synth.gradients(vs.lay, 0.02, 600 + t)
         vs.step_oracle(g, kind, lr, t)
         vs.step_gpu(to_dev(g), kind, lr, t)
     assert vs.compare(kind) == 0
-    lay_b, plan_b = build(specs, mask_b, fmts)
+    lay_b, plan_b = build(specs, mask_b, fmts, use_pvt=use_pvt)
     rs = omc.omc_reselect_plan_build(vs.plan, plan_b)
     arena_b = torch.full((lay_b.arena_bytes + 64,), 0xA5, dtype=torch.uint8, device="cuda")
     sb_b = torch.full((len(specs), 2), 7.0, device="cuda")
@@ -56,7 +56,7 @@ def run_reselect(specs, fmts, mask_a, mask_b, steps=2, kind=1, lr=0.05):
     torch.cuda.synchronize()
     assert torch.equal(before, vs.g_arena), "the old arena is read only"
     want_arena, want_sb = expected_after_reselect(specs, fmts, np.asarray(mask_a), vs.lay, vs.o_arena, vs.o_sb,
-                                                  np.asarray(mask_b), lay_b)
+                                                  np.asarray(mask_b), lay_b, use_pvt)
     got = arena_b.cpu().numpy()
     assert np.all(got[lay_b.arena_bytes:] == 0xA5), "wrote past the new arena"
     for i, s in enumerate(specs):                          # per variable, so that a failure names it
@@ -115,6 +115,15 @@ def test_reselect_ragged_sizes_and_degenerate_selections(case):
         mask_a = rng.random(nv) < 0.5
         mask_b = mask_a.copy()
     run_reselect(specs, fmts, mask_a, mask_b, steps=1, kind=0)
+
+
+def test_reselect_without_the_transformation():
+    """OMC_VAR_NO_PVT sets (the ablation's switch): newly quantized variables get (1, 0), decompression ignores nothing."""
+    specs = ragged_specs()
+    rng = np.random.default_rng(8)
+    mask_a, mask_b = rng.random(len(specs)) < 0.5, rng.random(len(specs)) < 0.5
+    _, _, _, _, sb_b, _, _ = run_reselect(specs, [(3, 7)] * len(specs), mask_a, mask_b, steps=1, kind=0, use_pvt=False)
+    assert np.all(sb_b.cpu().numpy() == np.array([1.0, 0.0], np.float32))
 
 
 def test_reselect_refuses_what_it_cannot_do():

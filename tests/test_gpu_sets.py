@@ -11,12 +11,12 @@ from gpu_util import bits_equal, to_dev
 pytestmark = pytest.mark.gpu
 
 
-def build(specs, mask, fmts):
+def build(specs, mask, fmts, use_pvt=True):
     gfs = [omc.fmt(*fmts[i]) if mask[i] else None for i in range(len(specs))]
     sizes = iter([omc.omc_packed_bytes(gfs[i], specs[i].n) for i in range(len(specs)) if mask[i]])
     lay = synth.make_layout(specs, mask, lambda n: next(sizes))
     table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gfs[i],
-                  quantized=bool(mask[i])) for i, s in enumerate(specs)]
+                  quantized=bool(mask[i]), use_pvt=use_pvt) for i, s in enumerate(specs)]
     return lay, omc.omc_plan_build(omc.make_var_table(table))
 
 
