@@ -267,6 +267,74 @@ def test_benchmark_set_whole_set_conversions_and_server_aggregation():
     assert torch.isfinite(out).all()
 
 
+def test_benchmark_set_reselection_and_transport_message():
+    """Config-2 sized set with the paper's 90 % partial quantization (S1E3M7), as bench.py's round_boundary leg runs it:
+    omc_reselect to another seeded 90 % subset, then omc_transport_pack of the result.  Every moved variable is compared
+    byte for byte on the GPU; sampled converted variables against the oracle's compress / decompress; the message's
+    payload against the arena it was packed from."""
+    specs = synth.conformer_varset(512, 17, 2048, 32, frontend=True)
+    fmt = (3, 7)
+    of, gf = orc.Format(*fmt), omc.fmt(*fmt)
+    plans, lays, masks = [], [], []
+    for seed in (1, 2):
+        mask = synth.ppq_mask(specs, 0.9, seed)
+        lay = synth.make_layout(specs, mask, lambda n: omc.omc_packed_bytes(gf, n))
+        table = [dict(data_offset=int(lay.data_offset[i]), aux_offset=int(lay.aux_offset[i]), n=s.n, fmt=gf,
+                      quantized=bool(mask[i])) for i, s in enumerate(specs)]
+        plans.append(omc.omc_plan_build(omc.make_var_table(table)))
+        lays.append(lay); masks.append(mask)
+    vals = _device_values(specs, lays[0], 7)
+    arena_a = torch.zeros(lays[0].arena_bytes, dtype=torch.uint8, device="cuda")
+    sb_a = torch.zeros((len(specs), 2), device="cuda")
+    ws = torch.empty(max(plans[0].workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    omc.omc_compress_set(vals, plans[0], arena_a, sb_a, ws)
+    del vals
+    rs = omc.omc_reselect_plan_build(plans[0], plans[1])
+    arena_b = torch.zeros(lays[1].arena_bytes, dtype=torch.uint8, device="cuda")
+    sb_b = torch.full((len(specs), 2), 7.0, device="cuda")
+    ws2 = torch.empty(max(rs.workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    omc.omc_reselect(rs, arena_a, sb_a, arena_b, sb_b, ws2)
+    torch.cuda.synchronize()
+    to_q = [i for i in range(len(specs)) if not masks[0][i] and masks[1][i]]
+    to_f = [i for i in range(len(specs)) if masks[0][i] and not masks[1][i]]
+    assert to_q and to_f
+    checked, budget = 0, 9_000_000
+    for i, s in enumerate(specs):
+        da, db = int(lays[0].data_offset[i]), int(lays[1].data_offset[i])
+        nb = omc.omc_packed_bytes(gf, s.n)
+        if masks[0][i] == masks[1][i]:                       # moved as bytes: compared in full, on the GPU
+            n_bytes = nb if masks[0][i] else 4 * s.n
+            assert torch.equal(arena_b[db:db + n_bytes], arena_a[da:da + n_bytes]), f"moved: {s.name}"
+            if masks[0][i]:
+                assert torch.equal(sb_b[i].view(torch.int32), sb_a[i].view(torch.int32))
+        elif budget >= s.n:                                   # converted: the oracle on as many as the budget allows
+            budget -= s.n
+            checked += 1
+            if masks[1][i]:
+                p, fit = orc.compress(arena_a[da:da + 4 * s.n].cpu().numpy().view(np.float32).copy(), of)
+                assert np.array_equal(arena_b[db:db + nb].cpu().numpy(), p), f"to codes: {s.name}"
+                assert bits_equal(sb_b[i].cpu().numpy(), fit)
+            else:
+                x = orc.decompress(arena_a[da:da + nb].cpu().numpy().copy(), s.n, of, sb_a[i].cpu().numpy())
+                assert bits_equal(arena_b[db:db + 4 * s.n].cpu().numpy().view(np.float32), x), f"to fp32: {s.name}"
+    assert checked >= 4
+    # the message of the new selection: payload = the arena, variable by variable
+    nbytes = omc.omc_transport_bytes(plans[1])
+    msg = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    omc.omc_transport_pack(plans[1], arena_b, sb_b, msg)
+    torch.cuda.synchronize()
+    meta = omc.omc_transport_meta_bytes(len(specs))
+    table, nvars, sb_off, arena_off, arena_bytes, _ = omc.omc_transport_open(msg[:meta].cpu().numpy(), nbytes)
+    assert nvars == len(specs)
+    for i, s in enumerate(specs):
+        db, dm = int(lays[1].data_offset[i]), arena_off + int(table[i].data_offset)
+        n_bytes = omc.omc_packed_bytes(gf, s.n) if masks[1][i] else 4 * s.n
+        assert torch.equal(msg[dm:dm + n_bytes], arena_b[db:db + n_bytes]), f"message payload: {s.name}"
+    sbm = msg[sb_off:sb_off + 8 * nvars].view(torch.float32).view(nvars, 2)
+    q = torch.from_numpy(np.asarray(masks[1])).cuda()
+    assert torch.equal(sbm[q].view(torch.int32), sb_b[q].view(torch.int32))
+
+
 def test_config2_every_variable_free_running():
     """BASELINE config 2 on every one of its 599 variables (not a sample): the whole 115 M-parameter set stepped
     twenty times on both sides without resynchronising; arena and (s, b) table identical at the end.  (Run
